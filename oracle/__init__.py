@@ -1,0 +1,174 @@
+"""CPU oracle (test infrastructure only): ctypes binding of asd_oracle.c.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this package.  It shares no code with the HIP engine.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "asd_oracle.c")
+_LIB = os.path.join(_HERE, "liborc.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc -O2 (OpenMP over independent output elements)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "max_seq", "dtype")] + \
+               [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
+
+
+class _GenParams(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_double), ("m", ctypes.c_int32), ("n", ctypes.c_int32),
+                ("use_cs", ctypes.c_int32), ("draft_len", ctypes.c_int32), ("mask_mode", ctypes.c_int32),
+                ("fixed_mask", ctypes.c_void_p)]
+
+
+class _GenStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("cycles", "drafted", "accepted", "emitted")]
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int32
+        L.orc_create.restype = vp
+        L.orc_create.argtypes = [ctypes.POINTER(_Config)]
+        L.orc_destroy.argtypes = [vp]
+        L.orc_set_weight.argtypes = [vp, i32, i32, vp]
+        L.orc_reset.argtypes = [vp]
+        L.orc_truncate.argtypes = [vp, i32]
+        L.orc_kv_len.argtypes = [vp]
+        L.orc_forward.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
+        L.orc_acs.argtypes = [vp, i32, i32, vp]
+        L.orc_cosine.restype = ctypes.c_double
+        L.orc_cosine.argtypes = [vp, vp, i32]
+        L.orc_admg.argtypes = [vp, i32, ctypes.c_double, i32, i32, i32, vp]
+        L.orc_generate_plain.argtypes = [vp, vp, i32, i32, vp]
+        L.orc_generate_spec.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_GenParams), vp,
+                                        ctypes.POINTER(_GenStats), vp, vp]
+        _lib = L
+    return _lib
+
+
+def cosine(x, y) -> float:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    y = np.ascontiguousarray(y, dtype=np.float64)
+    return float(_L().orc_cosine(x.ctypes.data, y.ctypes.data, x.size))
+
+
+def admg(C_attn, alpha: float, m: int, n: int, use_cs: bool = True) -> np.ndarray:
+    """Algorithm 1: skip mask [2L] (index 2l attention, 2l+1 MLP, 0-based l; 1 = removed)."""
+    C = np.ascontiguousarray(C_attn, dtype=np.float64)
+    mask = np.zeros(2 * C.size, dtype=np.uint8)
+    rc = _L().orc_admg(C.ctypes.data, C.size, alpha, m, n, int(use_cs), mask.ctypes.data)
+    if rc:
+        raise ValueError("orc_admg: invalid argument")
+    return mask
+
+
+def acs(cos_rows) -> np.ndarray:
+    cr = np.ascontiguousarray(cos_rows, dtype=np.float64)
+    out = np.empty(cr.shape[1], dtype=np.float64)
+    _L().orc_acs(cr.ctypes.data, cr.shape[0], cr.shape[1], out.ctypes.data)
+    return out
+
+
+class Oracle:
+    """One model instance: weights in storage type, unrounded double KV cache."""
+
+    def __init__(self, shape, max_seq: int):
+        self.shape = shape
+        self.max_seq = max_seq
+        c = _Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                    shape.d_ffn, shape.vocab, max_seq, shape.dtype, shape.rms_eps, shape.rope_theta)
+        self._h = _L().orc_create(ctypes.byref(c))
+        if not self._h:
+            raise ValueError("orc_create: invalid configuration")
+
+    def close(self):
+        if self._h:
+            _L().orc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def set_weight(self, tensor: int, layer: int, arr: np.ndarray):
+        a = np.ascontiguousarray(arr)
+        if _L().orc_set_weight(self._h, tensor, layer, a.ctypes.data):
+            raise ValueError("orc_set_weight failed")
+
+    def load(self, tensors):
+        for t, l, a in tensors:
+            self.set_weight(t, l, a)
+        return self
+
+    def reset(self):
+        _L().orc_reset(self._h)
+
+    def truncate(self, n: int):
+        if _L().orc_truncate(self._h, n):
+            raise ValueError("orc_truncate: bad length")
+
+    @property
+    def kv_len(self) -> int:
+        return _L().orc_kv_len(self._h)
+
+    def forward(self, tokens, pos0: int, skip=None, commit: bool = True, want_logits=True, want_hidden=False):
+        """Returns dict(logits [n,V], cos_rows [n,2L], cos [2L] mean over rows, argmax [n], hidden [n,d])."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        n, s = tok.size, self.shape
+        logits = np.empty((n, s.vocab), dtype=np.float64) if want_logits else None
+        cos_rows = np.empty((n, 2 * s.n_layers), dtype=np.float64)
+        am = np.empty(n, dtype=np.int32)
+        hid = np.empty((n, s.d_model), dtype=np.float64) if want_hidden else None
+        sk = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
+        rc = _L().orc_forward(self._h, tok.ctypes.data, n, pos0, None if sk is None else sk.ctypes.data,
+                              int(commit), None if logits is None else logits.ctypes.data,
+                              cos_rows.ctypes.data, am.ctypes.data, None if hid is None else hid.ctypes.data)
+        if rc:
+            raise ValueError(f"orc_forward failed ({rc})")
+        return {"logits": logits, "cos_rows": cos_rows, "cos": acs(cos_rows), "argmax": am, "hidden": hid}
+
+    def generate_plain(self, prompt, n_new: int) -> np.ndarray:
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.empty(n_new, dtype=np.int32)
+        rc = _L().orc_generate_plain(self._h, p.ctypes.data, p.size, n_new, out.ctypes.data)
+        if rc:
+            raise ValueError(f"orc_generate_plain failed ({rc})")
+        return out
+
+    def generate_spec(self, prompt, n_new: int, draft_len: int, alpha=0.985, m=3, n=2, use_cs=True,
+                      fixed_mask=None):
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.empty(n_new, dtype=np.int32)
+        fm = None if fixed_mask is None else np.ascontiguousarray(fixed_mask, dtype=np.uint8)
+        gp = _GenParams(alpha, m, n, int(use_cs), draft_len, 0 if fm is None else 1,
+                        None if fm is None else fm.ctypes.data)
+        st = _GenStats()
+        L2 = 2 * self.shape.n_layers
+        mask = np.zeros(L2, dtype=np.uint8)
+        C = np.zeros(L2, dtype=np.float64)
+        rc = _L().orc_generate_spec(self._h, p.ctypes.data, p.size, n_new, ctypes.byref(gp), out.ctypes.data,
+                                    ctypes.byref(st), mask.ctypes.data, C.ctypes.data)
+        if rc:
+            raise ValueError(f"orc_generate_spec failed ({rc})")
+        stats = {k: int(getattr(st, k)) for k in ("cycles", "drafted", "accepted", "emitted")}
+        return out, stats, mask, C

@@ -1,0 +1,461 @@
+/*
+ * CPU oracle for adaptive self-speculative decoding (ASD): TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, row-at-a-time double-precision implementation of
+ *   - the Llama-2 style decoder the paper runs on (Section 4 names the model
+ *     family; the decoder's definition is the public Llama-2 one),
+ *   - the per-sublayer cosine similarity between the hidden state entering and
+ *     leaving a sublayer, and its average over the rows of a call
+ *     (Section 3.2, the equation defining C_l),
+ *   - the Adaptive Draft Model Generator (Algorithm 1),
+ *   - plain greedy decoding and greedy speculative decoding with a
+ *     layer-skipping draft model (Section 1, the draft / verify / replace-the-
+ *     first-rejected-token protocol).
+ *
+ * It shares no code with the HIP engine and must never be used by it: only the
+ * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
+ * Weights are kept in their storage type (fp32, or bf16 bit patterns) and are
+ * widened exactly to double on use; every reduction is a sequential double
+ * sum, and nothing is rounded in between, so multi-row calls equal one-row
+ * calls bit for bit.  OpenMP only distributes independent output elements.
+ *
+ * Parity status: decoder, cosine, ADMG and the speculative loop are pinned by
+ * the CPU tests (independent Llama implementation, closed forms, invariants,
+ * brute force).  The paper's own speed-ups and ACS statistics need trained
+ * weights and datasets: parity unpinned for those.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum {
+    T_EMBED = 0, T_ATTN_NORM = 1, T_WQ = 2, T_WK = 3, T_WV = 4, T_WO = 5,
+    T_MLP_NORM = 6, T_WG = 7, T_WU = 8, T_WD = 9, T_FINAL_NORM = 10, T_LM_HEAD = 11
+};
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq, dtype;
+    double rms_eps, rope_theta;
+} orc_config;
+
+typedef struct {
+    void *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+    double *g_attn, *g_mlp;
+    double *kc, *vc;            /* [max_seq][n_kv_heads*head_dim], unrounded */
+} orc_layer;
+
+typedef struct {
+    orc_config c;
+    void *embed, *lm_head;
+    double* g_final;
+    orc_layer* layer;
+    int32_t kv_len;
+} orc_model;
+
+typedef struct {
+    double alpha;               /* CS threshold                              */
+    int32_t m, n;               /* rule 1 period (0 = off), rule 2 tail (0 = off) */
+    int32_t use_cs;             /* 0 disables CS thresholding                */
+    int32_t draft_len;          /* k >= 0                                    */
+    int32_t mask_mode;          /* 0 = ADMG from the prompt's ACS, 1 = fixed */
+    const uint8_t* fixed_mask;  /* [2L], 1 = skip, used when mask_mode == 1  */
+} orc_gen_params;
+
+typedef struct {
+    int64_t cycles, drafted, accepted, emitted;
+} orc_gen_stats;
+
+/* ------------------------------------------------------------------ storage */
+
+static size_t elem_size(int dtype) { return dtype == ORC_BF16 ? 2 : 4; }
+
+static inline double wget(const void* w, int dtype, size_t i) {
+    if (dtype == ORC_BF16) {
+        uint32_t u = (uint32_t)((const uint16_t*)w)[i] << 16;
+        float f; memcpy(&f, &u, 4);
+        return (double)f;
+    }
+    return (double)((const float*)w)[i];
+}
+
+static void tensor_dims(const orc_config* c, int t, size_t* rows, size_t* cols) {
+    size_t qd = (size_t)c->n_heads * c->head_dim, kd = (size_t)c->n_kv_heads * c->head_dim;
+    switch (t) {
+        case T_EMBED: case T_LM_HEAD: *rows = c->vocab; *cols = c->d_model; break;
+        case T_WQ: *rows = qd; *cols = c->d_model; break;
+        case T_WK: case T_WV: *rows = kd; *cols = c->d_model; break;
+        case T_WO: *rows = c->d_model; *cols = qd; break;
+        case T_WG: case T_WU: *rows = c->d_ffn; *cols = c->d_model; break;
+        case T_WD: *rows = c->d_model; *cols = c->d_ffn; break;
+        default: *rows = 1; *cols = c->d_model; break;   /* norm gains */
+    }
+}
+
+orc_model* orc_create(const orc_config* c) {
+    if (!c || c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 ||
+        c->n_heads % c->n_kv_heads || c->head_dim < 2 || c->head_dim % 2 || c->d_ffn < 1 ||
+        c->vocab < 1 || c->max_seq < 1 || (c->dtype != ORC_F32 && c->dtype != ORC_BF16))
+        return NULL;
+    orc_model* M = (orc_model*)calloc(1, sizeof *M);
+    M->c = *c;
+    M->layer = (orc_layer*)calloc((size_t)c->n_layers, sizeof(orc_layer));
+    size_t kvd = (size_t)c->n_kv_heads * c->head_dim;
+    for (int l = 0; l < c->n_layers; ++l) {
+        M->layer[l].kc = (double*)calloc((size_t)c->max_seq * kvd, sizeof(double));
+        M->layer[l].vc = (double*)calloc((size_t)c->max_seq * kvd, sizeof(double));
+    }
+    return M;
+}
+
+void orc_destroy(orc_model* M) {
+    if (!M) return;
+    for (int l = 0; l < M->c.n_layers; ++l) {
+        orc_layer* y = &M->layer[l];
+        free(y->wq); free(y->wk); free(y->wv); free(y->wo); free(y->wg); free(y->wu); free(y->wd);
+        free(y->g_attn); free(y->g_mlp); free(y->kc); free(y->vc);
+    }
+    free(M->layer); free(M->embed); free(M->lm_head); free(M->g_final); free(M);
+}
+
+/* Matrices arrive in storage type (row-major [rows][cols]); norm gains as fp32. */
+int orc_set_weight(orc_model* M, int32_t tensor, int32_t layer, const void* data) {
+    if (!M || !data || tensor < 0 || tensor > T_LM_HEAD) return -1;
+    int global = (tensor == T_EMBED || tensor == T_LM_HEAD || tensor == T_FINAL_NORM);
+    if (!global && (layer < 0 || layer >= M->c.n_layers)) return -1;
+    size_t r, k; tensor_dims(&M->c, tensor, &r, &k);
+    if (tensor == T_ATTN_NORM || tensor == T_MLP_NORM || tensor == T_FINAL_NORM) {
+        double* g = (double*)malloc(k * sizeof(double));
+        for (size_t i = 0; i < k; ++i) g[i] = (double)((const float*)data)[i];
+        double** slot = tensor == T_FINAL_NORM ? &M->g_final
+                      : tensor == T_ATTN_NORM ? &M->layer[layer].g_attn : &M->layer[layer].g_mlp;
+        free(*slot); *slot = g;
+        return 0;
+    }
+    size_t bytes = r * k * elem_size(M->c.dtype);
+    void* w = malloc(bytes);
+    memcpy(w, data, bytes);
+    void** slot;
+    orc_layer* y = global ? NULL : &M->layer[layer];
+    switch (tensor) {
+        case T_EMBED: slot = &M->embed; break;
+        case T_LM_HEAD: slot = &M->lm_head; break;
+        case T_WQ: slot = &y->wq; break;
+        case T_WK: slot = &y->wk; break;
+        case T_WV: slot = &y->wv; break;
+        case T_WO: slot = &y->wo; break;
+        case T_WG: slot = &y->wg; break;
+        case T_WU: slot = &y->wu; break;
+        default:   slot = &y->wd; break;
+    }
+    free(*slot); *slot = w;
+    return 0;
+}
+
+static int weights_complete(const orc_model* M) {
+    if (!M->embed || !M->lm_head || !M->g_final) return 0;
+    for (int l = 0; l < M->c.n_layers; ++l) {
+        const orc_layer* y = &M->layer[l];
+        if (!y->wq || !y->wk || !y->wv || !y->wo || !y->wg || !y->wu || !y->wd || !y->g_attn || !y->g_mlp)
+            return 0;
+    }
+    return 1;
+}
+
+void orc_reset(orc_model* M) { M->kv_len = 0; }
+int32_t orc_kv_len(const orc_model* M) { return M->kv_len; }
+int orc_truncate(orc_model* M, int32_t len) {
+    if (len < 0 || len > M->kv_len) return -1;
+    M->kv_len = len; return 0;
+}
+
+/* ------------------------------------------------------------- sublayer math */
+
+/* y[n] = sum_k W[n][k] x[k], sequential double sum over k. */
+static void matvec(const void* W, int dtype, size_t N, size_t K, const double* x, double* y) {
+    #pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < (int64_t)N; ++n) {
+        double acc = 0.0;
+        size_t base = (size_t)n * K;
+        for (size_t k = 0; k < K; ++k) acc += wget(W, dtype, base + k) * x[k];
+        y[n] = acc;
+    }
+}
+
+/* RMSNorm: x / sqrt(mean(x^2) + eps), times the gain. */
+static void rmsnorm(const double* x, const double* g, size_t d, double eps, double* out) {
+    double ss = 0.0;
+    for (size_t i = 0; i < d; ++i) ss += x[i] * x[i];
+    double r = 1.0 / sqrt(ss / (double)d + eps);
+    for (size_t i = 0; i < d; ++i) out[i] = x[i] * r * g[i];
+}
+
+/* Rotary embedding, half-split pairing (i, i + h/2), angle pos * theta^(-2i/h). */
+static void rope(double* v, int h, int pos, double theta) {
+    int half = h / 2;
+    for (int i = 0; i < half; ++i) {
+        double ang = (double)pos * pow(theta, -2.0 * (double)i / (double)h);
+        double c = cos(ang), s = sin(ang), a = v[i], b = v[i + half];
+        v[i] = a * c - b * s;
+        v[i + half] = b * c + a * s;
+    }
+}
+
+/*
+ * Cosine similarity of one row: <x,y> / (||x|| ||y||)  (Section 3.2, the summand of C_l).
+ * A norm below 1e-8 is replaced by 1e-8 and the result is clamped to [-1, 1], the
+ * range Algorithm 1 states for C.
+ */
+double orc_cosine(const double* x, const double* y, int32_t n) {
+    double xy = 0.0, xx = 0.0, yy = 0.0;
+    for (int i = 0; i < n; ++i) { xy += x[i] * y[i]; xx += x[i] * x[i]; yy += y[i] * y[i]; }
+    /* ||x|| ||y|| = sqrt(xx * yy); written this way cos(x, x) is exactly 1. */
+    if (xx < 1e-16) xx = 1e-16;
+    if (yy < 1e-16) yy = 1e-16;
+    double c = xy / sqrt(xx * yy);
+    return c > 1.0 ? 1.0 : (c < -1.0 ? -1.0 : c);
+}
+
+static double silu(double z) { return z / (1.0 + exp(-z)); }
+
+/*
+ * One token through the decoder at position pos.  skip[2l] drops the attention
+ * sublayer of layer l, skip[2l+1] its MLP (the draft model is the full model
+ * minus those sublayers, Section 1 and Algorithm 1's output sets); a dropped
+ * sublayer passes the hidden state through, so its cosine is exactly 1.
+ * X = hidden state entering the sublayer, Y = X + sublayer(norm(X)).
+ */
+static void decoder_row(orc_model* M, int tok, int pos, const uint8_t* skip,
+                        double* logits, double* cosr, double* hidden_out) {
+    const orc_config* c = &M->c;
+    const int d = c->d_model, h = c->head_dim, nh = c->n_heads, nkv = c->n_kv_heads, f = c->d_ffn;
+    const int qd = nh * h, kd = nkv * h, group = nh / nkv, dt = c->dtype;
+    double* x = (double*)malloc(sizeof(double) * d);
+    double* y = (double*)malloc(sizeof(double) * d);
+    double* xn = (double*)malloc(sizeof(double) * d);
+    double* q = (double*)malloc(sizeof(double) * qd);
+    double* o = (double*)malloc(sizeof(double) * qd);
+    double* gate = (double*)malloc(sizeof(double) * f);
+    double* up = (double*)malloc(sizeof(double) * f);
+    double* delta = (double*)malloc(sizeof(double) * d);
+    double* p = (double*)malloc(sizeof(double) * (size_t)(pos + 1));
+
+    for (int i = 0; i < d; ++i) x[i] = wget(M->embed, dt, (size_t)tok * d + i);
+
+    for (int l = 0; l < c->n_layers; ++l) {
+        orc_layer* L = &M->layer[l];
+        if (!(skip && skip[2 * l])) {
+            rmsnorm(x, L->g_attn, d, c->rms_eps, xn);
+            double* kr = L->kc + (size_t)pos * kd;
+            double* vr = L->vc + (size_t)pos * kd;
+            matvec(L->wq, dt, qd, d, xn, q);
+            matvec(L->wk, dt, kd, d, xn, kr);
+            matvec(L->wv, dt, kd, d, xn, vr);
+            for (int a = 0; a < nh; ++a) rope(q + a * h, h, pos, c->rope_theta);
+            for (int a = 0; a < nkv; ++a) rope(kr + a * h, h, pos, c->rope_theta);
+            double scale = 1.0 / sqrt((double)h);
+            for (int a = 0; a < nh; ++a) {
+                int kvh = a / group;
+                double mx = -INFINITY;
+                for (int t = 0; t <= pos; ++t) {
+                    const double* kt = L->kc + (size_t)t * kd + kvh * h;
+                    double s = 0.0;
+                    for (int i = 0; i < h; ++i) s += q[a * h + i] * kt[i];
+                    p[t] = s * scale;
+                    if (p[t] > mx) mx = p[t];
+                }
+                double z = 0.0;
+                for (int t = 0; t <= pos; ++t) { p[t] = exp(p[t] - mx); z += p[t]; }
+                for (int i = 0; i < h; ++i) {
+                    double acc = 0.0;
+                    for (int t = 0; t <= pos; ++t) acc += p[t] * L->vc[(size_t)t * kd + kvh * h + i];
+                    o[a * h + i] = acc / z;
+                }
+            }
+            matvec(L->wo, dt, d, qd, o, delta);
+            for (int i = 0; i < d; ++i) y[i] = x[i] + delta[i];
+            cosr[2 * l] = orc_cosine(x, y, d);
+            memcpy(x, y, sizeof(double) * d);
+        } else {
+            cosr[2 * l] = 1.0;
+        }
+        if (!(skip && skip[2 * l + 1])) {
+            rmsnorm(x, L->g_mlp, d, c->rms_eps, xn);
+            matvec(L->wg, dt, f, d, xn, gate);
+            matvec(L->wu, dt, f, d, xn, up);
+            for (int i = 0; i < f; ++i) gate[i] = silu(gate[i]) * up[i];
+            matvec(L->wd, dt, d, f, gate, delta);
+            for (int i = 0; i < d; ++i) y[i] = x[i] + delta[i];
+            cosr[2 * l + 1] = orc_cosine(x, y, d);
+            memcpy(x, y, sizeof(double) * d);
+        } else {
+            cosr[2 * l + 1] = 1.0;
+        }
+    }
+    if (hidden_out) memcpy(hidden_out, x, sizeof(double) * d);
+    if (logits) {
+        rmsnorm(x, M->g_final, d, c->rms_eps, xn);
+        matvec(M->lm_head, dt, c->vocab, d, xn, logits);
+    }
+    free(x); free(y); free(xn); free(q); free(o); free(gate); free(up); free(delta); free(p);
+}
+
+/* Greedy choice: largest logit, lowest index on ties. */
+static int32_t argmax_row(const double* v, int n) {
+    int32_t best = 0;
+    for (int i = 1; i < n; ++i) if (v[i] > v[best]) best = i;
+    return best;
+}
+
+/*
+ * Run n_rows tokens at positions pos0 .. pos0+n_rows-1 (pos0 must equal the
+ * cache length).  Outputs (any may be NULL): logits [n_rows][vocab],
+ * cos_rows [n_rows][2L] (index 2l attention, 2l+1 MLP), argmax [n_rows],
+ * hidden [n_rows][d] (hidden state entering the final norm).
+ * commit != 0 leaves the cache length at pos0 + n_rows, else at pos0.
+ */
+int orc_forward(orc_model* M, const int32_t* tokens, int32_t n_rows, int32_t pos0,
+                const uint8_t* skip, int32_t commit,
+                double* logits, double* cos_rows, int32_t* argmax, double* hidden) {
+    if (!M || !tokens || n_rows < 1 || !weights_complete(M)) return -1;
+    if (pos0 != M->kv_len || pos0 + n_rows > M->c.max_seq) return -2;
+    for (int i = 0; i < n_rows; ++i) if (tokens[i] < 0 || tokens[i] >= M->c.vocab) return -1;
+    const int V = M->c.vocab, L2 = 2 * M->c.n_layers;
+    double* lrow = (double*)malloc(sizeof(double) * V);
+    double* crow = (double*)malloc(sizeof(double) * L2);
+    for (int i = 0; i < n_rows; ++i) {
+        int need_logits = logits || argmax;
+        decoder_row(M, tokens[i], pos0 + i, skip, need_logits ? lrow : NULL, crow,
+                    hidden ? hidden + (size_t)i * M->c.d_model : NULL);
+        if (logits) memcpy(logits + (size_t)i * V, lrow, sizeof(double) * V);
+        if (argmax) argmax[i] = argmax_row(lrow, V);
+        if (cos_rows) memcpy(cos_rows + (size_t)i * L2, crow, sizeof(double) * L2);
+    }
+    free(lrow); free(crow);
+    M->kv_len = commit ? pos0 + n_rows : pos0;
+    return 0;
+}
+
+/* Average cosine similarity over the rows of a call: C_j = (1/S) sum_s cos_rows[s][j]. */
+void orc_acs(const double* cos_rows, int32_t n_rows, int32_t n_sub, double* C) {
+    for (int j = 0; j < n_sub; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < n_rows; ++i) s += cos_rows[(size_t)i * n_sub + j];
+        C[j] = s / (double)n_rows;
+    }
+}
+
+/*
+ * Algorithm 1 (ADMG).  C holds the L attention-sublayer ACS values; layers are
+ * numbered 1..L inside this function exactly as in the paper.
+ *   remove_ATTN = { l : C_l >= alpha, l <= L - n }
+ *   remove_MLP  = { l : l = j*m for a positive integer j, l <= L - n }
+ *   remove_ATTN = remove_ATTN U remove_MLP
+ * use_cs == 0 leaves the first set empty and m == 0 the second (the ablation's
+ * rule subsets); n == 0 protects no layer.  mask[2(l-1)] = 1 iff l in
+ * remove_ATTN, mask[2(l-1)+1] = 1 iff l in remove_MLP.
+ */
+int orc_admg(const double* C, int32_t L, double alpha, int32_t m, int32_t n, int32_t use_cs,
+             uint8_t* mask) {
+    if (!C || !mask || L < 1 || m < 0 || n < 0) return -1;
+    memset(mask, 0, (size_t)(2 * L));
+    for (int l = 1; l <= L; ++l) {
+        int in_attn = use_cs && C[l - 1] >= alpha && l <= L - n;
+        int in_mlp = m > 0 && l % m == 0 && l <= L - n;
+        mask[2 * (l - 1) + 1] = (uint8_t)in_mlp;
+        mask[2 * (l - 1)] = (uint8_t)(in_attn || in_mlp);
+    }
+    return 0;
+}
+
+/* Prefill all prompt rows with the full model; first token and the prompt's ACS. */
+static int prefill(orc_model* M, const int32_t* prompt, int32_t P, int32_t* t1, double* C /*[2L] or NULL*/) {
+    const int L2 = 2 * M->c.n_layers;
+    double* cr = (double*)malloc(sizeof(double) * (size_t)P * L2);
+    int32_t* am = (int32_t*)malloc(sizeof(int32_t) * P);
+    M->kv_len = 0;
+    int rc = orc_forward(M, prompt, P, 0, NULL, 1, NULL, cr, am, NULL);
+    if (rc == 0) { *t1 = am[P - 1]; if (C) orc_acs(cr, P, L2, C); }
+    free(cr); free(am);
+    return rc;
+}
+
+/* Plain greedy autoregressive decoding: t_{i+1} = argmax of the full model's next-token logits. */
+int orc_generate_plain(orc_model* M, const int32_t* prompt, int32_t P, int32_t N, int32_t* out) {
+    if (!M || !prompt || !out || P < 1 || N < 1 || P + N > M->c.max_seq) return -1;
+    int32_t t;
+    int rc = prefill(M, prompt, P, &t, NULL);
+    if (rc) return rc;
+    out[0] = t;
+    for (int i = 1; i < N; ++i) {
+        rc = orc_forward(M, &t, 1, P + i - 1, NULL, 1, NULL, NULL, &t, NULL);
+        if (rc) return rc;
+        out[i] = t;
+    }
+    return 0;
+}
+
+/*
+ * Greedy self-speculative decoding (Section 1; Section 3.2 for how D is chosen):
+ * after the prompt pass produced t_1 and the ACS, build the skip mask once,
+ * then repeat: draft k tokens one at a time with the masked model, verify
+ * [last, drafts] in one pass of the full model, keep the longest prefix of
+ * drafts that equals the full model's choices and replace the first rejected
+ * one by the full model's token (when none is rejected the full model's extra
+ * token is emitted too).  The last cycle drafts only as many tokens as can
+ * still be emitted.  mask_used [2L] and C_prompt [2L] may be NULL.
+ */
+int orc_generate_spec(orc_model* M, const int32_t* prompt, int32_t P, int32_t N,
+                      const orc_gen_params* gp, int32_t* out, orc_gen_stats* st,
+                      uint8_t* mask_used, double* C_prompt) {
+    if (!M || !prompt || !out || !gp || P < 1 || N < 1 || gp->draft_len < 0) return -1;
+    if (P + N + gp->draft_len > M->c.max_seq) return -1;
+    const int L = M->c.n_layers, k = gp->draft_len;
+    double* C = (double*)malloc(sizeof(double) * 2 * L);
+    double* Ca = (double*)malloc(sizeof(double) * L);
+    uint8_t* mask = (uint8_t*)calloc((size_t)(2 * L), 1);
+    int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (k + 1));
+    int32_t* g = (int32_t*)malloc(sizeof(int32_t) * (k + 1));
+    orc_gen_stats s = {0, 0, 0, 0};
+    int32_t last;
+    int rc = prefill(M, prompt, P, &last, C);
+    if (rc) goto done;
+    if (gp->mask_mode == 1) {
+        if (!gp->fixed_mask) { rc = -1; goto done; }
+        memcpy(mask, gp->fixed_mask, (size_t)(2 * L));
+    } else {
+        for (int l = 0; l < L; ++l) Ca[l] = C[2 * l];
+        rc = orc_admg(Ca, L, gp->alpha, gp->m, gp->n, gp->use_cs, mask);
+        if (rc) goto done;
+    }
+    out[0] = last; s.emitted = 1;
+    int32_t p = P;
+    while (s.emitted < N) {
+        int kk = k < N - (int)s.emitted - 1 ? k : N - (int)s.emitted - 1;
+        rows[0] = last;
+        for (int j = 1; j <= kk; ++j) {          /* draft with D */
+            rc = orc_forward(M, &rows[j - 1], 1, p + j - 1, mask, 1, NULL, NULL, &rows[j], NULL);
+            if (rc) goto done;
+        }
+        orc_truncate(M, p);
+        rc = orc_forward(M, rows, kk + 1, p, NULL, 1, NULL, NULL, g, NULL);   /* verify with M */
+        if (rc) goto done;
+        int a = 0;
+        while (a < kk && rows[a + 1] == g[a]) ++a;
+        for (int j = 1; j <= a; ++j) out[s.emitted++] = rows[j];
+        out[s.emitted++] = g[a];
+        last = g[a];
+        p += a + 1;
+        orc_truncate(M, p);
+        s.cycles++; s.drafted += kk; s.accepted += a;
+    }
+done:
+    if (rc == 0) {
+        if (st) *st = s;
+        if (mask_used) memcpy(mask_used, mask, (size_t)(2 * L));
+        if (C_prompt) memcpy(C_prompt, C, sizeof(double) * 2 * L);
+    }
+    free(C); free(Ca); free(mask); free(rows); free(g);
+    return rc;
+}

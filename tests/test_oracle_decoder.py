@@ -1,0 +1,241 @@
+"""Pins of the oracle's decoder and cosine taps against things other than itself.
+
+ * an independent Llama implementation (the `transformers` package, CPU, float64)
+   loaded with the same random weights: logits and the residual stream before and
+   after every sublayer, MHA and GQA;
+ * a whole-sequence matrix formulation written here with numpy (no KV cache, no
+   row loop) for a one-layer model;
+ * identities of the cosine of Section 3.2 and structural invariants (causality,
+   cache == recompute, a removed sublayer == a sublayer whose output projection is 0).
+"""
+import numpy as np
+import pytest
+import torch
+
+import asd_inputs as si
+import oracle
+from helpers import SMALL_GQA, SMALL_MHA, make_oracle, weights_dict
+
+
+def np_cos(x, y):
+    return float(np.dot(x, y) / (np.linalg.norm(x) * np.linalg.norm(y)))
+
+
+def hf_model(shape, w):
+    transformers = pytest.importorskip("transformers")
+    cfg = transformers.LlamaConfig(
+        hidden_size=shape.d_model, intermediate_size=shape.d_ffn, num_hidden_layers=shape.n_layers,
+        num_attention_heads=shape.n_heads, num_key_value_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+        vocab_size=shape.vocab, max_position_embeddings=512, rms_norm_eps=shape.rms_eps,
+        rope_theta=shape.rope_theta, attention_bias=False, mlp_bias=False, tie_word_embeddings=False,
+        hidden_act="silu", attn_implementation="eager")
+    m = transformers.LlamaForCausalLM(cfg).double().eval()
+    sd = {}
+    t = lambda a: torch.from_numpy(si.as_f64(a))
+    sd["model.embed_tokens.weight"] = t(w[(si.T_EMBED, 0)])
+    sd["lm_head.weight"] = t(w[(si.T_LM_HEAD, 0)])
+    sd["model.norm.weight"] = t(w[(si.T_FINAL_NORM, 0)])
+    names = {si.T_WQ: "self_attn.q_proj", si.T_WK: "self_attn.k_proj", si.T_WV: "self_attn.v_proj",
+             si.T_WO: "self_attn.o_proj", si.T_WG: "mlp.gate_proj", si.T_WU: "mlp.up_proj",
+             si.T_WD: "mlp.down_proj", si.T_ATTN_NORM: "input_layernorm",
+             si.T_MLP_NORM: "post_attention_layernorm"}
+    for l in range(shape.n_layers):
+        for tid, nm in names.items():
+            sd[f"model.layers.{l}.{nm}.weight"] = t(w[(tid, l)])
+    missing, unexpected = m.load_state_dict(sd, strict=False)
+    assert not [k for k in missing if "rotary" not in k] and not unexpected
+    return m
+
+
+def hf_run(m, tokens):
+    """logits [n,V] and, per sublayer, the residual stream entering / leaving it."""
+    taps = {}
+
+    def grab(key):
+        def hook(mod, args, kwargs):
+            taps[key] = (args[0] if args else kwargs["hidden_states"])[0].detach().numpy().copy()
+        return hook
+
+    hs = []
+    for l, layer in enumerate(m.model.layers):
+        hs.append(layer.input_layernorm.register_forward_pre_hook(grab(("x", l)), with_kwargs=True))
+        hs.append(layer.post_attention_layernorm.register_forward_pre_hook(grab(("y", l)), with_kwargs=True))
+    hs.append(m.model.norm.register_forward_pre_hook(grab(("x", len(m.model.layers))), with_kwargs=True))
+    with torch.no_grad():
+        logits = m(torch.tensor(np.asarray(tokens, dtype=np.int64))[None]).logits[0].numpy()
+    for h in hs:
+        h.remove()
+    return logits, taps
+
+
+@pytest.mark.parametrize("shape", [SMALL_MHA, SMALL_GQA], ids=["mha", "gqa"])
+def test_against_independent_llama_implementation(shape):
+    w = weights_dict(shape, seed=5, gain_std=0.1)
+    m = hf_model(shape, w)
+    tokens = si.prompt(11, 13, shape.vocab)
+    logits, taps = hf_run(m, tokens)
+    o = oracle.Oracle(shape, 64).load((t, l, a) for (t, l), a in w.items())
+    r = o.forward(tokens, 0, want_hidden=True)
+    # that implementation evaluates the rotary angles' cos/sin in float32, so agreement
+    # stops near 1e-7; a convention error (pairing, GQA mapping, norm, gate/up order) is O(1).
+    assert np.abs(r["logits"] - logits).max() < 1e-6
+    assert np.array_equal(r["argmax"], logits.argmax(-1))
+    assert np.abs(r["hidden"] - taps[("x", shape.n_layers)]).max() < 1e-6
+    for l in range(shape.n_layers):
+        for s in range(len(tokens)):
+            x, y, z = taps[("x", l)][s], taps[("y", l)][s], taps[("x", l + 1)][s]
+            assert abs(r["cos_rows"][s, 2 * l] - np_cos(x, y)) < 1e-7
+            assert abs(r["cos_rows"][s, 2 * l + 1] - np_cos(y, z)) < 1e-7
+    # average over the rows of the call (the ACS of Section 3.2)
+    assert np.abs(r["cos"] - r["cos_rows"].mean(0)).max() < 1e-15
+
+
+def test_removed_sublayer_equals_zero_output_projection():
+    """D = M minus sublayers: dropping one is the same function as zeroing its output projection."""
+    shape = SMALL_GQA
+    w = weights_dict(shape, seed=2, gain_std=0.05)
+    mask = np.array([0, 1, 1, 0, 1, 1], dtype=np.uint8)
+    wz = dict(w)
+    for l in range(shape.n_layers):
+        if mask[2 * l]:
+            wz[(si.T_WO, l)] = np.zeros_like(w[(si.T_WO, l)])
+        if mask[2 * l + 1]:
+            wz[(si.T_WD, l)] = np.zeros_like(w[(si.T_WD, l)])
+    tokens = si.prompt(3, 9, shape.vocab)
+    logits, _ = hf_run(hf_model(shape, wz), tokens)
+    o = oracle.Oracle(shape, 64).load((t, l, a) for (t, l), a in w.items())
+    r = o.forward(tokens, 0, skip=mask)
+    assert np.abs(r["logits"] - logits).max() < 1e-6
+    assert (r["cos_rows"][:, mask == 1] == 1.0).all()
+    assert (r["cos_rows"][:, mask == 0] < 1.0).all()
+    # zero-delta sublayer (projection = 0, not skipped): cos(x, x) is exactly 1
+    oz = oracle.Oracle(shape, 64).load((t, l, a) for (t, l), a in wz.items())
+    rz = oz.forward(tokens, 0)
+    assert (rz["cos_rows"][:, mask == 1] == 1.0).all()
+    assert np.array_equal(rz["logits"], r["logits"])
+
+
+def test_one_layer_model_against_matrix_formulation():
+    """Whole-sequence numpy formulation: causal mask matrix, no cache, no per-row loop."""
+    s = si.Shape("one", 1, 48, 3, 3, 16, 80, 50, si.DT_F32, 0, 0, 0)
+    w = {k: si.as_f64(a) for k, a in weights_dict(s, seed=9, gain_std=0.2).items()}
+    tok = si.prompt(4, 7, s.vocab)
+    S, h, nh = len(tok), s.head_dim, s.n_heads
+    rms = lambda x, g: x / np.sqrt((x * x).mean(-1, keepdims=True) + s.rms_eps) * g
+    X = w[(si.T_EMBED, 0)][tok]
+    xn = rms(X, w[(si.T_ATTN_NORM, 0)])
+    Q, K, V = (xn @ w[(t, 0)].T for t in (si.T_WQ, si.T_WK, si.T_WV))
+    pos = np.arange(S)[:, None]
+    ang = pos * s.rope_theta ** (-2.0 * np.arange(h // 2) / h)[None, :]
+
+    def rot(A):
+        A = A.reshape(S, nh, h)
+        a, b = A[..., : h // 2], A[..., h // 2:]
+        c, sn = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+        return np.concatenate([a * c - b * sn, b * c + a * sn], -1)
+
+    Qr, Kr, Vh = rot(Q), rot(K), V.reshape(S, nh, h)
+    sc = np.einsum("ind,jnd->nij", Qr, Kr) / np.sqrt(h)
+    sc = np.where(np.tril(np.ones((S, S), bool))[None], sc, -np.inf)
+    P = np.exp(sc - sc.max(-1, keepdims=True))
+    P /= P.sum(-1, keepdims=True)
+    O = np.einsum("nij,jnd->ind", P, Vh).reshape(S, nh * h)
+    Y = X + O @ w[(si.T_WO, 0)].T
+    yn = rms(Y, w[(si.T_MLP_NORM, 0)])
+    G, U = yn @ w[(si.T_WG, 0)].T, yn @ w[(si.T_WU, 0)].T
+    Z = Y + (G / (1 + np.exp(-G)) * U) @ w[(si.T_WD, 0)].T
+    logits = rms(Z, w[(si.T_FINAL_NORM, 0)]) @ w[(si.T_LM_HEAD, 0)].T
+
+    o = make_oracle(s, seed=9, max_seq=16, gain_std=0.2)
+    r = o.forward(tok, 0, want_hidden=True)
+    assert np.abs(r["logits"] - logits).max() < 1e-12
+    assert np.abs(r["hidden"] - Z).max() < 1e-13
+    for i in range(S):
+        assert abs(r["cos_rows"][i, 0] - np_cos(X[i], Y[i])) < 1e-13
+        assert abs(r["cos_rows"][i, 1] - np_cos(Y[i], Z[i])) < 1e-13
+
+
+def test_cosine_identities():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(257)
+    assert oracle.cosine(x, x) == 1.0
+    assert abs(oracle.cosine(x, 3.5 * x) - 1.0) < 1e-15
+    assert abs(oracle.cosine(x, -x) + 1.0) < 1e-15
+    y = rng.standard_normal(257)
+    y -= x * np.dot(x, y) / np.dot(x, x)
+    assert abs(oracle.cosine(x, y)) < 1e-15
+    assert abs(oracle.cosine(x, x + y) - np.linalg.norm(x) / np.hypot(np.linalg.norm(x), np.linalg.norm(y))) < 1e-14
+    e = np.zeros(4)
+    assert -1.0 <= oracle.cosine(e, e) <= 1.0          # zero norm: defined, in range
+    a, b = np.array([3.0, 4.0]), np.array([4.0, 3.0])
+    assert abs(oracle.cosine(a, b) - 24.0 / 25.0) < 1e-15
+    assert oracle.cosine(a, b) == oracle.cosine(b, a)
+
+
+def test_cache_equals_recompute_and_rows_equal_single_calls():
+    s = SMALL_GQA
+    o = make_oracle(s, seed=1)
+    tok = si.prompt(7, 12, s.vocab)
+    full = o.forward(tok, 0)
+    o.reset()
+    parts = [o.forward(tok[:5], 0), o.forward(tok[5:6], 5), o.forward(tok[6:], 6)]
+    assert np.array_equal(np.concatenate([p["logits"] for p in parts]), full["logits"])
+    assert np.array_equal(np.concatenate([p["cos_rows"] for p in parts]), full["cos_rows"])
+    # mean over the rows of one call == mean of the one-row calls
+    o.reset()
+    rows = [o.forward(tok[i:i + 1], i)["cos"] for i in range(len(tok))]
+    assert np.abs(np.mean(rows, 0) - full["cos"]).max() < 1e-15
+    assert (full["cos_rows"] <= 1.0).all() and (full["cos_rows"] >= -1.0).all()
+
+
+def test_causality_and_rollback():
+    s = SMALL_MHA
+    o = make_oracle(s, seed=3)
+    tok = si.prompt(1, 9, s.vocab)
+    a = o.forward(tok, 0)
+    tok2 = tok.copy()
+    tok2[6] = (tok2[6] + 1) % s.vocab
+    o.reset()
+    b = o.forward(tok2, 0)
+    assert np.array_equal(a["logits"][:6], b["logits"][:6])
+    assert not np.array_equal(a["logits"][6:], b["logits"][6:])
+    # uncommitted rows leave the cache length alone; truncate then replay reproduces the rows
+    o.truncate(4)
+    assert o.kv_len == 4
+    c = o.forward(tok[4:], 4, commit=False)
+    assert o.kv_len == 4 and np.array_equal(c["logits"], a["logits"][4:])
+    with pytest.raises(ValueError):
+        o.forward(tok[:1], 7)        # position must equal the cache length
+
+
+def test_all_keep_mask_is_the_full_model_and_bf16_storage_is_exact():
+    s = SMALL_GQA
+    tok = si.prompt(2, 6, s.vocab)
+    o = make_oracle(s, seed=4)
+    a = o.forward(tok, 0)
+    o.reset()
+    b = o.forward(tok, 0, skip=np.zeros(2 * s.n_layers, np.uint8))
+    assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["cos_rows"], b["cos_rows"])
+    # bf16 storage: same numbers as an fp32 model holding the widened bf16 values
+    s16 = s.with_(dtype=si.DT_BF16)
+    o16 = make_oracle(s16, seed=4)
+    o32 = oracle.Oracle(s, 256)
+    for t, l, arr in si.all_tensors(s16, 4):
+        o32.set_weight(t, l, si.bf16_to_f32(arr) if arr.dtype == np.uint16 else arr)
+    assert np.array_equal(o16.forward(tok, 0)["logits"], o32.forward(tok, 0)["logits"])
+
+
+def test_rope_depends_on_relative_position_only():
+    """Shifting every position by a constant leaves a one-layer attention output unchanged.
+
+    A single-layer model whose prompt is replayed after a dummy prefix token that the
+    attention cannot see is not expressible here, so the property is tested through the
+    scores: with identical tokens at every position, q.k for (i, j) depends on i - j only,
+    hence the attention of row i over identical keys/values is uniform and the output of
+    every row equals the row-0 output.
+    """
+    s = si.Shape("rope", 1, 32, 2, 2, 16, 48, 20, si.DT_F32, 0, 0, 0)
+    o = make_oracle(s, seed=6, max_seq=16)
+    r = o.forward(np.full(8, 7, np.int32), 0, want_hidden=True)
+    # identical tokens -> identical v at every position -> every row's hidden state equals row 0's
+    assert np.abs(r["hidden"] - r["hidden"][0]).max() < 1e-13
