@@ -1,0 +1,211 @@
+/*
+ * asd.h: C ABI of the MI355X (gfx950) engine for adaptive self-speculative decoding.
+ *
+ * The engine runs the batch-1 Llama-style decoder two ways: as a layer-skipping
+ * draft pass (one token per step, attention / MLP sublayers dropped per a skip
+ * mask) and as a (k+1)-row greedy verification pass over the full model, and it
+ * taps, in both, the cosine similarity between the hidden state entering and
+ * leaving every sublayer.  Paper anchors: Section 1 (draft / verify / replace the
+ * first rejected token), Section 3.2 (average cosine similarity C_l over the
+ * prompt, CS thresholding, rules 1 and 2) and Algorithm 1 (ADMG).
+ *
+ * Conventions
+ *   - Every function returns ASD_OK (0) or a negative ASD_E_* code; the message
+ *     is available from asd_last_error().  Outputs are written only on success.
+ *     No C++ exception crosses this boundary.
+ *   - Pointers are HOST pointers unless the comment says DEVICE.
+ *   - Device memory is caller-owned: the caller allocates one arena of
+ *     asd_arena_bytes() bytes (256-byte aligned) and lends it to the engine until
+ *     asd_destroy(); the engine never allocates or frees device memory.
+ *   - The HIP stream is caller-owned; all work is enqueued on it.  Calls that
+ *     return host data synchronise that stream before returning.
+ *   - Layers are 0-based here.  A skip mask has 2L bytes: index 2l = attention
+ *     sublayer of layer l, 2l+1 = its MLP; non-zero = removed from the model.
+ *   - An engine is not thread-safe; calls on one engine must not overlap.
+ *   - Matrices are row-major [out_features][in_features] in the storage type of
+ *     the configuration (fp32, or bf16 bit patterns); norm gains are fp32.
+ */
+#ifndef ASD_H
+#define ASD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ASD_OK = 0, ASD_E_INVAL = -1, ASD_E_STATE = -2, ASD_E_NOMEM = -3, ASD_E_IO = -4, ASD_E_HIP = -5 };
+
+enum { ASD_DT_F32 = 0, ASD_DT_BF16 = 1 };
+
+/* Tensor identifiers for asd_set_weight / asd_get_weight. */
+enum {
+    ASD_T_EMBED = 0, ASD_T_ATTN_NORM = 1, ASD_T_WQ = 2, ASD_T_WK = 3, ASD_T_WV = 4, ASD_T_WO = 5,
+    ASD_T_MLP_NORM = 6, ASD_T_WG = 7, ASD_T_WU = 8, ASD_T_WD = 9, ASD_T_FINAL_NORM = 10, ASD_T_LM_HEAD = 11
+};
+
+#define ASD_MAX_ROWS 16   /* rows per forward call: draft length k <= 15 */
+
+typedef struct asd_engine asd_engine;   /* opaque, library-owned host object */
+
+/*
+ * Model and cache shape.  Constraints (else ASD_E_INVAL): d_model, d_ffn, vocab,
+ * n_heads*head_dim multiples of 16; head_dim a multiple of 32 (bf16) / 16 (fp32)
+ * and <= 256; n_heads a multiple of n_kv_heads; page_tokens a multiple of 64;
+ * 1 <= max_rows <= ASD_MAX_ROWS; max_seq >= 1 (rounded up to whole pages).
+ * dtype is the storage type of weights, activations fed to the matrix cores and
+ * the KV cache; the residual stream and every accumulation are fp32.
+ */
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    int32_t max_seq, page_tokens, max_rows;
+    int32_t dtype;              /* ASD_DT_F32 or ASD_DT_BF16 */
+    float rms_eps, rope_theta;  /* 1e-5, 1e4 for Llama-2 */
+} asd_config;
+
+/*
+ * Parameters of speculative generation.  alpha, m, n are Algorithm 1's inputs
+ * (Table 2: 0.985, 3, 2); m = 0 switches rule 1 off, n = 0 rule 2, use_cs = 0
+ * CS thresholding (the rule subsets of the ablation, Table 5).
+ * draft_len = k >= 0 drafted tokens per cycle (0 = plain greedy decoding).
+ * mask_mode 0: skip mask = ADMG of the prompt's ACS (the paper's method);
+ * mask_mode 1: fixed_mask [2L] is used as given.
+ * use_graphs != 0 replays each draft/verify cycle as a captured HIP graph.
+ */
+typedef struct {
+    float alpha;
+    int32_t m, n, use_cs;
+    int32_t draft_len;
+    int32_t mask_mode;
+    const uint8_t* fixed_mask;
+    int32_t use_graphs;
+} asd_gen_params;
+
+/* Counters of one asd_decode / asd_generate call (emitted includes the first token for asd_generate). */
+typedef struct {
+    int64_t cycles, drafted, accepted, emitted;
+    double ms_prefill, ms_decode;
+} asd_gen_stats;
+
+/* Per-kernel-class GPU time of one profiled forward pass, from HIP events on the engine's stream. */
+enum { ASD_K_EMBED = 0, ASD_K_QKV = 1, ASD_K_ATTN = 2, ASD_K_ATTN_MERGE = 3, ASD_K_OPROJ = 4, ASD_K_GATEUP = 5,
+       ASD_K_DOWN = 6, ASD_K_LMHEAD = 7, ASD_K_FINISH = 8, ASD_K_COUNT = 9 };
+typedef struct {
+    double ms[ASD_K_COUNT];       /* summed duration of the launches of each class */
+    int32_t launches[ASD_K_COUNT];
+    double bytes[ASD_K_COUNT];    /* algorithmic bytes those launches must read (weights, KV) */
+    double ms_total;              /* first launch start to last launch end */
+} asd_kernel_times;
+
+/* Bytes of device memory the engine needs for this configuration (0 if the configuration is invalid). */
+size_t asd_arena_bytes(const asd_config* cfg);
+
+/*
+ * Create an engine on the current HIP device.  device_arena: DEVICE pointer to
+ * arena_bytes >= asd_arena_bytes(cfg) bytes, 256-byte aligned, borrowed until
+ * asd_destroy.  hip_stream: a hipStream_t (NULL = the default stream).
+ * The KV cache and workspace are cleared; weights are unset.
+ */
+int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, void* hip_stream, asd_engine** out);
+void asd_destroy(asd_engine* e);
+
+/* Message of the last failing call on this engine (or of the last failing asd_create when e is NULL). */
+const char* asd_last_error(const asd_engine* e);
+
+/*
+ * Weights.  asd_set_weight copies one tensor (bytes must match its size) from host
+ * or, when src_on_device != 0, from DEVICE memory, and re-tiles matrices into the
+ * engine's streaming layout.  asd_get_weight returns it to HOST memory, row-major.
+ * asd_init_synthetic fills every tensor on the device with the counter-based
+ * random-init recipe (std 0.02, per-sublayer log-uniform [1e-3,1] scales on W_o
+ * and W_d, gains 1), bit-identical to the host generator for the same seed.
+ * asd_load_weights_file reads a flat file: 8 bytes "ASDW0001", int32[8] =
+ * {n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, dtype}, then
+ * EMBED, FINAL_NORM, LM_HEAD, then per layer ATTN_NORM, WQ, WK, WV, WO, MLP_NORM,
+ * WG, WU, WD, each as asd_set_weight takes it.
+ */
+int asd_set_weight(asd_engine* e, int32_t tensor_id, int32_t layer, const void* src, size_t bytes, int32_t src_on_device);
+int asd_get_weight(asd_engine* e, int32_t tensor_id, int32_t layer, void* dst, size_t bytes);
+int asd_init_synthetic(asd_engine* e, uint64_t seed);
+int asd_load_weights_file(asd_engine* e, const char* path);
+
+/*
+ * Paged KV cache.  Logical page i (tokens [i*page_tokens, (i+1)*page_tokens)) lives
+ * in physical page table[i]; table must be a permutation of 0..n_pages-1 where
+ * n_pages = ceil(max_seq / page_tokens).  Default: identity.  Requires kv_len == 0.
+ */
+int asd_set_page_table(asd_engine* e, const int32_t* table, int32_t n_pages);
+
+/* Cache length control: reset = truncate to 0; truncate rolls back to new_len <= kv_len. */
+int asd_reset(asd_engine* e);
+int asd_truncate(asd_engine* e, int32_t new_len);
+int32_t asd_kv_len(const asd_engine* e);
+
+/*
+ * Forward pass with an explicit skip mask (the draft model is the full model minus
+ * the masked sublayers; NULL mask = full model).  tokens[n_rows] are fed at
+ * positions pos0 .. pos0+n_rows-1; pos0 must equal asd_kv_len() (ASD_E_STATE
+ * otherwise) and 1 <= n_rows <= max_rows.  commit != 0 leaves kv_len at
+ * pos0+n_rows, else at pos0.  Outputs, each optional (NULL):
+ *   logits [n_rows][vocab] fp32; cos [2L] = mean over the rows of the per-row
+ *   cosine similarity of every sublayer (a removed sublayer reports exactly 1);
+ *   cos_rows [n_rows][2L]; argmax [n_rows] (lowest index on ties).
+ */
+int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t pos0, const uint8_t* skip_mask,
+                int32_t commit, float* logits, float* cos, float* cos_rows, int32_t* argmax);
+
+/*
+ * Prompt pass (Section 3.2): resets the cache, runs all n prompt tokens through the
+ * full model in chunks of max_rows rows, returns the first generated token, the
+ * ACS of every sublayer over the n rows (cos_out [2L], optional) and the logits of
+ * the last row (last_logits [vocab], optional).  The ACS is kept in the engine for
+ * a following asd_decode with mask_mode 0.
+ */
+int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits);
+
+/*
+ * Algorithm 1 (ADMG), a pure host function: c_attn [L] are the attention sublayers'
+ * ACS values; skip_mask [2L] receives remove_ATTN (even indices) and remove_MLP
+ * (odd indices).  Layer l (0-based) is the paper's layer l+1: rule 1 removes it when
+ * (l+1) % m == 0, rule 2 protects l >= L-n, CS thresholding removes attention l
+ * when c_attn[l] >= alpha (compared in fp32).
+ */
+int asd_admg(const float* c_attn, int32_t n_layers, float alpha, int32_t m, int32_t n, int32_t use_cs, uint8_t* skip_mask);
+
+/*
+ * Greedy speculative decoding from the current cache state (Section 1): last_token
+ * is the newest token, not yet in the cache.  Emits exactly n_more tokens into
+ * out_tokens; they equal what plain greedy decoding of the full model emits.  Each
+ * cycle drafts min(k, tokens still needed - 1) tokens with the masked model,
+ * verifies them in one pass of the full model, keeps the accepted prefix plus the
+ * full model's token after it, and rolls the cache back to the accepted length.
+ * mask_used [2L] (optional) receives the skip mask in effect.
+ */
+int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_params* p,
+               int32_t* out_tokens, asd_gen_stats* stats, uint8_t* mask_used);
+
+/* asd_prefill + ADMG + asd_decode: out_tokens [n_new], out_tokens[0] is the prompt pass's token. */
+int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t n_new, const asd_gen_params* p,
+                 int32_t* out_tokens, asd_gen_stats* stats, uint8_t* mask_used);
+
+/*
+ * Measurement helpers (benchmark only; they leave kv_len unchanged).
+ * asd_time_pass: average milliseconds of one forward pass of n_rows rows at the
+ * current kv_len with the given mask, over reps back-to-back repetitions bracketed
+ * by HIP events on the engine's stream (as a captured graph when use_graph != 0);
+ * *bytes (optional) = algorithmic bytes one such pass must read.
+ * asd_profile_forward: one such pass with an event pair around every launch.
+ * asd_copy_bench: average milliseconds of a plain device copy kernel moving
+ * nbytes (read nbytes + write nbytes) inside the arena's scratch region; used to
+ * calibrate byte counters and to report the achievable HBM rate.
+ */
+int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, int32_t reps, int32_t use_graph,
+                  double* ms_avg, double* bytes);
+int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, asd_kernel_times* out);
+int asd_copy_bench(asd_engine* e, size_t nbytes, int32_t reps, double* ms_avg);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ASD_H */

@@ -108,7 +108,10 @@ class Oracle:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown
+            pass
 
     def set_weight(self, tensor: int, layer: int, arr: np.ndarray):
         a = np.ascontiguousarray(arr)

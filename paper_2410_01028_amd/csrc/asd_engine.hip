@@ -1,0 +1,980 @@
+// Host side of the engine: arena planning, weight loading, the forward-pass launch sequence
+// (skip-mask scheduling: a removed sublayer is simply not launched), prompt pass, the
+// draft / verify / accept loop with optional HIP-graph replay, and the C ABI of asd.h.
+#include "../../include/asd.h"
+#include "asd_attn.h"
+#include "asd_common.h"
+#include "asd_gemm.h"
+#include "asd_misc.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+namespace {
+
+thread_local std::string g_create_error;
+
+struct GemmCfg { int TN, NW, grid; };
+
+struct Layer {
+    char *wqkv, *wo, *wg, *wu, *wd;
+    float *g_attn, *g_mlp;
+};
+
+struct Profiler {
+    std::vector<hipEvent_t> ev;        // pairs
+    std::vector<int> cls;
+    std::vector<double> bytes;
+};
+
+}  // namespace
+
+struct asd_engine {
+    asd_config c;
+    hipStream_t stream;
+    char* arena;
+    size_t arena_bytes;
+    int es, KE, KBd, KBq, KBf;
+    int n_pages, nc_stride, qkv_tiles;
+    // weights
+    std::vector<Layer> layers;
+    char *embed, *lm;
+    float* g_final;
+    std::vector<uint8_t> have;          // per tensor slot
+    // cache
+    char* kv;
+    size_t kv_layer_bytes;
+    int32_t* page_table;
+    // workspace
+    float *xres, *ssq, *part, *cos_rows, *logits, *o_part, *rope;
+    float2* ml_part;
+    void *xb, *q, *attn_out, *hmid;
+    unsigned* counters;
+    double* cos_acc;
+    AmaxPart* amax_part;
+    int32_t *argmax, *tokbuf, *out_tokens;
+    DevState* st;
+    char* staging;
+    size_t staging_bytes;
+    // launch shapes
+    GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
+    // host state
+    int kv_len;
+    std::vector<float> acs;
+    bool acs_valid;
+    DevState* h_st;                     // pinned
+    std::map<std::vector<int>, hipGraphExec_t> graphs;
+    std::vector<uint8_t> graph_mask;
+    std::string err;
+};
+
+namespace {
+
+int fail(asd_engine* e, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (e) e->err = buf; else g_create_error = buf;
+    return code;
+}
+
+#define CK(e, expr)                                                                              \
+    do {                                                                                         \
+        hipError_t _r = (expr);                                                                  \
+        if (_r != hipSuccess) return fail(e, ASD_E_HIP, "%s: %s", #expr, hipGetErrorString(_r)); \
+    } while (0)
+
+size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+bool config_ok(const asd_config* c, std::string* why) {
+    auto bad = [&](const char* m) { if (why) *why = m; return false; };
+    if (!c) return bad("null configuration");
+    if (c->dtype != ASD_DT_F32 && c->dtype != ASD_DT_BF16) return bad("dtype must be ASD_DT_F32 or ASD_DT_BF16");
+    if (c->n_layers < 1 || c->d_model < 16 || c->n_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 16 || c->d_ffn < 16 ||
+        c->vocab < 16 || c->max_seq < 1)
+        return bad("non-positive dimension");
+    if (c->d_model % 16 || c->d_ffn % 16 || c->vocab % 16) return bad("d_model, d_ffn and vocab must be multiples of 16");
+    if (c->n_heads % c->n_kv_heads) return bad("n_heads must be a multiple of n_kv_heads");
+    const int hq = c->dtype == ASD_DT_BF16 ? 32 : 16;
+    if (c->head_dim % hq) return bad("head_dim must be a multiple of 32 (bf16) or 16 (fp32)");
+    if (c->head_dim != 32 && c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 32, 64 or 128");
+    if (c->page_tokens < 64 || c->page_tokens % 64) return bad("page_tokens must be a positive multiple of 64");
+    if (c->max_rows < 1 || c->max_rows > ASD_MAX_ROWS) return bad("max_rows must be in 1..16");
+    if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return bad("rms_eps must be > 0 and rope_theta > 1");
+    if ((long)c->n_layers * 2 > 4096) return bad("too many layers");
+    return true;
+}
+
+GemmCfg pick_cfg(int epi, int tiles, int KB) {
+    GemmCfg g;
+    if (epi == EPI_QKV) g.TN = 2;
+    else if (epi == EPI_LM) g.TN = 2;
+    else if (epi == EPI_GU) g.TN = tiles <= 2048 ? 1 : 2;
+    else g.TN = tiles <= 1024 ? 1 : 2;
+    g.grid = (epi == EPI_QKV) ? tiles / 2 : (tiles + g.TN - 1) / g.TN;
+    const int maxnw = (epi == EPI_RES) ? 16 : 8;
+    g.NW = 4;
+    for (int nw = maxnw; nw > 4; nw /= 2)
+        if ((long)g.grid * nw <= 8192 && KB / nw >= 4) { g.NW = nw; break; }
+    return g;
+}
+
+struct Plan {
+    size_t embed, lm, g_final, layer0, layer_stride, wqkv, wo, wg, wu, wd, g_attn, g_mlp;
+    size_t kv, kv_layer, page_table;
+    size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
+        argmax, tokbuf, out_tokens, st, staging, staging_bytes, total;
+    int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
+    GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
+};
+
+Plan make_plan(const asd_config& c) {
+    Plan p{};
+    p.es = c.dtype == ASD_DT_BF16 ? 2 : 4;
+    p.KE = 16 / p.es;
+    const int kblk = 4 * p.KE;
+    const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+    p.KBd = (c.d_model + kblk - 1) / kblk;
+    p.KBq = (qd + kblk - 1) / kblk;
+    p.KBf = (c.d_ffn + kblk - 1) / kblk;
+    p.n_pages = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
+    p.nc_stride = p.n_pages * c.page_tokens / ASD_CHUNK;
+    p.qkv_tiles = (qd + 2 * kvd) / 16;
+    p.g_qkv = pick_cfg(EPI_QKV, p.qkv_tiles, p.KBd);
+    p.g_o = pick_cfg(EPI_RES, c.d_model / 16, p.KBq);
+    p.g_gu = pick_cfg(EPI_GU, c.d_ffn / 16, p.KBd);
+    p.g_down = pick_cfg(EPI_RES, c.d_model / 16, p.KBf);
+    p.g_lm = pick_cfg(EPI_LM, c.vocab / 16, p.KBd);
+
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    const size_t frag = 1024;   // bytes of one (tile, k-block)
+    p.embed = take((size_t)c.vocab * c.d_model * p.es);
+    p.lm = take((size_t)(c.vocab / 16) * p.KBd * frag);
+    p.g_final = take((size_t)c.d_model * 4);
+    p.layer0 = off;
+    p.wqkv = take((size_t)p.qkv_tiles * p.KBd * frag) - p.layer0;
+    p.wo = take((size_t)(c.d_model / 16) * p.KBq * frag) - p.layer0;
+    p.wg = take((size_t)(c.d_ffn / 16) * p.KBd * frag) - p.layer0;
+    p.wu = take((size_t)(c.d_ffn / 16) * p.KBd * frag) - p.layer0;
+    p.wd = take((size_t)(c.d_model / 16) * p.KBf * frag) - p.layer0;
+    p.g_attn = take((size_t)c.d_model * 4) - p.layer0;
+    p.g_mlp = take((size_t)c.d_model * 4) - p.layer0;
+    p.layer_stride = off - p.layer0;
+    off = p.layer0 + p.layer_stride * c.n_layers;
+    p.kv_layer = (size_t)p.n_pages * c.n_kv_heads * 2 * c.page_tokens * c.head_dim * p.es;
+    p.kv = take(p.kv_layer * c.n_layers);
+    p.page_table = take((size_t)p.n_pages * 4);
+    p.xres = take((size_t)ASD_ROWS * c.d_model * 4);
+    p.ssq = take(ASD_ROWS * 4);
+    const int pmax = p.g_o.grid > p.g_down.grid ? p.g_o.grid : p.g_down.grid;
+    p.part = take((size_t)pmax * ASD_ROWS * 2 * 4);
+    p.cos_rows = take((size_t)2 * c.n_layers * ASD_ROWS * 4);
+    p.logits = take((size_t)ASD_ROWS * c.vocab * 4);
+    p.o_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
+    p.rope = take((size_t)p.n_pages * c.page_tokens * (c.head_dim / 2) * 2 * 4);
+    p.ml_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * 8);
+    p.xb = take((size_t)p.KBd * frag);
+    p.q = take((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es);
+    p.attn_out = take((size_t)p.KBq * frag);
+    p.hmid = take((size_t)p.KBf * frag);
+    p.counters = take(256);
+    p.cos_acc = take((size_t)2 * c.n_layers * 8);
+    p.amax_part = take((size_t)p.g_lm.grid * ASD_ROWS * sizeof(AmaxPart));
+    p.argmax = take(ASD_ROWS * 4);
+    p.tokbuf = take(64 * 4);
+    p.out_tokens = take((size_t)(p.n_pages * c.page_tokens + 64) * 4);
+    p.st = take(sizeof(DevState));
+    size_t biggest = (size_t)c.vocab * c.d_model;
+    if ((size_t)c.d_ffn * c.d_model > biggest) biggest = (size_t)c.d_ffn * c.d_model;
+    if ((size_t)qd * c.d_model > biggest) biggest = (size_t)qd * c.d_model;
+    p.staging_bytes = align_up(biggest * p.es + 4096);
+    p.staging = take(p.staging_bytes);
+    p.total = off;
+    return p;
+}
+
+// ------------------------------------------------------------------ tensor table
+struct TensorInfo { int rows, cols; bool norm; bool tiled; };
+
+bool tensor_info(const asd_config& c, int t, TensorInfo* ti) {
+    const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+    switch (t) {
+        case ASD_T_EMBED: *ti = {c.vocab, c.d_model, false, false}; return true;
+        case ASD_T_LM_HEAD: *ti = {c.vocab, c.d_model, false, true}; return true;
+        case ASD_T_WQ: *ti = {qd, c.d_model, false, true}; return true;
+        case ASD_T_WK: case ASD_T_WV: *ti = {kvd, c.d_model, false, true}; return true;
+        case ASD_T_WO: *ti = {c.d_model, qd, false, true}; return true;
+        case ASD_T_WG: case ASD_T_WU: *ti = {c.d_ffn, c.d_model, false, true}; return true;
+        case ASD_T_WD: *ti = {c.d_model, c.d_ffn, false, true}; return true;
+        case ASD_T_ATTN_NORM: case ASD_T_MLP_NORM: case ASD_T_FINAL_NORM: *ti = {1, c.d_model, true, false}; return true;
+        default: return false;
+    }
+}
+bool tensor_is_global(int t) { return t == ASD_T_EMBED || t == ASD_T_LM_HEAD || t == ASD_T_FINAL_NORM; }
+int have_slot(const asd_engine* e, int t, int layer) { return tensor_is_global(t) ? t : 12 + layer * 12 + t; }
+
+// device address of a tensor (for tiled ones: the start of its tiles) and its k-block count
+char* tensor_addr(asd_engine* e, int t, int layer, int* KB) {
+    const asd_config& c = e->c;
+    const size_t frag = 1024;
+    const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+    *KB = e->KBd;
+    switch (t) {
+        case ASD_T_EMBED: return e->embed;
+        case ASD_T_LM_HEAD: return e->lm;
+        case ASD_T_FINAL_NORM: return (char*)e->g_final;
+        case ASD_T_ATTN_NORM: return (char*)e->layers[layer].g_attn;
+        case ASD_T_MLP_NORM: return (char*)e->layers[layer].g_mlp;
+        case ASD_T_WQ: return e->layers[layer].wqkv;
+        case ASD_T_WK: return e->layers[layer].wqkv + (size_t)(qd / 16) * e->KBd * frag;
+        case ASD_T_WV: return e->layers[layer].wqkv + (size_t)((qd + kvd) / 16) * e->KBd * frag;
+        case ASD_T_WO: *KB = e->KBq; return e->layers[layer].wo;
+        case ASD_T_WG: return e->layers[layer].wg;
+        case ASD_T_WU: return e->layers[layer].wu;
+        case ASD_T_WD: *KB = e->KBf; return e->layers[layer].wd;
+    }
+    return nullptr;
+}
+
+template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, int N, int K, int KB, bool untile) {
+    const size_t frags = (size_t)(N / 16) * KB * 64;
+    const unsigned grid = (unsigned)((frags + 255) / 256);
+    using El = typename T::elem;
+    if (untile) untile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, KB);
+    else tile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, KB);
+}
+
+// ------------------------------------------------------------------ GEMM dispatch
+template <class T, int EPI, int TN, int NW>
+void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
+    gemm_kernel<T, EPI, TN, NW, 4><<<grid, NW * 64, 0, s>>>(a);
+}
+
+template <class T, int EPI>
+bool launch_gemm_t(hipStream_t s, const GemmCfg& g, const GemmArgs& a) {
+#define CASE(tn, nw) if (g.TN == tn && g.NW == nw) { launch_gemm_inst<T, EPI, tn, nw>(s, g.grid, a); return true; }
+    if constexpr (EPI == EPI_QKV) { CASE(2, 4) CASE(2, 8) }
+    if constexpr (EPI == EPI_RES) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) CASE(2, 16) }
+    if constexpr (EPI == EPI_GU) { CASE(1, 4) CASE(1, 8) CASE(2, 4) CASE(2, 8) }
+    if constexpr (EPI == EPI_LM) { CASE(2, 4) CASE(2, 8) }
+#undef CASE
+    return false;
+}
+
+template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmArgs& a) {
+    return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
+}
+
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
+    const int H = e->c.head_dim;
+    dim3 gp(nc, e->c.n_heads), gm(e->c.n_heads, a.M);
+#define ATT(h)                                                                              \
+    if (H == h) {                                                                           \
+        if (merge) attn_merge_kernel<T, h><<<gm, h, 0, e->stream>>>(a);                     \
+        else attn_partial_kernel<T, h><<<gp, 64, 0, e->stream>>>(a);                        \
+    }
+    ATT(32) ATT(64) ATT(128)
+#undef ATT
+}
+void launch_attn(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
+    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc, merge); else launch_attn_t<F32>(e, a, nc, merge);
+}
+
+// ------------------------------------------------------------------ algorithmic bytes
+// What one forward pass must read: kept sublayers' weights, the LM head, and the K/V of ctx positions.
+void pass_bytes(const asd_engine* e, const uint8_t* mask, int ctx, double* by_class) {
+    const asd_config& c = e->c;
+    const double es = e->es, qd = (double)c.n_heads * c.head_dim, kvd = (double)c.n_kv_heads * c.head_dim;
+    for (int i = 0; i < ASD_K_COUNT; ++i) by_class[i] = 0.0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        if (!(mask && mask[2 * l])) {
+            by_class[ASD_K_QKV] += es * (qd + 2 * kvd) * c.d_model;
+            by_class[ASD_K_ATTN] += es * 2 * kvd * ctx;
+            by_class[ASD_K_OPROJ] += es * qd * c.d_model;
+        }
+        if (!(mask && mask[2 * l + 1])) {
+            by_class[ASD_K_GATEUP] += es * 2.0 * c.d_ffn * c.d_model;
+            by_class[ASD_K_DOWN] += es * (double)c.d_ffn * c.d_model;
+        }
+    }
+    by_class[ASD_K_LMHEAD] = es * (double)c.vocab * c.d_model;
+}
+
+// ------------------------------------------------------------------ forward pass (enqueue only)
+const float* next_gain(const asd_engine* e, const uint8_t* mask, int after /* sublayer index, -1 = before all */) {
+    for (int j = after + 1; j < 2 * e->c.n_layers; ++j)
+        if (!(mask && mask[j])) return (j & 1) ? e->layers[j / 2].g_mlp : e->layers[j / 2].g_attn;
+    return e->g_final;
+}
+
+struct Prof {
+    Profiler* p;
+    hipStream_t s;
+    void begin(int cls, double bytes) {
+        if (!p) return;
+        hipEvent_t a, b;
+        hipEventCreate(&a); hipEventCreate(&b);
+        hipEventRecord(a, s);
+        p->ev.push_back(a); p->ev.push_back(b); p->cls.push_back(cls); p->bytes.push_back(bytes);
+    }
+    void end() { if (p) hipEventRecord(p->ev.back(), s); }
+};
+
+int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
+                    Profiler* profiler, int ctx_for_bytes) {
+    const asd_config& c = e->c;
+    Prof pr{profiler, e->stream};
+    double cls_bytes[ASD_K_COUNT];
+    pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // per-sublayer figures: divide the full-model totals by L
+    const double L = c.n_layers;
+    const float inv_d = 1.f / (float)c.d_model;
+
+    pr.begin(ASD_K_EMBED, 0);
+    if (c.dtype == ASD_DT_BF16)
+        embed_kernel<BF16><<<M, 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model, next_gain(e, mask, -1),
+                                                     e->xres, e->xb, e->ssq);
+    else
+        embed_kernel<F32><<<M, 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model, next_gain(e, mask, -1),
+                                                    e->xres, e->xb, e->ssq);
+    pr.end();
+
+    GemmArgs base{};
+    base.M = M; base.ssq = e->ssq; base.inv_d = inv_d; base.eps = c.rms_eps;
+    base.xres = e->xres; base.xb = e->xb; base.part = e->part; base.d = c.d_model;
+    base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.q = e->q; base.page_table = e->page_table;
+    base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
+    base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part; base.argmax = e->argmax;
+
+    for (int l = 0; l < c.n_layers; ++l) {
+        const Layer& ly = e->layers[l];
+        if (!(mask && mask[2 * l])) {
+            GemmArgs a = base;
+            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.n_tiles = e->qkv_tiles; a.KB = e->KBd;
+            a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
+            pr.begin(ASD_K_QKV, cls_bytes[ASD_K_QKV] / L);
+            if (!launch_gemm<EPI_QKV>(e, e->g_qkv, a)) return fail(e, ASD_E_STATE, "no QKV kernel for this shape");
+            pr.end();
+
+            AttnArgs t{};
+            t.q = e->q; t.kv = a.kv; t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M;
+            t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
+            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
+            t.o_part = e->o_part; t.ml_part = e->ml_part; t.out = e->attn_out;
+            pr.begin(ASD_K_ATTN, cls_bytes[ASD_K_ATTN] / L);
+            launch_attn(e, t, nc, false);
+            pr.end();
+            pr.begin(ASD_K_ATTN_MERGE, 0);
+            launch_attn(e, t, nc, true);
+            pr.end();
+
+            GemmArgs o = base;
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.n_tiles = c.d_model / 16; o.KB = e->KBq;
+            o.g_next = next_gain(e, mask, 2 * l); o.counter = e->counters;
+            o.cos_rows = e->cos_rows + (size_t)(2 * l) * ASD_ROWS; o.cos_acc = e->cos_acc + 2 * l;
+            pr.begin(ASD_K_OPROJ, cls_bytes[ASD_K_OPROJ] / L);
+            if (!launch_gemm<EPI_RES>(e, e->g_o, o)) return fail(e, ASD_E_STATE, "no O-projection kernel for this shape");
+            pr.end();
+        }
+        if (!(mask && mask[2 * l + 1])) {
+            GemmArgs a = base;
+            a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb;
+            a.n_tiles = c.d_ffn / 16; a.KB = e->KBd;
+            pr.begin(ASD_K_GATEUP, cls_bytes[ASD_K_GATEUP] / L);
+            if (!launch_gemm<EPI_GU>(e, e->g_gu, a)) return fail(e, ASD_E_STATE, "no gate/up kernel for this shape");
+            pr.end();
+
+            GemmArgs dn = base;
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.n_tiles = c.d_model / 16; dn.KB = e->KBf;
+            dn.g_next = next_gain(e, mask, 2 * l + 1); dn.counter = e->counters + 1;
+            dn.cos_rows = e->cos_rows + (size_t)(2 * l + 1) * ASD_ROWS; dn.cos_acc = e->cos_acc + 2 * l + 1;
+            pr.begin(ASD_K_DOWN, cls_bytes[ASD_K_DOWN] / L);
+            if (!launch_gemm<EPI_RES>(e, e->g_down, dn)) return fail(e, ASD_E_STATE, "no down-projection kernel for this shape");
+            pr.end();
+        }
+    }
+    GemmArgs lm = base;
+    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.n_tiles = c.vocab / 16; lm.KB = e->KBd;
+    lm.counter = e->counters + 2;
+    pr.begin(ASD_K_LMHEAD, cls_bytes[ASD_K_LMHEAD]);
+    if (!launch_gemm<EPI_LM>(e, e->g_lm, lm)) return fail(e, ASD_E_STATE, "no LM-head kernel for this shape");
+    pr.end();
+    hipError_t r = hipGetLastError();
+    if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
+    return ASD_OK;
+}
+
+bool weights_ready(asd_engine* e) {
+    for (uint8_t h : e->have) if (!h) return false;
+    return true;
+}
+
+int chunks_for(int last_pos) { return last_pos / ASD_CHUNK + 1; }
+
+int check_tokens(asd_engine* e, const int32_t* t, int n) {
+    for (int i = 0; i < n; ++i)
+        if (t[i] < 0 || t[i] >= e->c.vocab) return fail(e, ASD_E_INVAL, "token id %d at index %d outside [0, %d)", t[i], i, e->c.vocab);
+    return ASD_OK;
+}
+
+int check_mask(asd_engine*, const uint8_t*) { return ASD_OK; }
+
+void drop_graphs(asd_engine* e) {
+    for (auto& kv : e->graphs) hipGraphExecDestroy(kv.second);
+    e->graphs.clear();
+}
+
+int capacity(const asd_engine* e) { return e->n_pages * e->c.page_tokens; }
+
+}  // namespace
+
+// =================================================================== C ABI
+extern "C" {
+
+size_t asd_arena_bytes(const asd_config* cfg) {
+    if (!config_ok(cfg, nullptr)) return 0;
+    return make_plan(*cfg).total;
+}
+
+const char* asd_last_error(const asd_engine* e) { return e ? e->err.c_str() : g_create_error.c_str(); }
+
+int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, void* hip_stream, asd_engine** out) {
+    std::string why;
+    if (!out) return fail(nullptr, ASD_E_INVAL, "out is NULL");
+    if (!config_ok(cfg, &why)) return fail(nullptr, ASD_E_INVAL, "invalid configuration: %s", why.c_str());
+    if (!device_arena) return fail(nullptr, ASD_E_INVAL, "device_arena is NULL");
+    if ((uintptr_t)device_arena % 256) return fail(nullptr, ASD_E_INVAL, "device_arena must be 256-byte aligned");
+    Plan p = make_plan(*cfg);
+    if (arena_bytes < p.total)
+        return fail(nullptr, ASD_E_NOMEM, "arena too small: %zu bytes given, %zu needed", arena_bytes, p.total);
+    asd_engine* e = new (std::nothrow) asd_engine();
+    if (!e) return fail(nullptr, ASD_E_NOMEM, "host allocation failed");
+    e->c = *cfg; e->stream = (hipStream_t)hip_stream; e->arena = (char*)device_arena; e->arena_bytes = arena_bytes;
+    e->es = p.es; e->KE = p.KE; e->KBd = p.KBd; e->KBq = p.KBq; e->KBf = p.KBf;
+    e->n_pages = p.n_pages; e->nc_stride = p.nc_stride; e->qkv_tiles = p.qkv_tiles;
+    char* A = e->arena;
+    e->embed = A + p.embed; e->lm = A + p.lm; e->g_final = (float*)(A + p.g_final);
+    e->layers.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        char* B = A + p.layer0 + p.layer_stride * l;
+        e->layers[l] = Layer{B + p.wqkv, B + p.wo, B + p.wg, B + p.wu, B + p.wd, (float*)(B + p.g_attn), (float*)(B + p.g_mlp)};
+    }
+    e->have.assign(12 + (size_t)cfg->n_layers * 12, 1);
+    for (int t = 0; t <= ASD_T_LM_HEAD; ++t) {
+        if (tensor_is_global(t)) e->have[t] = 0;
+        else for (int l = 0; l < cfg->n_layers; ++l) e->have[12 + l * 12 + t] = 0;
+    }
+    e->kv = A + p.kv; e->kv_layer_bytes = p.kv_layer; e->page_table = (int32_t*)(A + p.page_table);
+    e->xres = (float*)(A + p.xres); e->ssq = (float*)(A + p.ssq); e->part = (float*)(A + p.part);
+    e->cos_rows = (float*)(A + p.cos_rows); e->logits = (float*)(A + p.logits); e->o_part = (float*)(A + p.o_part);
+    e->rope = (float*)(A + p.rope); e->ml_part = (float2*)(A + p.ml_part);
+    e->xb = A + p.xb; e->q = A + p.q; e->attn_out = A + p.attn_out; e->hmid = A + p.hmid;
+    e->counters = (unsigned*)(A + p.counters); e->cos_acc = (double*)(A + p.cos_acc);
+    e->amax_part = (AmaxPart*)(A + p.amax_part); e->argmax = (int32_t*)(A + p.argmax);
+    e->tokbuf = (int32_t*)(A + p.tokbuf); e->out_tokens = (int32_t*)(A + p.out_tokens); e->st = (DevState*)(A + p.st);
+    e->staging = A + p.staging; e->staging_bytes = p.staging_bytes;
+    e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
+    e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_valid = false; e->h_st = nullptr;
+
+    hipError_t r = hipHostMalloc((void**)&e->h_st, sizeof(DevState), hipHostMallocDefault);
+    if (r != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(r)); }
+    // clear cache + workspace (everything after the weights), then build the tables
+    r = hipMemsetAsync(A + p.kv, 0, p.total - p.kv, e->stream);
+    if (r == hipSuccess) {
+        const size_t nrope = (size_t)capacity(e) * (cfg->head_dim / 2);
+        rope_table_kernel<<<(unsigned)((nrope + 255) / 256), 256, 0, e->stream>>>(e->rope, capacity(e), cfg->head_dim / 2,
+                                                                                  (double)cfg->rope_theta);
+        iota_kernel<<<(e->n_pages + 255) / 256, 256, 0, e->stream>>>(e->page_table, e->n_pages);
+        r = hipStreamSynchronize(e->stream);
+    }
+    if (r != hipSuccess) {
+        hipHostFree(e->h_st); delete e;
+        return fail(nullptr, ASD_E_HIP, "engine initialisation: %s", hipGetErrorString(r));
+    }
+    *out = e;
+    return ASD_OK;
+}
+
+void asd_destroy(asd_engine* e) {
+    if (!e) return;
+    hipStreamSynchronize(e->stream);
+    drop_graphs(e);
+    if (e->h_st) hipHostFree(e->h_st);
+    delete e;
+}
+
+int asd_set_weight(asd_engine* e, int32_t t, int32_t layer, const void* src, size_t bytes, int32_t src_on_device) {
+    if (!e) return ASD_E_INVAL;
+    TensorInfo ti;
+    if (!src || !tensor_info(e->c, t, &ti)) return fail(e, ASD_E_INVAL, "bad tensor id or NULL source");
+    if (!tensor_is_global(t) && (layer < 0 || layer >= e->c.n_layers)) return fail(e, ASD_E_INVAL, "layer %d out of range", layer);
+    const size_t need = (size_t)ti.rows * ti.cols * (ti.norm ? 4 : e->es);
+    if (bytes != need) return fail(e, ASD_E_INVAL, "tensor %d needs %zu bytes, got %zu", t, need, bytes);
+    int KB;
+    char* dst = tensor_addr(e, t, layer, &KB);
+    const hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+    if (!ti.tiled) {
+        CK(e, hipMemcpyAsync(dst, src, bytes, kind, e->stream));
+    } else {
+        const void* dsrc = src;
+        if (!src_on_device) {
+            CK(e, hipMemcpyAsync(e->staging, src, bytes, hipMemcpyHostToDevice, e->stream));
+            dsrc = e->staging;
+        }
+        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, dsrc, dst, ti.rows, ti.cols, KB, false);
+        else launch_tile<F32>(e, dsrc, dst, ti.rows, ti.cols, KB, false);
+    }
+    CK(e, hipStreamSynchronize(e->stream));
+    e->have[have_slot(e, t, layer)] = 1;
+    return ASD_OK;
+}
+
+int asd_get_weight(asd_engine* e, int32_t t, int32_t layer, void* dst, size_t bytes) {
+    if (!e) return ASD_E_INVAL;
+    TensorInfo ti;
+    if (!dst || !tensor_info(e->c, t, &ti)) return fail(e, ASD_E_INVAL, "bad tensor id or NULL destination");
+    if (!tensor_is_global(t) && (layer < 0 || layer >= e->c.n_layers)) return fail(e, ASD_E_INVAL, "layer %d out of range", layer);
+    const size_t need = (size_t)ti.rows * ti.cols * (ti.norm ? 4 : e->es);
+    if (bytes != need) return fail(e, ASD_E_INVAL, "tensor %d has %zu bytes, buffer has %zu", t, need, bytes);
+    if (!e->have[have_slot(e, t, layer)]) return fail(e, ASD_E_STATE, "tensor %d of layer %d was never set", t, layer);
+    int KB;
+    char* src = tensor_addr(e, t, layer, &KB);
+    if (ti.tiled) {
+        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, src, e->staging, ti.rows, ti.cols, KB, true);
+        else launch_tile<F32>(e, src, e->staging, ti.rows, ti.cols, KB, true);
+        src = e->staging;
+    }
+    CK(e, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipStreamSynchronize(e->stream));
+    return ASD_OK;
+}
+
+// host copy of the input generator's stream key and constants (pure integer / one sqrt / one pow)
+static uint64_t h_mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31; return z;
+}
+static uint64_t h_stream(uint64_t seed, uint32_t tensor, uint32_t layer) {
+    return h_mix64(h_mix64(seed + 0x9E3779B97F4A7C15ULL) ^ (((uint64_t)tensor << 32) | layer));
+}
+
+int asd_init_synthetic(asd_engine* e, uint64_t seed) {
+    if (!e) return ASD_E_INVAL;
+    const asd_config& c = e->c;
+    const uint64_t G = 0x9E3779B97F4A7C15ULL;
+    auto cst = [](double std) { return (float)(std / (65536.0 * std::sqrt(8.0 / 12.0))); };
+    auto scale = [&](int j) {
+        const uint64_t r = h_mix64(h_stream(seed, 101u, 0u) + (uint64_t)(j + 1) * G);
+        const double u = (double)(r >> 11) * (1.0 / 9007199254740992.0);
+        return std::pow(10.0, -3.0 * u);
+    };
+    auto gen = [&](int t, int layer, double std) {
+        TensorInfo ti; tensor_info(c, t, &ti);
+        int KB; char* dst = tensor_addr(e, t, layer, &KB);
+        const uint64_t st = h_stream(seed, (uint32_t)t, (uint32_t)layer);
+        const size_t frags = ti.tiled ? (size_t)(ti.rows / 16) * KB * 64 : ((size_t)ti.rows * ti.cols + e->KE - 1) / e->KE;
+        const unsigned grid = (unsigned)((frags + 255) / 256);
+        if (c.dtype == ASD_DT_BF16)
+            synth_weight_kernel<BF16><<<grid, 256, 0, e->stream>>>((uint16_t*)dst, ti.rows, ti.cols, KB, st, cst(std), ti.tiled);
+        else
+            synth_weight_kernel<F32><<<grid, 256, 0, e->stream>>>((float*)dst, ti.rows, ti.cols, KB, st, cst(std), ti.tiled);
+    };
+    auto ones = [&](float* p) { fill_f32_kernel<<<(c.d_model + 255) / 256, 256, 0, e->stream>>>(p, c.d_model, 1.f); };
+    gen(ASD_T_EMBED, 0, 0.02); gen(ASD_T_LM_HEAD, 0, 0.02); ones(e->g_final);
+    for (int l = 0; l < c.n_layers; ++l) {
+        gen(ASD_T_WQ, l, 0.02); gen(ASD_T_WK, l, 0.02); gen(ASD_T_WV, l, 0.02);
+        gen(ASD_T_WO, l, 0.02 * scale(2 * l));
+        gen(ASD_T_WG, l, 0.02); gen(ASD_T_WU, l, 0.02);
+        gen(ASD_T_WD, l, 0.02 * scale(2 * l + 1));
+        ones(e->layers[l].g_attn); ones(e->layers[l].g_mlp);
+    }
+    CK(e, hipGetLastError());
+    CK(e, hipStreamSynchronize(e->stream));
+    std::fill(e->have.begin(), e->have.end(), 1);
+    return ASD_OK;
+}
+
+int asd_load_weights_file(asd_engine* e, const char* path) {
+    if (!e) return ASD_E_INVAL;
+    if (!path) return fail(e, ASD_E_INVAL, "path is NULL");
+    FILE* f = fopen(path, "rb");
+    if (!f) return fail(e, ASD_E_IO, "cannot open %s", path);
+    char magic[8];
+    int32_t hdr[8];
+    const asd_config& c = e->c;
+    const int32_t want[8] = {c.n_layers, c.d_model, c.n_heads, c.n_kv_heads, c.head_dim, c.d_ffn, c.vocab, c.dtype};
+    if (fread(magic, 1, 8, f) != 8 || memcmp(magic, "ASDW0001", 8) || fread(hdr, 4, 8, f) != 8) {
+        fclose(f); return fail(e, ASD_E_IO, "%s: bad header", path);
+    }
+    if (memcmp(hdr, want, sizeof want)) { fclose(f); return fail(e, ASD_E_INVAL, "%s: shape differs from the engine's", path); }
+    std::vector<char> buf;
+    auto one = [&](int t, int layer) -> int {
+        TensorInfo ti; tensor_info(c, t, &ti);
+        const size_t bytes = (size_t)ti.rows * ti.cols * (ti.norm ? 4 : e->es);
+        buf.resize(bytes);
+        if (fread(buf.data(), 1, bytes, f) != bytes) return fail(e, ASD_E_IO, "%s: file too short", path);
+        return asd_set_weight(e, t, layer, buf.data(), bytes, 0);
+    };
+    int rc = ASD_OK;
+    const int gl[3] = {ASD_T_EMBED, ASD_T_FINAL_NORM, ASD_T_LM_HEAD};
+    const int ly[9] = {ASD_T_ATTN_NORM, ASD_T_WQ, ASD_T_WK, ASD_T_WV, ASD_T_WO, ASD_T_MLP_NORM, ASD_T_WG, ASD_T_WU, ASD_T_WD};
+    for (int i = 0; i < 3 && rc == ASD_OK; ++i) rc = one(gl[i], 0);
+    for (int l = 0; l < c.n_layers && rc == ASD_OK; ++l)
+        for (int i = 0; i < 9 && rc == ASD_OK; ++i) rc = one(ly[i], l);
+    fclose(f);
+    return rc;
+}
+
+int asd_set_page_table(asd_engine* e, const int32_t* table, int32_t n_pages) {
+    if (!e) return ASD_E_INVAL;
+    if (!table || n_pages != e->n_pages) return fail(e, ASD_E_INVAL, "page table must have %d entries", e->n_pages);
+    if (e->kv_len != 0) return fail(e, ASD_E_STATE, "page table can only change while the cache is empty");
+    std::vector<uint8_t> seen(n_pages, 0);
+    for (int i = 0; i < n_pages; ++i) {
+        if (table[i] < 0 || table[i] >= n_pages || seen[table[i]]) return fail(e, ASD_E_INVAL, "page table is not a permutation");
+        seen[table[i]] = 1;
+    }
+    CK(e, hipMemcpyAsync(e->page_table, table, (size_t)n_pages * 4, hipMemcpyHostToDevice, e->stream));
+    CK(e, hipStreamSynchronize(e->stream));
+    drop_graphs(e);
+    return ASD_OK;
+}
+
+int asd_reset(asd_engine* e) { if (!e) return ASD_E_INVAL; e->kv_len = 0; return ASD_OK; }
+int asd_truncate(asd_engine* e, int32_t n) {
+    if (!e) return ASD_E_INVAL;
+    if (n < 0 || n > e->kv_len) return fail(e, ASD_E_INVAL, "truncate to %d outside [0, %d]", n, e->kv_len);
+    e->kv_len = n; return ASD_OK;
+}
+int32_t asd_kv_len(const asd_engine* e) { return e ? e->kv_len : ASD_E_INVAL; }
+
+int asd_admg(const float* C, int32_t L, float alpha, int32_t m, int32_t n, int32_t use_cs, uint8_t* mask) {
+    if (!C || !mask || L < 1 || m < 0 || n < 0) return ASD_E_INVAL;
+    if (use_cs && !(alpha > 0.f && alpha < 1.f)) return ASD_E_INVAL;
+    for (int i = 0; i < L; ++i) {
+        const bool free_to_go = i < L - n;                       // rule 2 keeps the last n layers
+        const bool periodic = m > 0 && (i + 1) % m == 0;         // rule 1, layers counted from 1
+        const bool similar = use_cs && C[i] >= alpha;            // CS thresholding
+        mask[2 * i + 1] = free_to_go && periodic;
+        mask[2 * i] = free_to_go && (similar || periodic);
+    }
+    return ASD_OK;
+}
+
+// run rows [tokens, tokens+n) at the current cache end; results stay on the device
+static int forward_rows(asd_engine* e, const int32_t* tokens, int n, const uint8_t* mask, Profiler* prof) {
+    CK(e, hipMemcpyAsync(e->tokbuf, tokens, (size_t)n * 4, hipMemcpyHostToDevice, e->stream));
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, 0, 0);
+    return enqueue_forward(e, e->tokbuf, n, 0, mask, chunks_for(e->kv_len + n - 1), prof, e->kv_len + n);
+}
+
+int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t pos0, const uint8_t* mask, int32_t commit,
+                float* logits, float* cos, float* cos_rows, int32_t* argmax) {
+    if (!e) return ASD_E_INVAL;
+    if (!tokens) return fail(e, ASD_E_INVAL, "tokens is NULL");
+    if (n_rows < 1 || n_rows > e->c.max_rows) return fail(e, ASD_E_INVAL, "n_rows %d outside [1, %d]", n_rows, e->c.max_rows);
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    if (pos0 != e->kv_len) return fail(e, ASD_E_STATE, "pos0 %d differs from the cache length %d", pos0, e->kv_len);
+    if (pos0 + n_rows > capacity(e)) return fail(e, ASD_E_INVAL, "position %d exceeds the cache capacity %d", pos0 + n_rows, capacity(e));
+    int rc = check_tokens(e, tokens, n_rows);
+    if (rc) return rc;
+    const int L2 = 2 * e->c.n_layers;
+    CK(e, hipMemsetAsync(e->cos_acc, 0, (size_t)L2 * 8, e->stream));
+    rc = forward_rows(e, tokens, n_rows, mask, nullptr);
+    if (rc) return rc;
+    std::vector<double> acc(L2);
+    std::vector<float> rows((size_t)L2 * ASD_ROWS);
+    std::vector<int32_t> am(ASD_ROWS);
+    std::vector<float> lg;
+    CK(e, hipMemcpyAsync(acc.data(), e->cos_acc, (size_t)L2 * 8, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipMemcpyAsync(rows.data(), e->cos_rows, rows.size() * 4, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipMemcpyAsync(am.data(), e->argmax, ASD_ROWS * 4, hipMemcpyDeviceToHost, e->stream));
+    if (logits) {
+        lg.resize((size_t)n_rows * e->c.vocab);
+        CK(e, hipMemcpyAsync(lg.data(), e->logits, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
+    }
+    CK(e, hipStreamSynchronize(e->stream));
+    if (logits) memcpy(logits, lg.data(), lg.size() * 4);
+    for (int j = 0; j < L2; ++j) {
+        const bool skipped = mask && mask[j];
+        if (cos) cos[j] = skipped ? 1.f : (float)(acc[j] / n_rows);
+        if (cos_rows) for (int r = 0; r < n_rows; ++r) cos_rows[(size_t)r * L2 + j] = skipped ? 1.f : rows[(size_t)j * ASD_ROWS + r];
+    }
+    if (argmax) memcpy(argmax, am.data(), (size_t)n_rows * 4);
+    if (commit) e->kv_len = pos0 + n_rows;
+    return ASD_OK;
+}
+
+int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits) {
+    if (!e) return ASD_E_INVAL;
+    if (!tokens || !first_token) return fail(e, ASD_E_INVAL, "tokens or first_token is NULL");
+    if (n < 1 || n > capacity(e)) return fail(e, ASD_E_INVAL, "prompt length %d outside [1, %d]", n, capacity(e));
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    int rc = check_tokens(e, tokens, n);
+    if (rc) return rc;
+    const int L2 = 2 * e->c.n_layers;
+    e->kv_len = 0; e->acs_valid = false;
+    CK(e, hipMemsetAsync(e->cos_acc, 0, (size_t)L2 * 8, e->stream));
+    int rows = 0;
+    for (int p = 0; p < n; p += rows) {
+        rows = n - p < e->c.max_rows ? n - p : e->c.max_rows;
+        rc = forward_rows(e, tokens + p, rows, nullptr, nullptr);
+        if (rc) return rc;
+        e->kv_len = p + rows;
+    }
+    std::vector<double> acc(L2);
+    int32_t am[ASD_ROWS];
+    CK(e, hipMemcpyAsync(acc.data(), e->cos_acc, (size_t)L2 * 8, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipMemcpyAsync(am, e->argmax, ASD_ROWS * 4, hipMemcpyDeviceToHost, e->stream));
+    std::vector<float> lg;
+    if (last_logits) {
+        lg.resize(e->c.vocab);
+        CK(e, hipMemcpyAsync(lg.data(), e->logits + (size_t)(rows - 1) * e->c.vocab, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
+    }
+    CK(e, hipStreamSynchronize(e->stream));
+    for (int j = 0; j < L2; ++j) e->acs[j] = (float)(acc[j] / n);
+    e->acs_valid = true;
+    if (cos_out) memcpy(cos_out, e->acs.data(), (size_t)L2 * 4);
+    if (last_logits) memcpy(last_logits, lg.data(), lg.size() * 4);
+    *first_token = am[rows - 1];
+    return ASD_OK;
+}
+
+// one draft/verify/accept cycle, enqueue only: kk draft steps with the masked model, then a (kk+1)-row verify
+static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx) {
+    for (int j = 0; j < kk; ++j) {
+        int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx);
+        if (rc) return rc;
+        draft_next_kernel<<<1, 1, 0, e->stream>>>(e->argmax, e->tokbuf, j);
+    }
+    int rc = enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx);
+    if (rc) return rc;
+    accept_kernel<<<1, 1, 0, e->stream>>>(e->st, e->tokbuf, e->argmax, kk, e->out_tokens);
+    return ASD_OK;
+}
+
+int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_params* p, int32_t* out, asd_gen_stats* stats,
+               uint8_t* mask_used) {
+    if (!e) return ASD_E_INVAL;
+    if (!p || !out) return fail(e, ASD_E_INVAL, "params or out_tokens is NULL");
+    if (n_more < 1) return fail(e, ASD_E_INVAL, "n_more must be >= 1");
+    const int k = p->draft_len, L = e->c.n_layers;
+    if (k < 0 || k + 1 > e->c.max_rows) return fail(e, ASD_E_INVAL, "draft_len %d outside [0, %d]", k, e->c.max_rows - 1);
+    if (last_token < 0 || last_token >= e->c.vocab) return fail(e, ASD_E_INVAL, "last_token outside the vocabulary");
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    if (e->kv_len + n_more + k > capacity(e))
+        return fail(e, ASD_E_INVAL, "cache capacity %d too small for %d + %d + %d positions", capacity(e), e->kv_len, n_more, k);
+    std::vector<uint8_t> mask(2 * (size_t)L, 0);
+    if (p->mask_mode == 1) {
+        if (!p->fixed_mask) return fail(e, ASD_E_INVAL, "mask_mode 1 needs fixed_mask");
+        for (int j = 0; j < 2 * L; ++j) mask[j] = p->fixed_mask[j] ? 1 : 0;
+    } else if (p->mask_mode == 0) {
+        if (!e->acs_valid) return fail(e, ASD_E_STATE, "mask_mode 0 needs the ACS of a preceding asd_prefill");
+        std::vector<float> ca(L);
+        for (int l = 0; l < L; ++l) ca[l] = e->acs[2 * l];
+        if (asd_admg(ca.data(), L, p->alpha, p->m, p->n, p->use_cs, mask.data()))
+            return fail(e, ASD_E_INVAL, "invalid ADMG parameters (alpha in (0,1), m >= 0, n >= 0)");
+    } else {
+        return fail(e, ASD_E_INVAL, "mask_mode must be 0 or 1");
+    }
+    if (mask != e->graph_mask) { drop_graphs(e); e->graph_mask = mask; }
+
+    const auto t0 = std::chrono::steady_clock::now();
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, n_more, 1);
+    set_token_kernel<<<1, 1, 0, e->stream>>>(e->tokbuf, last_token);
+    int emitted = 0;
+    while (emitted < n_more) {
+        const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
+        const int nc = chunks_for(e->kv_len + kk);
+        int rc = ASD_OK;
+        if (p->use_graphs) {
+            const std::vector<int> key{kk, nc};
+            auto it = e->graphs.find(key);
+            if (it == e->graphs.end()) {
+                hipGraph_t g = nullptr;
+                hipGraphExec_t ge = nullptr;
+                CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
+                rc = enqueue_cycle(e, kk, mask.data(), nc, e->kv_len + kk + 1);
+                hipError_t r2 = hipStreamEndCapture(e->stream, &g);
+                if (rc) { if (g) hipGraphDestroy(g); return rc; }
+                if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(r2));
+                r2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+                hipGraphDestroy(g);
+                if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(r2));
+                it = e->graphs.emplace(key, ge).first;
+            }
+            CK(e, hipGraphLaunch(it->second, e->stream));
+        } else {
+            rc = enqueue_cycle(e, kk, mask.data(), nc, e->kv_len + kk + 1);
+            if (rc) return rc;
+        }
+        CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
+        CK(e, hipStreamSynchronize(e->stream));
+        if (e->h_st->emitted <= emitted) return fail(e, ASD_E_STATE, "decode cycle made no progress");
+        emitted = e->h_st->emitted;
+        e->kv_len = e->h_st->pos;
+    }
+    CK(e, hipMemcpyAsync(out, e->out_tokens, (size_t)n_more * 4, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipStreamSynchronize(e->stream));
+    const auto t1 = std::chrono::steady_clock::now();
+    if (stats) {
+        stats->cycles = e->h_st->cycles; stats->drafted = e->h_st->drafted; stats->accepted = e->h_st->accepted;
+        stats->emitted = emitted; stats->ms_prefill = 0.0;
+        stats->ms_decode = std::chrono::duration<double, std::milli>(t1 - t0).count();
+    }
+    if (mask_used) memcpy(mask_used, mask.data(), mask.size());
+    return ASD_OK;
+}
+
+int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t n_new, const asd_gen_params* p, int32_t* out,
+                 asd_gen_stats* stats, uint8_t* mask_used) {
+    if (!e) return ASD_E_INVAL;
+    if (!p || !out) return fail(e, ASD_E_INVAL, "params or out_tokens is NULL");
+    if (n_new < 1) return fail(e, ASD_E_INVAL, "n_new must be >= 1");
+    if (p->draft_len + 1 > e->c.max_rows) return fail(e, ASD_E_INVAL, "draft_len %d outside [0, %d]", p->draft_len, e->c.max_rows - 1);
+    if (p->mask_mode == 1 && !p->fixed_mask) return fail(e, ASD_E_INVAL, "mask_mode 1 needs fixed_mask");
+    if (p->draft_len < 0 || n_prompt < 1 || n_prompt + n_new + p->draft_len > capacity(e))
+        return fail(e, ASD_E_INVAL, "prompt %d + new %d + draft %d exceeds the cache capacity %d", n_prompt, n_new, p->draft_len, capacity(e));
+    const auto t0 = std::chrono::steady_clock::now();
+    int32_t t1 = 0;
+    int rc = asd_prefill(e, prompt, n_prompt, &t1, nullptr, nullptr);
+    if (rc) return rc;
+    const double ms_pre = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    out[0] = t1;
+    asd_gen_stats st{};
+    if (n_new > 1) {
+        rc = asd_decode(e, t1, n_new - 1, p, out + 1, &st, mask_used);
+        if (rc) return rc;
+    } else if (mask_used) {
+        memset(mask_used, 0, 2 * (size_t)e->c.n_layers);
+    }
+    if (stats) { *stats = st; stats->emitted = st.emitted + 1; stats->ms_prefill = ms_pre; }
+    return ASD_OK;
+}
+
+// ------------------------------------------------------------------ measurement helpers
+static int bench_tokens(asd_engine* e, int n_rows) {
+    int32_t t[ASD_ROWS];
+    for (int i = 0; i < n_rows; ++i) t[i] = (int32_t)((1 + 7919 * i) % e->c.vocab);
+    CK(e, hipMemcpyAsync(e->tokbuf, t, (size_t)n_rows * 4, hipMemcpyHostToDevice, e->stream));
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, 0, 0);
+    CK(e, hipStreamSynchronize(e->stream));
+    return ASD_OK;
+}
+
+static int bench_checks(asd_engine* e, int n_rows) {
+    if (n_rows < 1 || n_rows > e->c.max_rows) return fail(e, ASD_E_INVAL, "n_rows %d outside [1, %d]", n_rows, e->c.max_rows);
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    if (e->kv_len + n_rows > capacity(e)) return fail(e, ASD_E_INVAL, "no room for %d rows after %d cached positions", n_rows, e->kv_len);
+    return ASD_OK;
+}
+
+int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* mask, int32_t reps, int32_t use_graph, double* ms_avg, double* bytes) {
+    if (!e) return ASD_E_INVAL;
+    if (!ms_avg || reps < 1) return fail(e, ASD_E_INVAL, "ms_avg is NULL or reps < 1");
+    int rc = bench_checks(e, n_rows);
+    if (rc) return rc;
+    rc = bench_tokens(e, n_rows);
+    if (rc) return rc;
+    const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
+    hipGraphExec_t ge = nullptr;
+    if (use_graph) {
+        hipGraph_t g = nullptr;
+        CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
+        rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);
+        hipError_t r2 = hipStreamEndCapture(e->stream, &g);
+        if (rc) { if (g) hipGraphDestroy(g); return rc; }
+        if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(r2));
+        r2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+        hipGraphDestroy(g);
+        if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(r2));
+    }
+    auto once = [&]() -> int {
+        if (ge) { CK(e, hipGraphLaunch(ge, e->stream)); return ASD_OK; }
+        return enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);
+    };
+    rc = once();                                   // warm-up
+    hipEvent_t a = nullptr, b = nullptr;
+    if (!rc) { hipEventCreate(&a); hipEventCreate(&b); hipEventRecord(a, e->stream); }
+    for (int i = 0; i < reps && !rc; ++i) rc = once();
+    float ms = 0.f;
+    if (!rc) {
+        hipEventRecord(b, e->stream);
+        hipError_t r2 = hipEventSynchronize(b);
+        if (r2 == hipSuccess) r2 = hipEventElapsedTime(&ms, a, b);
+        if (r2 != hipSuccess) rc = fail(e, ASD_E_HIP, "event timing: %s", hipGetErrorString(r2));
+    }
+    if (a) hipEventDestroy(a);
+    if (b) hipEventDestroy(b);
+    if (ge) hipGraphExecDestroy(ge);
+    if (rc) return rc;
+    *ms_avg = (double)ms / reps;
+    if (bytes) {
+        double cls[ASD_K_COUNT];
+        pass_bytes(e, mask, ctx, cls);
+        *bytes = 0.0;
+        for (int i = 0; i < ASD_K_COUNT; ++i) *bytes += cls[i];
+    }
+    return ASD_OK;
+}
+
+int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* mask, asd_kernel_times* out) {
+    if (!e) return ASD_E_INVAL;
+    if (!out) return fail(e, ASD_E_INVAL, "out is NULL");
+    int rc = bench_checks(e, n_rows);
+    if (rc) return rc;
+    rc = bench_tokens(e, n_rows);
+    if (rc) return rc;
+    const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
+    rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);     // warm-up
+    if (rc) return rc;
+    Profiler pf;
+    rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, &pf, ctx);
+    hipError_t r2 = hipStreamSynchronize(e->stream);
+    memset(out, 0, sizeof *out);
+    if (!rc && r2 == hipSuccess) {
+        for (size_t i = 0; i < pf.cls.size(); ++i) {
+            float ms = 0.f;
+            hipEventElapsedTime(&ms, pf.ev[2 * i], pf.ev[2 * i + 1]);
+            out->ms[pf.cls[i]] += ms; out->launches[pf.cls[i]] += 1; out->bytes[pf.cls[i]] += pf.bytes[i];
+        }
+        float tot = 0.f;
+        if (!pf.ev.empty()) hipEventElapsedTime(&tot, pf.ev.front(), pf.ev.back());
+        out->ms_total = tot;
+    }
+    for (hipEvent_t ev : pf.ev) hipEventDestroy(ev);
+    if (rc) return rc;
+    if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "profiled pass: %s", hipGetErrorString(r2));
+    return ASD_OK;
+}
+
+int asd_copy_bench(asd_engine* e, size_t nbytes, int32_t reps, double* ms_avg) {
+    if (!e) return ASD_E_INVAL;
+    if (!ms_avg || reps < 1 || nbytes < 16 || nbytes % 16) return fail(e, ASD_E_INVAL, "nbytes must be a positive multiple of 16, reps >= 1");
+    // source: the start of the arena (weights are only read); destination: the staging region
+    if (nbytes > e->staging_bytes || nbytes > (size_t)(e->staging - e->arena)) return fail(e, ASD_E_INVAL, "nbytes exceeds the scratch region (%zu)", e->staging_bytes);
+    hipEvent_t a, b;
+    hipEventCreate(&a); hipEventCreate(&b);
+    copy_kernel<<<2048, 256, 0, e->stream>>>((const u32x4*)e->arena, (u32x4*)e->staging, nbytes / 16);
+    hipEventRecord(a, e->stream);
+    for (int i = 0; i < reps; ++i) copy_kernel<<<2048, 256, 0, e->stream>>>((const u32x4*)e->arena, (u32x4*)e->staging, nbytes / 16);
+    hipEventRecord(b, e->stream);
+    hipError_t r = hipEventSynchronize(b);
+    float ms = 0.f;
+    if (r == hipSuccess) r = hipEventElapsedTime(&ms, a, b);
+    hipEventDestroy(a); hipEventDestroy(b);
+    if (r != hipSuccess) return fail(e, ASD_E_HIP, "copy benchmark: %s", hipGetErrorString(r));
+    *ms_avg = (double)ms / reps;
+    return ASD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,309 @@
+// Weight-streaming small-M GEMM: out[m][n] = sum_k X[m][k] * W[n][k], m < 16, with fused epilogues.
+//
+// One workgroup owns a few 16-row tiles of W; its NW waves split K into contiguous
+// slices, each wave streaming its slice of every tile (1 KiB per load instruction,
+// U steps in flight) through the matrix cores with the 16 activation rows as the
+// other operand.  The slices are then summed through LDS in wave order, so every
+// output element has one fixed reduction order that does not depend on how many of
+// the 16 rows are in use: row i of a (k+1)-row verification pass and the same row
+// run alone give identical bits.  The grid never depends on the row count either.
+//
+// Epilogues (what a decoder sublayer needs right after the contraction):
+//   EPI_QKV  RMSNorm scale, rotary embedding, q -> tiled q buffer, k/v -> paged KV cache
+//   EPI_RES  y = x + out (residual add), tiled copy of y*gain for the next norm, and the
+//            cosine tap: per-workgroup partials of <x,y> and ||y||^2, finished by the
+//            last workgroup to arrive (fixed order) into cos(x,y) and the new ||y||^2
+//   EPI_GU   RMSNorm scale, silu(gate) * up -> tiled activation
+//   EPI_LM   RMSNorm scale, logits, per-workgroup argmax, finished by the last workgroup
+#pragma once
+#include "asd_common.h"
+
+enum { EPI_QKV = 0, EPI_RES = 1, EPI_GU = 2, EPI_LM = 3 };
+
+struct AmaxPart { float v; int32_t i; };
+
+struct GemmArgs {
+    const u32x4* W;          // tiled weights
+    const u32x4* W2;         // EPI_GU: tiled up-projection (W is the gate projection)
+    const u32x4* X;          // tiled activations
+    int32_t n_tiles;         // output features / 16
+    int32_t KB;              // k-blocks
+    int32_t M;               // rows in use
+    float* ssq;              // [16] ||residual row||^2 : RMSNorm scale (QKV, GU, LM); cosine tap in/out (RES)
+    float inv_d, eps;
+    // EPI_RES
+    float* xres;             // [16][d] fp32 residual stream, updated in place
+    void* xb;                // tiled copy of y * g_next in storage type
+    const float* g_next;     // gain of the norm that reads y next
+    float* part;             // [grid][16][2]
+    unsigned* counter;       // arrival counter (returns to 0)
+    float* cos_rows;         // [16] cosine of this sublayer per row
+    double* cos_acc;         // running sum over rows of this sublayer's cosine
+    int32_t d;
+    // EPI_QKV
+    const DevState* st;
+    int32_t pos_off;
+    const float* rope;       // [max_seq][h/2][2] cos, sin
+    void* q;                 // [n_h][h/KE][16][KE]
+    void* kv;                // this layer's cache pages
+    const int32_t* page_table;
+    int32_t n_h, n_kv, h, page_tokens;
+    // EPI_GU
+    void* hmid;
+    // EPI_LM
+    float* logits;           // [16][V]
+    int32_t V;
+    AmaxPart* amax_part;     // [grid][16]
+    int32_t* argmax;         // [16]
+};
+
+// Stream the k-blocks [kb0, kb1) of NA weight tiles and the matching activation fragments.
+template <class T, int NA, int U>
+__device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int kb0, int kb1,
+                                           f32x4 (&acc)[NA]) {
+    u32x4 a[U][NA], b[U];
+    const int n = kb1 - kb0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u < n) {
+            const size_t o = (size_t)(kb0 + u) * ASD_WAVE;
+            b[u] = X[o];
+#pragma unroll
+            for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o);
+        }
+    }
+    for (int i = 0; i < n; i += U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (i + u < n) {
+#pragma unroll
+                for (int s = 0; s < NA; ++s) mma16<T>(acc[s], a[u][s], b[u]);
+                const int nx = i + u + U;
+                if (nx < n) {
+                    const size_t o = (size_t)(kb0 + nx) * ASD_WAVE;
+                    b[u] = X[o];
+#pragma unroll
+                    for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o);
+                }
+            }
+        }
+    }
+}
+
+template <class T, int EPI, int TN, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
+    constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
+    constexpr int NT = NW * 64;
+    constexpr bool kLast = (EPI == EPI_RES || EPI == EPI_LM);
+    __shared__ f32x4 red[NW][NA][64];
+    __shared__ float epi_a[kLast ? NA * 256 : 1];
+    __shared__ float epi_b[EPI == EPI_RES ? NA * 256 : 1];
+    __shared__ float fin_a[kLast ? NT : 1];
+    __shared__ float fin_b[kLast ? NT : 1];
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, bid = blockIdx.x;
+
+    int tile[NA];
+    bool tval[NA];
+    if constexpr (EPI == EPI_QKV) {
+        static_assert(EPI != EPI_QKV || TN == 2, "rotary pairs need the two half-head tiles together");
+        const int hpt = a.h / 16, half = hpt / 2;
+        tile[0] = (bid / half) * hpt + (bid % half);
+        tile[1] = tile[0] + half;
+        tval[0] = tval[1] = true;
+    } else {
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
+            tile[t] = bid * TN + t;
+            tval[t] = tile[t] < a.n_tiles;
+            if constexpr (EPI == EPI_GU) { tile[TN + t] = tile[t]; tval[TN + t] = tval[t]; }
+        }
+    }
+
+    const u32x4* A[NA];
+#pragma unroll
+    for (int s = 0; s < NA; ++s) {
+        const u32x4* base = (EPI == EPI_GU && s >= TN) ? a.W2 : a.W;
+        A[s] = base + (size_t)(tval[s] ? tile[s] : 0) * a.KB * ASD_WAVE + lane;
+    }
+    const int kb0 = (int)((long)w * a.KB / NW), kb1 = (int)((long)(w + 1) * a.KB / NW);
+
+    f32x4 acc[NA];
+#pragma unroll
+    for (int s = 0; s < NA; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    stream_mma<T, NA, U>(A, a.X + lane, kb0, kb1, acc);
+
+#pragma unroll
+    for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
+    __syncthreads();
+
+    // element e of a 16x16 tile: row m = e / 16, local feature nl = e % 16 (consecutive threads -> consecutive features)
+    auto gather = [&](int s, int m, int nl) -> float {
+        const int src = (nl >> 2) * 16 + m, r = nl & 3;
+        float v = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) v += red[ww][s][src][r];
+        return v;
+    };
+
+    if constexpr (EPI == EPI_QKV) {
+        using E = typename T::elem;
+        const int hpt = a.h / 16, half = hpt / 2, head = bid / half, j = bid % half;
+        for (int e = tid; e < 256; e += NT) {
+            const int m = e >> 4, nl = e & 15;
+            if (m >= a.M) continue;
+            const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
+            float v0 = gather(0, m, nl) * rs, v1 = gather(1, m, nl) * rs;
+            const int i = j * 16 + nl, hh = a.h / 2;
+            const int pos = a.st->pos + a.pos_off + m;
+            if (head < a.n_h + a.n_kv) {
+                const float c = a.rope[((size_t)pos * hh + i) * 2], sn = a.rope[((size_t)pos * hh + i) * 2 + 1];
+                const float o0 = v0 * c - v1 * sn, o1 = v1 * c + v0 * sn;
+                v0 = o0; v1 = o1;
+            }
+            if (head < a.n_h) {
+                E* q = (E*)a.q + (size_t)head * a.h * ASD_ROWS;
+                q[act_index<T>(i, m)] = T::from_f32(v0);
+                q[act_index<T>(i + hh, m)] = T::from_f32(v1);
+            } else {
+                const bool isk = head < a.n_h + a.n_kv;
+                const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
+                const int PT = a.page_tokens, page = a.page_table[pos / PT], slot = pos % PT;
+                E* base = (E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * a.h;
+                if (isk) {                       // K[slot][h]
+                    base[(size_t)slot * a.h + i] = T::from_f32(v0);
+                    base[(size_t)slot * a.h + i + hh] = T::from_f32(v1);
+                } else {                         // V transposed: [h][slot]
+                    base += (size_t)PT * a.h;
+                    base[(size_t)i * PT + slot] = T::from_f32(v0);
+                    base[(size_t)(i + hh) * PT + slot] = T::from_f32(v1);
+                }
+            }
+        }
+        return;
+    }
+
+    if constexpr (EPI == EPI_GU) {
+        using E = typename T::elem;
+        for (int e = tid; e < TN * 256; e += NT) {
+            const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+            if (m >= a.M || !tval[s]) continue;
+            const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
+            const float g = gather(s, m, nl) * rs, u = gather(TN + s, m, nl) * rs;
+            const float act = g / (1.f + __expf(-g)) * u;
+            ((E*)a.hmid)[act_index<T>(tile[s] * 16 + nl, m)] = T::from_f32(act);
+        }
+        return;
+    }
+
+    if constexpr (EPI == EPI_RES) {
+        using E = typename T::elem;
+        for (int e = tid; e < NA * 256; e += NT) {
+            const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+            float pxy = 0.f, pyy = 0.f;
+            if (m < a.M && tval[s]) {
+                const int n = tile[s] * 16 + nl;
+                const float x = a.xres[(size_t)m * a.d + n];
+                const float y = x + gather(s, m, nl);
+                a.xres[(size_t)m * a.d + n] = y;
+                ((E*)a.xb)[act_index<T>(n, m)] = T::from_f32(y * a.g_next[n]);
+                pxy = x * y; pyy = y * y;
+            }
+            epi_a[e] = pxy; epi_b[e] = pyy;
+        }
+        __syncthreads();
+        if (tid < 16) {
+            float sxy = 0.f, syy = 0.f;
+            for (int s = 0; s < NA; ++s)
+                for (int nl = 0; nl < 16; ++nl) { sxy += epi_a[s * 256 + tid * 16 + nl]; syy += epi_b[s * 256 + tid * 16 + nl]; }
+            a.part[((size_t)bid * 16 + tid) * 2] = sxy;
+            a.part[((size_t)bid * 16 + tid) * 2 + 1] = syy;
+        }
+    }
+
+    if constexpr (EPI == EPI_LM) {
+        for (int e = tid; e < NA * 256; e += NT) {
+            const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+            float lg = -INFINITY;
+            if (m < a.M && tval[s]) {
+                const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
+                lg = gather(s, m, nl) * rs;
+                a.logits[(size_t)m * a.V + tile[s] * 16 + nl] = lg;
+            }
+            epi_a[e] = lg;
+        }
+        __syncthreads();
+        if (tid < 16) {
+            AmaxPart best{-INFINITY, 0x7fffffff};
+            for (int s = 0; s < NA; ++s)
+                for (int nl = 0; nl < 16; ++nl) {
+                    const float v = epi_a[s * 256 + tid * 16 + nl];
+                    if (v > best.v) { best.v = v; best.i = tile[s] * 16 + nl; }
+                }
+            a.amax_part[(size_t)bid * 16 + tid] = best;
+        }
+    }
+
+    if constexpr (kLast) {
+        // The last workgroup to arrive finishes the cross-workgroup reduction in a fixed order.
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned old = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (old == gridDim.x - 1);
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();
+        constexpr int J = NT / 16;
+        const int m = tid & 15, j = tid >> 4, P = gridDim.x;
+        if constexpr (EPI == EPI_RES) {
+            float sxy = 0.f, syy = 0.f;
+            for (int p = j; p < P; p += J) {
+                sxy += __builtin_nontemporal_load(&a.part[((size_t)p * 16 + m) * 2]);
+                syy += __builtin_nontemporal_load(&a.part[((size_t)p * 16 + m) * 2 + 1]);
+            }
+            fin_a[tid] = sxy; fin_b[tid] = syy;
+            __syncthreads();
+            if (tid < 16) {
+                float xy = 0.f, yy = 0.f;
+                for (int jj = 0; jj < J; ++jj) { xy += fin_a[jj * 16 + tid]; yy += fin_b[jj * 16 + tid]; }
+                float c = 0.f;
+                if (tid < a.M) {
+                    const float xx = a.ssq[tid];
+                    c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
+                    c = fminf(1.f, fmaxf(-1.f, c));
+                    a.ssq[tid] = yy;
+                    a.cos_rows[tid] = c;
+                }
+                fin_a[tid] = c;
+            }
+            __syncthreads();
+            if (tid == 0) {
+                double sum = 0.0;
+                for (int r = 0; r < a.M; ++r) sum += (double)fin_a[r];
+                *a.cos_acc += sum;
+                __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        } else {
+            AmaxPart best{-INFINITY, 0x7fffffff};
+            for (int p = j; p < P; p += J) {
+                const AmaxPart c = a.amax_part[(size_t)p * 16 + m];
+                if (c.v > best.v || (c.v == best.v && c.i < best.i)) best = c;
+            }
+            fin_a[tid] = best.v; fin_b[tid] = __int_as_float(best.i);
+            __syncthreads();
+            if (tid < 16) {
+                AmaxPart b2{-INFINITY, 0x7fffffff};
+                for (int jj = 0; jj < J; ++jj) {
+                    const float v = fin_a[jj * 16 + tid];
+                    const int i = __float_as_int(fin_b[jj * 16 + tid]);
+                    if (v > b2.v || (v == b2.v && i < b2.i)) { b2.v = v; b2.i = i; }
+                }
+                if (tid < a.M) a.argmax[tid] = b2.i;
+            }
+            if (tid == 0) __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}

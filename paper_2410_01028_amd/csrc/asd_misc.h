@@ -1,0 +1,148 @@
+// Small kernels around the contractions: embedding gather, accept/rollback, decoding state,
+// rotary table, weight re-tiling, the on-device synthetic weight generator, a plain copy.
+#pragma once
+#include "asd_common.h"
+
+// ---------------------------------------------------------------- embedding + first norm statistics
+// One workgroup per row: x = E[token], ||x||^2, and the tiled copy x * gain for the first kept norm.
+template <class T>
+__global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
+                                                    const float* g_first, float* xres, void* xb, float* ssq) {
+    using El = typename T::elem;
+    __shared__ float red[256];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const El* row = E + (size_t)tokens[m] * d;
+    float ss = 0.f;
+    for (int i = tid; i < d; i += 256) {
+        const float x = T::to_f32(row[i]);
+        xres[(size_t)m * d + i] = x;
+        ((El*)xb)[act_index<T>(i, m)] = T::from_f32(x * g_first[i]);
+        ss += x * x;
+    }
+    red[tid] = ss;
+    __syncthreads();
+    for (int s = 128; s > 0; s >>= 1) {
+        if (tid < s) red[tid] += red[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) ssq[m] = red[0];
+}
+
+// ---------------------------------------------------------------- decoding state
+__global__ void set_state_kernel(DevState* st, int pos, int emitted, int target, int reset_counts) {
+    st->pos = pos; st->emitted = emitted; st->target = target;
+    if (reset_counts) { st->cycles = 0; st->drafted = 0; st->accepted = 0; }
+}
+__global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok; }
+
+// Draft step j: the drafted token becomes row j+1 of the coming verification pass.
+__global__ void draft_next_kernel(const int32_t* argmax, int32_t* tokbuf, int j) { tokbuf[j + 1] = argmax[0]; }
+
+// Accept / rollback after a verification pass over rows [last, d_1..d_kk]: g_i = full model's
+// choice after row i.  a = length of the longest prefix with d_{i+1} == g_i; emit d_1..d_a, g_a;
+// the cache keeps pos + a + 1 positions; g_a is the next cycle's first row.
+__global__ void accept_kernel(DevState* st, int32_t* tokbuf, const int32_t* argmax, int kk, int32_t* out) {
+    int a = 0;
+    while (a < kk && tokbuf[a + 1] == argmax[a]) ++a;
+    int e = st->emitted;
+    for (int j = 1; j <= a && e < st->target; ++j) out[e++] = tokbuf[j];
+    if (e < st->target) out[e++] = argmax[a];
+    st->emitted = e;
+    st->pos += a + 1;
+    st->cycles += 1; st->drafted += kk; st->accepted += a;
+    tokbuf[0] = argmax[a];
+}
+
+// ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double
+__global__ void rope_table_kernel(float* tab, int max_seq, int half, double theta) {
+    const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)max_seq * half) return;
+    const int pos = (int)(idx / half), i = (int)(idx % half);
+    const double ang = (double)pos * pow(theta, -(double)i / (double)half);
+    tab[idx * 2] = (float)cos(ang);
+    tab[idx * 2 + 1] = (float)sin(ang);
+}
+
+__global__ void iota_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = i;
+}
+
+// ---------------------------------------------------------------- weight tiling
+// dst fragment index f = (tile*KB + kb)*64 + lane; lane = 16g + r -> row 16*tile + r, k = kb*4KE + g*KE .. +KE
+template <class T>
+__global__ void tile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, int KB) {
+    constexpr int KE = T::KE;
+    const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= (size_t)(N / 16) * KB * 64) return;
+    const int lane = (int)(f & 63);
+    const size_t tk = f >> 6;
+    const int kb = (int)(tk % KB), tile = (int)(tk / KB);
+    const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+#pragma unroll
+    for (int j = 0; j < KE; ++j) dst[f * KE + j] = (k0 + j < K) ? src[(size_t)row * K + k0 + j] : (typename T::elem)0;
+}
+template <class T>
+__global__ void untile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, int KB) {
+    constexpr int KE = T::KE;
+    const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= (size_t)(N / 16) * KB * 64) return;
+    const int lane = (int)(f & 63);
+    const size_t tk = f >> 6;
+    const int kb = (int)(tk % KB), tile = (int)(tk / KB);
+    const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+#pragma unroll
+    for (int j = 0; j < KE; ++j) if (k0 + j < K) dst[(size_t)row * K + k0 + j] = src[f * KE + j];
+}
+
+// ---------------------------------------------------------------- synthetic weights (counter based)
+// Same recipe as the host input generator: element i of a tensor draws mix64(stream + (c+1)*GOLD)
+// for c = 2i, 2i+1; the sum of the eight 16-bit fields minus 262140, times one fp32 constant,
+// rounded once to the storage type.
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31; return z;
+}
+__device__ __forceinline__ int field_sum(uint64_t r) {
+    return (int)(r & 0xFFFF) + (int)((r >> 16) & 0xFFFF) + (int)((r >> 32) & 0xFFFF) + (int)(r >> 48);
+}
+__device__ __forceinline__ float synth_value(uint64_t stream, uint64_t i, float cst) {
+    const uint64_t G = 0x9E3779B97F4A7C15ULL;
+    const int s = field_sum(mix64(stream + (2 * i + 1) * G)) + field_sum(mix64(stream + (2 * i + 2) * G)) - 262140;
+    return (float)s * cst;
+}
+// tiled == 0: dst row-major [N][K];  tiled != 0: dst in the tiled weight layout (K padded with zeros)
+template <class T>
+__global__ void synth_weight_kernel(typename T::elem* dst, int N, int K, int KB, uint64_t stream, float cst, int tiled) {
+    constexpr int KE = T::KE;
+    const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tiled) {
+        if (f >= (size_t)(N / 16) * KB * 64) return;
+        const int lane = (int)(f & 63);
+        const size_t tk = f >> 6;
+        const int kb = (int)(tk % KB), tile = (int)(tk / KB);
+        const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+#pragma unroll
+        for (int j = 0; j < KE; ++j)
+            dst[f * KE + j] = (k0 + j < K) ? T::from_f32(synth_value(stream, (uint64_t)row * K + k0 + j, cst))
+                                           : (typename T::elem)0;
+    } else {
+        if (f >= ((size_t)N * K + KE - 1) / KE) return;
+#pragma unroll
+        for (int j = 0; j < KE; ++j) {
+            const size_t i = f * KE + j;
+            if (i < (size_t)N * K) dst[i] = T::from_f32(synth_value(stream, i, cst));
+        }
+    }
+}
+__global__ void fill_f32_kernel(float* p, size_t n, float v) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------- plain copy (byte-counter calibration, achievable HBM rate)
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* src, u32x4* dst, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
