@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the adaptive self-speculative decoding engine on one MI355X.
+
+One timed step = one greedy decode of the workload's new tokens after its prompt has been
+processed (the prompt pass runs once, untimed: the hot path is the draft / verify loop; the
+prompt's KV cache and all weights are resident in HBM when the timed region starts).
+`value` is plain greedy decoding (draft length 0: every token is one single-row pass of the
+verification kernels), the figure the HBM-roofline target is stated for; the speculative
+runs (ADMG mask from the prompt's ACS, and the all-keep bracket) are reported beside it with
+their acceptance, which on random-init weights is an artefact of the init.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
+
+
+def cpu_baseline(shape, seed, n_prompt=2, n_decode=6):
+    """The oracle as it stands, timed on this host: a short prompt plus a few greedy tokens."""
+    import asd_inputs as si
+    import oracle
+    t0 = time.time()
+    orc = oracle.Oracle(shape, n_prompt + n_decode + 1)
+    for t, l, a in si.all_tensors(shape, seed):
+        orc.set_weight(t, l, a)
+    t_load = time.time() - t0
+    prompt = si.prompt(seed, n_prompt, shape.vocab)
+    t0 = time.time()
+    orc.forward(prompt, 0, want_logits=False)
+    t_prompt = time.time() - t0
+    tok = np.array([1], np.int32)
+    t0 = time.time()
+    for i in range(n_decode):
+        r = orc.forward(tok, n_prompt + i, want_logits=False)
+        tok = r["argmax"][:1].copy()
+    t_dec = time.time() - t0
+    orc.close()
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n_decode / t_dec, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{shape.name} shape, full depth and width: {n_prompt}-token prompt then {n_decode} plain greedy "
+                      f"tokens (decode phase timed: {t_dec:.1f} s; prompt {t_prompt:.1f} s; weight generation "
+                      f"{t_load:.1f} s not counted)"}
+
+
+def read_traffic(path):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, or None."""
+    try:
+        for ln in open(path):
+            if ln.startswith("TRAFFIC_BYTES_PER_LAUNCH"):
+                return float(ln.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b", help="tiny | 7b | 13b | 7b-long | 70b")
+    ap.add_argument("--draft-len", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    import asd_inputs as si
+    import paper_2410_01028_amd as asd
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    shape = si.SHAPES[args.workload]
+    seed = 0
+    k = args.draft_len if args.draft_len is not None else shape.draft_len
+    P, N = shape.prompt_len, shape.n_new
+    max_seq = P + N + 16
+    eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens=256))
+    eng.init_synthetic(seed)
+    prompt = si.prompt(seed, P, shape.vocab)
+    L2 = 2 * shape.n_layers
+
+    t0 = time.time()
+    first, acs, _ = eng.prefill(prompt)
+    torch.cuda.synchronize()
+    t_prefill = time.time() - t0
+
+    def decode_step(draft_len, **kw):
+        eng.truncate(P)
+        return eng.decode(first, N - 1, draft_len, **kw)
+
+    for _ in range(args.warmup):
+        decode_step(0)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for _ in range(args.steps):
+        plain, st_plain, _ = decode_step(0)
+    torch.cuda.synchronize()
+    total = time.time() - t0
+    ms_per_step = total / args.steps * 1e3
+    value = (N - 1) * args.steps / total
+
+    out = {
+        "metric": "greedy decode tokens/s at batch 1", "value": round(value, 2), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if shape.dtype else "f32",
+        "data": "synthetic (seeded random-init weights, uniform-random prompt; stands in for Llama-2 checkpoints and "
+                "CNN/DM, XSum, HumanEval prompts)",
+        "config": {"workload": f"{shape.name}: {shape.n_layers} layers, d_model {shape.d_model}, {shape.n_heads} heads "
+                               f"({shape.n_kv_heads} KV) x {shape.head_dim}, FFN {shape.d_ffn}, vocab {shape.vocab}; "
+                               f"batch 1, prompt {P}, {N} greedy tokens",
+                   "mode": "plain greedy (draft length 0), decode phase after the prompt pass", "draft_len_spec": k},
+        "prefill_ms": round(t_prefill * 1e3, 1),
+        "e2e_tokens_per_s": round(N / (t_prefill + ms_per_step / 1e3), 2),
+    }
+
+    # ---- roofline of the dominant kernel (gate/up projection GEMM), HIP events on the engine's stream
+    reps = 5
+    acc = {}
+    for _ in range(reps):
+        pf = eng.profile_forward(1)
+        for name, v in pf.items():
+            if name == "ms_total":
+                continue
+            a = acc.setdefault(name, {"ms": 0.0, "launches": 0, "bytes": 0.0})
+            a["ms"] += v["ms"]; a["launches"] += v["launches"]; a["bytes"] += v["bytes"]
+    gu = acc["gateup"]
+    avg_ms = gu["ms"] / gu["launches"]
+    bytes_per_launch = gu["bytes"] / gu["launches"]
+    achieved = bytes_per_launch / avg_ms / 1e6
+    out["roofline"] = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": round(achieved / HBM_PEAK_GBS, 4),
+                       "traffic": read_traffic(os.path.join(ROOT, "profiles", f"gemm_gateup_{shape.name}_hbm_traffic.txt")),
+                       "kernel": "gemm_kernel<BF16, EPI_GU> (gate/up projection + SiLU*mul)",
+                       "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(avg_ms * 1e3, 2)}
+    out["kernels"] = {n: {"avg_us": round(v["ms"] / v["launches"] * 1e3, 2),
+                          "GBps": round(v["bytes"] / max(v["ms"], 1e-12) / 1e6, 1) if v["bytes"] else None}
+                      for n, v in acc.items() if v["launches"]}
+
+    if not args.no_extras:
+        eng.truncate(P)
+        ms1, by1 = eng.time_pass(1, None, 30, True)
+        msv, byv = eng.time_pass(k + 1, None, 30, True)
+        mask = asd.admg(acs[0::2], 0.985, 3, 2)
+        msd, byd = eng.time_pass(1, mask, 30, True)
+        out["passes"] = {
+            "full_1row": {"ms": round(ms1, 4), "GBps": round(by1 / ms1 / 1e6, 1), "frac_peak": round(by1 / ms1 / 1e6 / HBM_PEAK_GBS, 4)},
+            f"verify_{k + 1}rows": {"ms": round(msv, 4), "GBps": round(byv / msv / 1e6, 1), "frac_peak": round(byv / msv / 1e6 / HBM_PEAK_GBS, 4)},
+            "draft_admg_1row": {"ms": round(msd, 4), "GBps": round(byd / msd / 1e6, 1), "frac_peak": round(byd / msd / 1e6 / HBM_PEAK_GBS, 4),
+                                "kept_attn": int(shape.n_layers - mask[0::2].sum()), "kept_mlp": int(shape.n_layers - mask[1::2].sum())},
+        }
+        cp = eng.copy_bench(192 << 20, 10)
+        out["copy_kernel_GBps"] = round(2 * (192 << 20) / cp / 1e6, 1)
+        spec = {}
+        for name, kw in (("admg_a0.985_m3_n2", dict(alpha=0.985, m=3, n=2)),
+                         ("all_keep", dict(fixed_mask=np.zeros(L2, np.uint8)))):
+            decode_step(k, **kw)
+            torch.cuda.synchronize()
+            t0 = time.time()
+            toks, st, used = decode_step(k, **kw)
+            dt = time.time() - t0
+            spec[name] = {"tokens_per_s": round((N - 1) / dt, 2), "cycles": st["cycles"], "drafted": st["drafted"],
+                          "accepted": st["accepted"], "tokens_equal_plain": bool(np.array_equal(toks, plain))}
+        out["speculative"] = spec
+
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+
+    if not args.no_cpu_baseline:
+        if shape.name == "tiny":
+            out["cpu_baseline"] = cpu_baseline(shape, seed, 8, 24)
+        else:
+            out["cpu_baseline"] = cpu_baseline(shape, seed, 2, 6)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -330,7 +330,7 @@ struct Prof {
 };
 
 int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
-                    Profiler* profiler, int ctx_for_bytes) {
+                    Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0) {
     const asd_config& c = e->c;
     Prof pr{profiler, e->stream};
     double cls_bytes[ASD_K_COUNT];
@@ -352,7 +352,14 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
     base.xres = e->xres; base.xb = e->xb; base.part = e->part; base.d = c.d_model;
     base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.q = e->q; base.page_table = e->page_table;
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
-    base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part; base.argmax = e->argmax;
+    base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part;
+    // the cosine tap still open: partials of the last residual-add kernel and where its cosine goes
+    int open_P = 0, open_sub = -1;
+    auto consume = [&](GemmArgs& g) {
+        g.part_in = e->part; g.P_in = open_P;
+        if (open_P > 0) { g.fin_cos_rows = e->cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = e->cos_acc + open_sub; }
+        open_P = 0;
+    };
 
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& ly = e->layers[l];
@@ -360,6 +367,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
             GemmArgs a = base;
             a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.n_tiles = e->qkv_tiles; a.KB = e->KBd;
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
+            consume(a);
             pr.begin(ASD_K_QKV, cls_bytes[ASD_K_QKV] / L);
             if (!launch_gemm<EPI_QKV>(e, e->g_qkv, a)) return fail(e, ASD_E_STATE, "no QKV kernel for this shape");
             pr.end();
@@ -378,8 +386,8 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
 
             GemmArgs o = base;
             o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.n_tiles = c.d_model / 16; o.KB = e->KBq;
-            o.g_next = next_gain(e, mask, 2 * l); o.counter = e->counters;
-            o.cos_rows = e->cos_rows + (size_t)(2 * l) * ASD_ROWS; o.cos_acc = e->cos_acc + 2 * l;
+            o.g_next = next_gain(e, mask, 2 * l);
+            open_P = e->g_o.grid; open_sub = 2 * l;
             pr.begin(ASD_K_OPROJ, cls_bytes[ASD_K_OPROJ] / L);
             if (!launch_gemm<EPI_RES>(e, e->g_o, o)) return fail(e, ASD_E_STATE, "no O-projection kernel for this shape");
             pr.end();
@@ -388,14 +396,15 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
             GemmArgs a = base;
             a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb;
             a.n_tiles = c.d_ffn / 16; a.KB = e->KBd;
+            consume(a);
             pr.begin(ASD_K_GATEUP, cls_bytes[ASD_K_GATEUP] / L);
             if (!launch_gemm<EPI_GU>(e, e->g_gu, a)) return fail(e, ASD_E_STATE, "no gate/up kernel for this shape");
             pr.end();
 
             GemmArgs dn = base;
             dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.n_tiles = c.d_model / 16; dn.KB = e->KBf;
-            dn.g_next = next_gain(e, mask, 2 * l + 1); dn.counter = e->counters + 1;
-            dn.cos_rows = e->cos_rows + (size_t)(2 * l + 1) * ASD_ROWS; dn.cos_acc = e->cos_acc + 2 * l + 1;
+            dn.g_next = next_gain(e, mask, 2 * l + 1);
+            open_P = e->g_down.grid; open_sub = 2 * l + 1;
             pr.begin(ASD_K_DOWN, cls_bytes[ASD_K_DOWN] / L);
             if (!launch_gemm<EPI_RES>(e, e->g_down, dn)) return fail(e, ASD_E_STATE, "no down-projection kernel for this shape");
             pr.end();
@@ -403,9 +412,13 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
     }
     GemmArgs lm = base;
     lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.n_tiles = c.vocab / 16; lm.KB = e->KBd;
-    lm.counter = e->counters + 2;
+    consume(lm);
     pr.begin(ASD_K_LMHEAD, cls_bytes[ASD_K_LMHEAD]);
     if (!launch_gemm<EPI_LM>(e, e->g_lm, lm)) return fail(e, ASD_E_STATE, "no LM-head kernel for this shape");
+    pr.end();
+    pr.begin(ASD_K_FINISH, 0);
+    finish_kernel<<<1, 256, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg, e->st,
+                                            e->tokbuf, e->out_tokens);
     pr.end();
     hipError_t r = hipGetLastError();
     if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
@@ -752,14 +765,10 @@ int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_
 // one draft/verify/accept cycle, enqueue only: kk draft steps with the masked model, then a (kk+1)-row verify
 static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx) {
     for (int j = 0; j < kk; ++j) {
-        int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx);
+        int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_DRAFT, j);
         if (rc) return rc;
-        draft_next_kernel<<<1, 1, 0, e->stream>>>(e->argmax, e->tokbuf, j);
     }
-    int rc = enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx);
-    if (rc) return rc;
-    accept_kernel<<<1, 1, 0, e->stream>>>(e->st, e->tokbuf, e->argmax, kk, e->out_tokens);
-    return ASD_OK;
+    return enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, kk);
 }
 
 int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_params* p, int32_t* out, asd_gen_stats* stats,

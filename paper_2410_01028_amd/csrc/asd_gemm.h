@@ -11,10 +11,14 @@
 // Epilogues (what a decoder sublayer needs right after the contraction):
 //   EPI_QKV  RMSNorm scale, rotary embedding, q -> tiled q buffer, k/v -> paged KV cache
 //   EPI_RES  y = x + out (residual add), tiled copy of y*gain for the next norm, and the
-//            cosine tap: per-workgroup partials of <x,y> and ||y||^2, finished by the
-//            last workgroup to arrive (fixed order) into cos(x,y) and the new ||y||^2
+//            cosine tap: per-workgroup partials of <x,y> and ||y||^2
 //   EPI_GU   RMSNorm scale, silu(gate) * up -> tiled activation
-//   EPI_LM   RMSNorm scale, logits, per-workgroup argmax, finished by the last workgroup
+//   EPI_LM   RMSNorm scale, logits, per-workgroup argmax candidates
+// The three epilogues that need the RMSNorm scale are always the next launch after an
+// EPI_RES kernel (or after the embedding): every workgroup sums that kernel's partials in
+// the same fixed order to get ||y||^2, and workgroup 0 also finishes the producing
+// sublayer's cosine, cos = <x,y> / sqrt(||x||^2 ||y||^2).  No workgroup ever waits for
+// another inside a kernel, so no device-scope fence (and no L2 write-back) is needed.
 #pragma once
 #include "asd_common.h"
 
@@ -29,16 +33,18 @@ struct GemmArgs {
     int32_t n_tiles;         // output features / 16
     int32_t KB;              // k-blocks
     int32_t M;               // rows in use
-    float* ssq;              // [16] ||residual row||^2 : RMSNorm scale (QKV, GU, LM); cosine tap in/out (RES)
+    float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap (or the embedding)
     float inv_d, eps;
+    // input side of QKV / GU / LM: partials of the kernel that produced the residual (P_in = 0: use ssq as is)
+    const float* part_in;    // [P_in][16][2]
+    int32_t P_in;
+    float* fin_cos_rows;     // [16] cosine per row of the producing sublayer (written by workgroup 0)
+    double* fin_cos_acc;     // its running sum over rows
     // EPI_RES
     float* xres;             // [16][d] fp32 residual stream, updated in place
     void* xb;                // tiled copy of y * g_next in storage type
     const float* g_next;     // gain of the norm that reads y next
-    float* part;             // [grid][16][2]
-    unsigned* counter;       // arrival counter (returns to 0)
-    float* cos_rows;         // [16] cosine of this sublayer per row
-    double* cos_acc;         // running sum over rows of this sublayer's cosine
+    float* part;             // [grid][16][2] partial <x,y>, ||y||^2 of this workgroup's features
     int32_t d;
     // EPI_QKV
     const DevState* st;
@@ -53,8 +59,7 @@ struct GemmArgs {
     // EPI_LM
     float* logits;           // [16][V]
     int32_t V;
-    AmaxPart* amax_part;     // [grid][16]
-    int32_t* argmax;         // [16]
+    AmaxPart* amax_part;     // [grid][16] best (logit, index) among this workgroup's features
 };
 
 // Stream the k-blocks [kb0, kb1) of NA weight tiles and the matching activation fragments.
@@ -94,13 +99,13 @@ template <class T, int EPI, int TN, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
     constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     constexpr int NT = NW * 64;
-    constexpr bool kLast = (EPI == EPI_RES || EPI == EPI_LM);
+    constexpr bool kNormed = (EPI != EPI_RES);          // input went through RMSNorm: needs the row scale
     __shared__ f32x4 red[NW][NA][64];
-    __shared__ float epi_a[kLast ? NA * 256 : 1];
+    __shared__ float epi_a[(EPI == EPI_RES || EPI == EPI_LM) ? NA * 256 : 1];
     __shared__ float epi_b[EPI == EPI_RES ? NA * 256 : 1];
-    __shared__ float fin_a[kLast ? NT : 1];
-    __shared__ float fin_b[kLast ? NT : 1];
-    __shared__ int is_last;
+    __shared__ float fin_a[kNormed ? NT : 1];
+    __shared__ float fin_b[kNormed ? NT : 1];
+    __shared__ float rscale[16];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, bid = blockIdx.x;
 
@@ -136,7 +141,47 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
 
 #pragma unroll
     for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
-    __syncthreads();
+
+    if constexpr (kNormed) {
+        // ||y||^2 per row from the producing kernel's partials (same order in every workgroup)
+        constexpr int J = NT / 16;
+        const int m = tid & 15, j = tid >> 4;
+        float syy = 0.f, sxy = 0.f;
+        if (m < a.M) {
+            for (int p = j; p < a.P_in; p += J) {
+                syy += a.part_in[((size_t)p * 16 + m) * 2 + 1];
+                if (bid == 0) sxy += a.part_in[((size_t)p * 16 + m) * 2];
+            }
+        }
+        fin_a[tid] = syy; fin_b[tid] = sxy;
+        __syncthreads();
+        if (tid < 16) {
+            float yy = 0.f, xy = 0.f;
+            if (a.P_in > 0) {
+                for (int jj = 0; jj < J; ++jj) { yy += fin_a[jj * 16 + tid]; xy += fin_b[jj * 16 + tid]; }
+            } else if (tid < a.M) {
+                yy = a.ssq[tid];
+            }
+            rscale[tid] = rsqrtf(yy * a.inv_d + a.eps);
+            float c = 0.f;
+            if (bid == 0 && a.P_in > 0 && tid < a.M) {
+                const float xx = a.ssq[tid];
+                c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
+                c = fminf(1.f, fmaxf(-1.f, c));
+                a.ssq[tid] = yy;
+                a.fin_cos_rows[tid] = c;
+            }
+            fin_a[tid] = c;
+        }
+        __syncthreads();
+        if (bid == 0 && a.P_in > 0 && tid == 0) {
+            double sum = 0.0;
+            for (int r = 0; r < a.M; ++r) sum += (double)fin_a[r];
+            *a.fin_cos_acc += sum;
+        }
+    } else {
+        __syncthreads();
+    }
 
     // element e of a 16x16 tile: row m = e / 16, local feature nl = e % 16 (consecutive threads -> consecutive features)
     auto gather = [&](int s, int m, int nl) -> float {
@@ -153,7 +198,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
         for (int e = tid; e < 256; e += NT) {
             const int m = e >> 4, nl = e & 15;
             if (m >= a.M) continue;
-            const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
+            const float rs = rscale[m];
             float v0 = gather(0, m, nl) * rs, v1 = gather(1, m, nl) * rs;
             const int i = j * 16 + nl, hh = a.h / 2;
             const int pos = a.st->pos + a.pos_off + m;
@@ -189,7 +234,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
         for (int e = tid; e < TN * 256; e += NT) {
             const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
             if (m >= a.M || !tval[s]) continue;
-            const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
+            const float rs = rscale[m];
             const float g = gather(s, m, nl) * rs, u = gather(TN + s, m, nl) * rs;
             const float act = g / (1.f + __expf(-g)) * u;
             ((E*)a.hmid)[act_index<T>(tile[s] * 16 + nl, m)] = T::from_f32(act);
@@ -227,8 +272,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
             float lg = -INFINITY;
             if (m < a.M && tval[s]) {
-                const float rs = rsqrtf(a.ssq[m] * a.inv_d + a.eps);
-                lg = gather(s, m, nl) * rs;
+                lg = gather(s, m, nl) * rscale[m];
                 a.logits[(size_t)m * a.V + tile[s] * 16 + nl] = lg;
             }
             epi_a[e] = lg;
@@ -242,68 +286,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                     if (v > best.v) { best.v = v; best.i = tile[s] * 16 + nl; }
                 }
             a.amax_part[(size_t)bid * 16 + tid] = best;
-        }
-    }
-
-    if constexpr (kLast) {
-        // The last workgroup to arrive finishes the cross-workgroup reduction in a fixed order.
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned old = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            is_last = (old == gridDim.x - 1);
-        }
-        __syncthreads();
-        if (!is_last) return;
-        __threadfence();
-        constexpr int J = NT / 16;
-        const int m = tid & 15, j = tid >> 4, P = gridDim.x;
-        if constexpr (EPI == EPI_RES) {
-            float sxy = 0.f, syy = 0.f;
-            for (int p = j; p < P; p += J) {
-                sxy += __builtin_nontemporal_load(&a.part[((size_t)p * 16 + m) * 2]);
-                syy += __builtin_nontemporal_load(&a.part[((size_t)p * 16 + m) * 2 + 1]);
-            }
-            fin_a[tid] = sxy; fin_b[tid] = syy;
-            __syncthreads();
-            if (tid < 16) {
-                float xy = 0.f, yy = 0.f;
-                for (int jj = 0; jj < J; ++jj) { xy += fin_a[jj * 16 + tid]; yy += fin_b[jj * 16 + tid]; }
-                float c = 0.f;
-                if (tid < a.M) {
-                    const float xx = a.ssq[tid];
-                    c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
-                    c = fminf(1.f, fmaxf(-1.f, c));
-                    a.ssq[tid] = yy;
-                    a.cos_rows[tid] = c;
-                }
-                fin_a[tid] = c;
-            }
-            __syncthreads();
-            if (tid == 0) {
-                double sum = 0.0;
-                for (int r = 0; r < a.M; ++r) sum += (double)fin_a[r];
-                *a.cos_acc += sum;
-                __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        } else {
-            AmaxPart best{-INFINITY, 0x7fffffff};
-            for (int p = j; p < P; p += J) {
-                const AmaxPart c = a.amax_part[(size_t)p * 16 + m];
-                if (c.v > best.v || (c.v == best.v && c.i < best.i)) best = c;
-            }
-            fin_a[tid] = best.v; fin_b[tid] = __int_as_float(best.i);
-            __syncthreads();
-            if (tid < 16) {
-                AmaxPart b2{-INFINITY, 0x7fffffff};
-                for (int jj = 0; jj < J; ++jj) {
-                    const float v = fin_a[jj * 16 + tid];
-                    const int i = __float_as_int(fin_b[jj * 16 + tid]);
-                    if (v > b2.v || (v == b2.v && i < b2.i)) { b2.v = v; b2.i = i; }
-                }
-                if (tid < a.M) a.argmax[tid] = b2.i;
-            }
-            if (tid == 0) __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
 }

@@ -35,22 +35,53 @@ __global__ void set_state_kernel(DevState* st, int pos, int emitted, int target,
 }
 __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok; }
 
-// Draft step j: the drafted token becomes row j+1 of the coming verification pass.
-__global__ void draft_next_kernel(const int32_t* argmax, int32_t* tokbuf, int j) { tokbuf[j + 1] = argmax[0]; }
-
-// Accept / rollback after a verification pass over rows [last, d_1..d_kk]: g_i = full model's
-// choice after row i.  a = length of the longest prefix with d_{i+1} == g_i; emit d_1..d_a, g_a;
-// the cache keeps pos + a + 1 positions; g_a is the next cycle's first row.
-__global__ void accept_kernel(DevState* st, int32_t* tokbuf, const int32_t* argmax, int kk, int32_t* out) {
-    int a = 0;
-    while (a < kk && tokbuf[a + 1] == argmax[a]) ++a;
-    int e = st->emitted;
-    for (int j = 1; j <= a && e < st->target; ++j) out[e++] = tokbuf[j];
-    if (e < st->target) out[e++] = argmax[a];
-    st->emitted = e;
-    st->pos += a + 1;
-    st->cycles += 1; st->drafted += kk; st->accepted += a;
-    tokbuf[0] = argmax[a];
+// After the LM head: pick each row's greedy token from the per-workgroup candidates (largest
+// logit, lowest index on ties), then, by mode,
+//   FIN_NONE    nothing more;
+//   FIN_DRAFT   draft step j: the drafted token becomes row j+1 of the coming verification pass;
+//   FIN_ACCEPT  accept / rollback after a verification pass over rows [last, d_1..d_kk], g_i = the
+//               full model's choice after row i: a = length of the longest prefix with
+//               d_{i+1} == g_i; emit d_1..d_a, g_a; the cache keeps pos + a + 1 positions; g_a is
+//               the next cycle's first row.
+enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
+struct AmaxCand { float v; int32_t i; };
+__global__ __launch_bounds__(256) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+                                                     DevState* st, int32_t* tokbuf, int32_t* out) {
+    __shared__ float bv[256];
+    __shared__ int bi[256];
+    const int tid = threadIdx.x, m = tid & 15, j = tid >> 4;
+    float v = -INFINITY; int idx = 0x7fffffff;
+    if (m < M)
+        for (int p = j; p < P; p += 16) {
+            const AmaxCand c = cand[(size_t)p * 16 + m];
+            if (c.v > v || (c.v == v && c.i < idx)) { v = c.v; idx = c.i; }
+        }
+    bv[tid] = v; bi[tid] = idx;
+    __syncthreads();
+    if (tid < 16 && tid < M) {
+        for (int jj = 0; jj < 16; ++jj) {
+            const float cv = bv[jj * 16 + tid]; const int ci = bi[jj * 16 + tid];
+            if (cv > v || (cv == v && ci < idx)) { v = cv; idx = ci; }
+        }
+        argmax[tid] = idx;
+        bi[tid] = idx;
+    }
+    __syncthreads();
+    if (tid != 0) return;
+    if (mode == FIN_DRAFT) {
+        tokbuf[j_or_kk + 1] = bi[0];
+    } else if (mode == FIN_ACCEPT) {
+        const int kk = j_or_kk;
+        int a = 0;
+        while (a < kk && tokbuf[a + 1] == bi[a]) ++a;
+        int e = st->emitted;
+        for (int q = 1; q <= a && e < st->target; ++q) out[e++] = tokbuf[q];
+        if (e < st->target) out[e++] = bi[a];
+        st->emitted = e;
+        st->pos += a + 1;
+        st->cycles += 1; st->drafted += kk; st->accepted += a;
+        tokbuf[0] = bi[a];
+    }
 }
 
 // ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double
