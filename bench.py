@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--draft-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras")
+    ap.add_argument("--n-new", type=int, default=None, help="override the workload's number of new tokens (profiling runs)")
+    ap.add_argument("--copy-only-extra", action="store_true", help="with --no-extras: still run the plain copy kernel (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -87,7 +89,7 @@ def main():
     shape = si.SHAPES[args.workload]
     seed = 0
     k = args.draft_len if args.draft_len is not None else shape.draft_len
-    P, N = shape.prompt_len, shape.n_new
+    P, N = shape.prompt_len, (args.n_new or shape.n_new)
     max_seq = P + N + 16
     eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens=256))
     eng.init_synthetic(seed)
@@ -151,6 +153,9 @@ def main():
                           "GBps": round(v["bytes"] / max(v["ms"], 1e-12) / 1e6, 1) if v["bytes"] else None}
                       for n, v in acc.items() if v["launches"]}
 
+    if args.no_extras and args.copy_only_extra:
+        cp = eng.copy_bench(192 << 20, 10)
+        out["copy_kernel_GBps"] = round(2 * (192 << 20) / cp / 1e6, 1)
     if not args.no_extras:
         eng.truncate(P)
         ms1, by1 = eng.time_pass(1, None, 30, True)
