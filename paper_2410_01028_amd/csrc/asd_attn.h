@@ -1,10 +1,15 @@
-// Decode attention over the paged KV cache for up to 16 query rows (split-KV + fixed-order merge).
+// Decode attention over the paged KV cache for up to 16 query rows (split-KV + fixed-order merges).
 //
-// Work item = (query head, chunk of 64 keys at absolute positions [64c, 64c+64)), one wave.
-// Scores S[key][row] and the output O[dim][row] are both matrix-core products with the 16
-// query rows as columns, so a row's result never depends on how many rows the call has;
-// chunk boundaries are absolute, and the merge walks the chunks in ascending order.  A row
-// at position p sees keys 0..p (causal among the rows of the call as well).
+// Work item = (query head, chunk of 64 keys at absolute positions [64c, 64c+64)), one wave, so
+// that a head's chunks spread over many compute units (one unit alone cannot pull a head's
+// K/V fast enough).  Scores S[key][row] and the output O[dim][row] are both matrix-core
+// products with the 16 query rows as columns, so a row's result never depends on how many
+// rows the call has; chunk boundaries are absolute.  The wave that finishes a head's last
+// outstanding chunk merges that head's chunk partials in ascending chunk order.  Partials and
+// the arrival counter are exchanged with device-scope relaxed atomic stores / loads (served
+// past the non-coherent per-XCD L2), ordered by waiting for the stores to complete before the
+// counter is bumped; no cache-wide fence is involved.
+// A row at position p sees keys 0..p (causal among the rows of the call as well).
 //
 // Cache page layout per (page, kv head): K[page_tokens][h] then V transposed [h][page_tokens],
 // which makes the fragments of both products contiguous 16-byte loads:
@@ -16,6 +21,22 @@
 #pragma once
 #include "asd_common.h"
 
+#define ATT_RB 2                           // rows per merge round
+#define ATT_CB 16                          // chunk partials requested per merge round
+#define ATT_NCL 4                          // chunk statistics per lane: up to 256 chunks (16K positions) per head
+
+// device-scope coherent scalar accesses (relaxed atomics: served past the per-XCD L2)
+__device__ __forceinline__ void coherent_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 coherent_load2(const float* p) {          // p 8-byte aligned
+    const uint64_t u = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return float2{__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32))};
+}
+
 struct AttnArgs {
     const void* q;            // [n_h][h/KE][16][KE]
     const void* kv;           // this layer's cache pages
@@ -25,9 +46,10 @@ struct AttnArgs {
     int32_t n_h, n_kv, h, page_tokens;
     int32_t nc_stride;        // chunks per head in the partial buffers
     float scale;              // 1/sqrt(h)
-    float* o_part;            // [n_h][nc_stride][16][h] unnormalised partial outputs
-    float2* ml_part;          // [n_h][nc_stride][16] (chunk max, chunk sum)
-    void* out;                // tiled activation [n_h*h] (merge)
+    float* o_part;            // [n_h][nc_stride][16][h] unnormalised chunk outputs
+    float* ml_part;           // [n_h][nc_stride][16][2] (chunk max, chunk sum)
+    unsigned* arrivals;       // [n_h] chunks finished per head (returns to 0)
+    void* out;                // tiled activation [n_h*h]
 };
 
 // key (0..63, relative to the chunk) held by score tile kt, tile row r
@@ -38,7 +60,7 @@ template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
 template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 
 template <class T, int H>
-__global__ __launch_bounds__(64) void attn_partial_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
     using E = typename T::elem;
     constexpr int KE = T::KE;
     constexpr int HS = H / (4 * KE);            // fragment steps over the head dimension
@@ -46,8 +68,8 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const AttnArgs a) {
     constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
     const int c = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     const int g = lane >> 4, m = lane & 15, r = lane & 15;
-    const int pos0 = a.st->pos + a.pos_off;
-    if (c * ASD_CHUNK > pos0 + a.M - 1) return;          // no row of this call sees this chunk
+    const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
+    if (c * ASD_CHUNK > last) return;                    // no row of this call sees this chunk
     const int kvh = head / (a.n_h / a.n_kv);
     const int PT = a.page_tokens;
     const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
@@ -70,7 +92,7 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const AttnArgs a) {
             mma16<T>(s[kt], kf, qf[hs]);
         }
     }
-    // ---- V^T fragments (independent of the scores: issue early)
+    // ---- V^T fragments (independent of the scores: issued early)
     u32x4 vf[HT][KST];
 #pragma unroll
     for (int ht = 0; ht < HT; ++ht)
@@ -129,28 +151,88 @@ __global__ __launch_bounds__(64) void attn_partial_kernel(const AttnArgs a) {
         f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KST; ++ks) mma16<T>(o, vf[ht][ks], pf[ks]);
-        if (m < a.M) *(f32x4*)(op + ht * 16 + 4 * g) = o;
+        if (m < a.M) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) coherent_store(op + ht * 16 + 4 * g + j, o[j]);
+        }
     }
-    if (g == 0 && m < a.M) a.ml_part[((size_t)head * a.nc_stride + c) * ASD_ROWS + m] = float2{mx, l};
-}
+    float* mlp = a.ml_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * 2;
+    if (g == 0 && m < a.M) { coherent_store(mlp, mx); coherent_store(mlp + 1, l); }
 
-// Merge the chunk partials of one (head, row) in ascending chunk order and write the tiled activation.
-template <class T, int H>
-__global__ __launch_bounds__(H) void attn_merge_kernel(const AttnArgs a) {
-    using E = typename T::elem;
-    const int head = blockIdx.x, m = blockIdx.y, hd = threadIdx.x;
-    const int pos = a.st->pos + a.pos_off + m;
-    const int nc = pos / ASD_CHUNK + 1;
-    const float2* ml = a.ml_part + (size_t)head * a.nc_stride * ASD_ROWS + m;
-    float gmax = -INFINITY;
-    for (int c = 0; c < nc; ++c) gmax = fmaxf(gmax, ml[(size_t)c * ASD_ROWS].x);
-    float L = 0.f, o = 0.f;
-    const float* op = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + m) * H + hd;
-    for (int c = 0; c < nc; ++c) {
-        const float2 v = ml[(size_t)c * ASD_ROWS];
-        const float w = __expf(v.x - gmax);
-        L += v.y * w;
-        o += op[(size_t)c * ASD_ROWS * H] * w;
+    // ---- arrival: the wave that completes the head's last chunk merges
+    const int n_chunks = last / ASD_CHUNK + 1;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's partial stores have completed
+    unsigned old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __shfl(old, 0);
+    if ((int)old != n_chunks - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- merge, ATT_RB rows per round: chunk statistics with one chunk per lane, outputs with two head
+    //      dims per lane; all loads of a round are requested before any is used
+    const bool mine = 2 * lane < H;
+    for (int m0 = 0; m0 < a.M; m0 += ATT_RB) {
+        float2 st[ATT_RB][ATT_NCL], v[ATT_RB][ATT_CB];
+        int nc[ATT_RB];
+#pragma unroll
+        for (int rb = 0; rb < ATT_RB; ++rb) {
+            const int mm = m0 + rb;
+            nc[rb] = mm < a.M ? (pos0 + mm) / ASD_CHUNK + 1 : 0;
+            const float* ml = a.ml_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * 2;
+            const float* opm = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * H + 2 * lane;
+#pragma unroll
+            for (int q = 0; q < ATT_NCL; ++q) {
+                const int cc = lane + 64 * q;
+                st[rb][q] = cc < nc[rb] ? coherent_load2(ml + (size_t)cc * ASD_ROWS * 2) : float2{-INFINITY, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < ATT_CB; ++u)
+                v[rb][u] = (mine && u < nc[rb]) ? coherent_load2(opm + (size_t)u * ASD_ROWS * H) : float2{0.f, 0.f};
+        }
+#pragma unroll
+        for (int rb = 0; rb < ATT_RB; ++rb) {
+            const int mm = m0 + rb;
+            if (mm >= a.M) break;
+            float gmax = -INFINITY;
+#pragma unroll
+            for (int q = 0; q < ATT_NCL; ++q) gmax = fmaxf(gmax, st[rb][q].x);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) gmax = fmaxf(gmax, __shfl_xor(gmax, o));
+            float wq[ATT_NCL], L = 0.f;
+#pragma unroll
+            for (int q = 0; q < ATT_NCL; ++q) { wq[q] = __expf(st[rb][q].x - gmax); L += st[rb][q].y * wq[q]; }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) L += __shfl_xor(L, o);
+            auto weight = [&](int cc) {
+                float wgt = 0.f;
+#pragma unroll
+                for (int q = 0; q < ATT_NCL; ++q) { const float t = __shfl(wq[q], cc & 63); if ((cc >> 6) == q) wgt = t; }
+                return wgt;
+            };
+            float2 acc = float2{0.f, 0.f};
+#pragma unroll
+            for (int u = 0; u < ATT_CB; ++u) {                 // ascending chunk order
+                const float wgt = weight(u);
+                if (u < nc[rb]) { acc.x += v[rb][u].x * wgt; acc.y += v[rb][u].y * wgt; }
+            }
+            const float* opm = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * H + 2 * lane;
+            for (int c0 = ATT_CB; c0 < nc[rb]; c0 += 8) {      // contexts beyond ATT_CB chunks: 8 more per trip
+                float2 x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    x[u] = (mine && c0 + u < nc[rb]) ? coherent_load2(opm + (size_t)(c0 + u) * ASD_ROWS * H) : float2{0.f, 0.f};
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float wgt = weight(c0 + u);
+                    if (c0 + u < nc[rb]) { acc.x += x[u].x * wgt; acc.y += x[u].y * wgt; }
+                }
+            }
+            if (mine) {
+                ((E*)a.out)[act_index<T>(head * H + 2 * lane, mm)] = T::from_f32(acc.x / L);
+                ((E*)a.out)[act_index<T>(head * H + 2 * lane + 1, mm)] = T::from_f32(acc.y / L);
+            }
+        }
     }
-    ((E*)a.out)[act_index<T>(head * H + hd, m)] = T::from_f32(o / L);
 }

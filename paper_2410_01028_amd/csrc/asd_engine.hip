@@ -11,6 +11,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <string>
@@ -20,7 +21,7 @@ namespace {
 
 thread_local std::string g_create_error;
 
-struct GemmCfg { int TN, NW, grid; };
+struct GemmCfg { int TN, NW, grid, kmajor, kint; };
 
 struct Layer {
     char *wqkv, *wo, *wg, *wu, *wd;
@@ -53,7 +54,8 @@ struct asd_engine {
     int32_t* page_table;
     // workspace
     float *xres, *ssq, *part, *cos_rows, *logits, *o_part, *rope;
-    float2* ml_part;
+    float* ml_part;
+    unsigned* arrivals;
     void *xb, *q, *attn_out, *hmid;
     unsigned* counters;
     double* cos_acc;
@@ -113,24 +115,39 @@ bool config_ok(const asd_config* c, std::string* why) {
     return true;
 }
 
-GemmCfg pick_cfg(int epi, int tiles, int KB) {
-    GemmCfg g;
-    if (epi == EPI_QKV) g.TN = 2;
-    else if (epi == EPI_LM) g.TN = 2;
-    else if (epi == EPI_GU) g.TN = tiles <= 2048 ? 1 : 2;
-    else g.TN = tiles <= 1024 ? 1 : 2;
-    g.grid = (epi == EPI_QKV) ? tiles / 2 : (tiles + g.TN - 1) / g.TN;
+// Launch shape and weight layout per GEMM class.  Tile-major keeps a tile's K range contiguous; k-major
+// keeps the fragments of all tiles for one k-block contiguous (with interleaved k-blocks per wave the
+// whole grid then sweeps one contiguous window).  Chosen by measurement on the 7B shape; ASD_TUNE
+// (development aid) overrides, e.g. ASD_TUNE="qkv=1,8,1,1;o=1,16,0,0" (TN, NW, k-major, interleave).
+GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
+    GemmCfg g{};
+    g.TN = 1;
+    if (epi == EPI_LM) g.TN = 2;
+    if (epi == EPI_GU && tiles > 2048) g.TN = 2;
+    if (epi == EPI_RES && tiles > 1024) g.TN = 2;
+    g.kmajor = (cls == ASD_K_QKV || cls == ASD_K_DOWN || cls == ASD_K_LMHEAD) ? 1 : 0;
+    g.kint = g.kmajor;
     const int maxnw = (epi == EPI_RES) ? 16 : 8;
     g.NW = 4;
     for (int nw = maxnw; nw > 4; nw /= 2)
-        if ((long)g.grid * nw <= 8192 && KB / nw >= 4) { g.NW = nw; break; }
+        if ((long)((tiles + g.TN - 1) / g.TN) * nw <= 8192 && KB / nw >= 4) { g.NW = nw; break; }
+    static const char* names[] = {"", "qkv", "", "", "o", "gu", "down", "lm"};
+    if (const char* env = getenv("ASD_TUNE")) {
+        std::string e(env), key = std::string(names[cls]) + "=";
+        size_t pos = (";" + e).find(";" + key);
+        if (pos != std::string::npos) {
+            int tn, nw, km, ki;
+            if (sscanf(e.c_str() + pos + key.size(), "%d,%d,%d,%d", &tn, &nw, &km, &ki) == 4) { g.TN = tn; g.NW = nw; g.kmajor = km; g.kint = ki; }
+        }
+    }
+    g.grid = (tiles + g.TN - 1) / g.TN;
     return g;
 }
 
 struct Plan {
     size_t embed, lm, g_final, layer0, layer_stride, wqkv, wo, wg, wu, wd, g_attn, g_mlp;
     size_t kv, kv_layer, page_table;
-    size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
+    size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
         argmax, tokbuf, out_tokens, st, staging, staging_bytes, total;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
@@ -148,11 +165,11 @@ Plan make_plan(const asd_config& c) {
     p.n_pages = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
     p.nc_stride = p.n_pages * c.page_tokens / ASD_CHUNK;
     p.qkv_tiles = (qd + 2 * kvd) / 16;
-    p.g_qkv = pick_cfg(EPI_QKV, p.qkv_tiles, p.KBd);
-    p.g_o = pick_cfg(EPI_RES, c.d_model / 16, p.KBq);
-    p.g_gu = pick_cfg(EPI_GU, c.d_ffn / 16, p.KBd);
-    p.g_down = pick_cfg(EPI_RES, c.d_model / 16, p.KBf);
-    p.g_lm = pick_cfg(EPI_LM, c.vocab / 16, p.KBd);
+    p.g_qkv = pick_cfg(EPI_QKV, ASD_K_QKV, p.qkv_tiles, p.KBd);
+    p.g_o = pick_cfg(EPI_RES, ASD_K_OPROJ, c.d_model / 16, p.KBq);
+    p.g_gu = pick_cfg(EPI_GU, ASD_K_GATEUP, c.d_ffn / 16, p.KBd);
+    p.g_down = pick_cfg(EPI_RES, ASD_K_DOWN, c.d_model / 16, p.KBf);
+    p.g_lm = pick_cfg(EPI_LM, ASD_K_LMHEAD, c.vocab / 16, p.KBd);
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -175,13 +192,15 @@ Plan make_plan(const asd_config& c) {
     p.page_table = take((size_t)p.n_pages * 4);
     p.xres = take((size_t)ASD_ROWS * c.d_model * 4);
     p.ssq = take(ASD_ROWS * 4);
-    const int pmax = p.g_o.grid > p.g_down.grid ? p.g_o.grid : p.g_down.grid;
+    int pmax = p.g_o.grid > p.g_down.grid ? p.g_o.grid : p.g_down.grid;
+    if (pmax < EMBED_SPLIT) pmax = EMBED_SPLIT;
     p.part = take((size_t)pmax * ASD_ROWS * 2 * 4);
     p.cos_rows = take((size_t)2 * c.n_layers * ASD_ROWS * 4);
     p.logits = take((size_t)ASD_ROWS * c.vocab * 4);
     p.o_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
     p.rope = take((size_t)p.n_pages * c.page_tokens * (c.head_dim / 2) * 2 * 4);
     p.ml_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * 8);
+    p.arrivals = take((size_t)c.n_heads * 4);
     p.xb = take((size_t)p.KBd * frag);
     p.q = take((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es);
     p.attn_out = take((size_t)p.KBq * frag);
@@ -222,35 +241,42 @@ bool tensor_info(const asd_config& c, int t, TensorInfo* ti) {
 bool tensor_is_global(int t) { return t == ASD_T_EMBED || t == ASD_T_LM_HEAD || t == ASD_T_FINAL_NORM; }
 int have_slot(const asd_engine* e, int t, int layer) { return tensor_is_global(t) ? t : 12 + layer * 12 + t; }
 
-// device address of a tensor (for tiled ones: the start of its tiles) and its k-block count
-char* tensor_addr(asd_engine* e, int t, int layer, int* KB) {
-    const asd_config& c = e->c;
-    const size_t frag = 1024;
-    const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
-    *KB = e->KBd;
-    switch (t) {
-        case ASD_T_EMBED: return e->embed;
-        case ASD_T_LM_HEAD: return e->lm;
-        case ASD_T_FINAL_NORM: return (char*)e->g_final;
-        case ASD_T_ATTN_NORM: return (char*)e->layers[layer].g_attn;
-        case ASD_T_MLP_NORM: return (char*)e->layers[layer].g_mlp;
-        case ASD_T_WQ: return e->layers[layer].wqkv;
-        case ASD_T_WK: return e->layers[layer].wqkv + (size_t)(qd / 16) * e->KBd * frag;
-        case ASD_T_WV: return e->layers[layer].wqkv + (size_t)((qd + kvd) / 16) * e->KBd * frag;
-        case ASD_T_WO: *KB = e->KBq; return e->layers[layer].wo;
-        case ASD_T_WG: return e->layers[layer].wg;
-        case ASD_T_WU: return e->layers[layer].wu;
-        case ASD_T_WD: *KB = e->KBf; return e->layers[layer].wd;
-    }
-    return nullptr;
+// where a tensor lives: base address of its (possibly fused) tile array and how its tiles are laid out
+struct TensorLoc { char* base; TileMap tm; };
+
+TileMap make_map(const GemmCfg& g, int total_tiles, int KB, int tile0, int rope_h) {
+    TileMap tm;
+    tm.ts = g.kmajor ? 1 : KB; tm.ks = g.kmajor ? total_tiles : 1; tm.tile0 = tile0; tm.KB = KB; tm.rope_h = rope_h;
+    return tm;
 }
 
-template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, int N, int K, int KB, bool untile) {
-    const size_t frags = (size_t)(N / 16) * KB * 64;
+TensorLoc tensor_loc(asd_engine* e, int t, int layer) {
+    const asd_config& c = e->c;
+    const int qd = c.n_heads * c.head_dim, kvd = c.n_kv_heads * c.head_dim;
+    const TileMap none{};
+    switch (t) {
+        case ASD_T_EMBED: return {e->embed, none};
+        case ASD_T_FINAL_NORM: return {(char*)e->g_final, none};
+        case ASD_T_ATTN_NORM: return {(char*)e->layers[layer].g_attn, none};
+        case ASD_T_MLP_NORM: return {(char*)e->layers[layer].g_mlp, none};
+        case ASD_T_LM_HEAD: return {e->lm, make_map(e->g_lm, c.vocab / 16, e->KBd, 0, 0)};
+        case ASD_T_WQ: return {e->layers[layer].wqkv, make_map(e->g_qkv, e->qkv_tiles, e->KBd, 0, c.head_dim)};
+        case ASD_T_WK: return {e->layers[layer].wqkv, make_map(e->g_qkv, e->qkv_tiles, e->KBd, qd / 16, c.head_dim)};
+        case ASD_T_WV: return {e->layers[layer].wqkv, make_map(e->g_qkv, e->qkv_tiles, e->KBd, (qd + kvd) / 16, c.head_dim)};
+        case ASD_T_WO: return {e->layers[layer].wo, make_map(e->g_o, c.d_model / 16, e->KBq, 0, 0)};
+        case ASD_T_WG: return {e->layers[layer].wg, make_map(e->g_gu, c.d_ffn / 16, e->KBd, 0, 0)};
+        case ASD_T_WU: return {e->layers[layer].wu, make_map(e->g_gu, c.d_ffn / 16, e->KBd, 0, 0)};
+        case ASD_T_WD: return {e->layers[layer].wd, make_map(e->g_down, c.d_model / 16, e->KBf, 0, 0)};
+    }
+    return {nullptr, none};
+}
+
+template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, int N, int K, const TileMap& tm, bool untile) {
+    const size_t frags = (size_t)(N / 16) * tm.KB * 64;
     const unsigned grid = (unsigned)((frags + 255) / 256);
     using El = typename T::elem;
-    if (untile) untile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, KB);
-    else tile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, KB);
+    if (untile) untile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, tm);
+    else tile_weight_kernel<T><<<grid, 256, 0, e->stream>>>((const El*)src, (El*)dst, N, K, tm);
 }
 
 // ------------------------------------------------------------------ GEMM dispatch
@@ -262,10 +288,10 @@ void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
 template <class T, int EPI>
 bool launch_gemm_t(hipStream_t s, const GemmCfg& g, const GemmArgs& a) {
 #define CASE(tn, nw) if (g.TN == tn && g.NW == nw) { launch_gemm_inst<T, EPI, tn, nw>(s, g.grid, a); return true; }
-    if constexpr (EPI == EPI_QKV) { CASE(2, 4) CASE(2, 8) }
+    if constexpr (EPI == EPI_QKV) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) }
     if constexpr (EPI == EPI_RES) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) CASE(2, 16) }
     if constexpr (EPI == EPI_GU) { CASE(1, 4) CASE(1, 8) CASE(2, 4) CASE(2, 8) }
-    if constexpr (EPI == EPI_LM) { CASE(2, 4) CASE(2, 8) }
+    if constexpr (EPI == EPI_LM) { CASE(1, 4) CASE(1, 8) CASE(2, 4) CASE(2, 8) }
 #undef CASE
     return false;
 }
@@ -274,19 +300,15 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
     return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
 }
 
-template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc) {
     const int H = e->c.head_dim;
-    dim3 gp(nc, e->c.n_heads), gm(e->c.n_heads, a.M);
-#define ATT(h)                                                                              \
-    if (H == h) {                                                                           \
-        if (merge) attn_merge_kernel<T, h><<<gm, h, 0, e->stream>>>(a);                     \
-        else attn_partial_kernel<T, h><<<gp, 64, 0, e->stream>>>(a);                        \
-    }
-    ATT(32) ATT(64) ATT(128)
-#undef ATT
+    dim3 gp(nc, e->c.n_heads);
+    if (H == 32) attn_kernel<T, 32><<<gp, 64, 0, e->stream>>>(a);
+    if (H == 64) attn_kernel<T, 64><<<gp, 64, 0, e->stream>>>(a);
+    if (H == 128) attn_kernel<T, 128><<<gp, 64, 0, e->stream>>>(a);
 }
-void launch_attn(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
-    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc, merge); else launch_attn_t<F32>(e, a, nc, merge);
+void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
+    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
 }
 
 // ------------------------------------------------------------------ algorithmic bytes
@@ -340,11 +362,11 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
 
     pr.begin(ASD_K_EMBED, 0);
     if (c.dtype == ASD_DT_BF16)
-        embed_kernel<BF16><<<M, 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model, next_gain(e, mask, -1),
-                                                     e->xres, e->xb, e->ssq);
+        embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model,
+                                                                        next_gain(e, mask, -1), e->xres, e->xb, e->part);
     else
-        embed_kernel<F32><<<M, 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model, next_gain(e, mask, -1),
-                                                    e->xres, e->xb, e->ssq);
+        embed_kernel<F32><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model,
+                                                                       next_gain(e, mask, -1), e->xres, e->xb, e->part);
     pr.end();
 
     GemmArgs base{};
@@ -354,18 +376,21 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
     base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part;
     // the cosine tap still open: partials of the last residual-add kernel and where its cosine goes
-    int open_P = 0, open_sub = -1;
+    // (the embedding leaves EMBED_SPLIT partials of ||x||^2 and no cosine to finish)
+    int open_P = EMBED_SPLIT, open_sub = -1;
     auto consume = [&](GemmArgs& g) {
         g.part_in = e->part; g.P_in = open_P;
-        if (open_P > 0) { g.fin_cos_rows = e->cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = e->cos_acc + open_sub; }
-        open_P = 0;
+        if (open_sub >= 0) { g.fin_cos_rows = e->cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = e->cos_acc + open_sub; }
+    };
+    auto layout = [&](GemmArgs& g, const GemmCfg& cfg, int total_tiles, int KB) {
+        g.KB = KB; g.w_tile_stride = cfg.kmajor ? 1 : KB; g.w_kb_stride = cfg.kmajor ? total_tiles : 1; g.k_interleave = cfg.kint;
     };
 
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& ly = e->layers[l];
         if (!(mask && mask[2 * l])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.n_tiles = e->qkv_tiles; a.KB = e->KBd;
+            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.n_tiles = e->qkv_tiles; layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
             consume(a);
             pr.begin(ASD_K_QKV, cls_bytes[ASD_K_QKV] / L);
@@ -376,16 +401,13 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
             t.q = e->q; t.kv = a.kv; t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
-            t.o_part = e->o_part; t.ml_part = e->ml_part; t.out = e->attn_out;
+            t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
             pr.begin(ASD_K_ATTN, cls_bytes[ASD_K_ATTN] / L);
-            launch_attn(e, t, nc, false);
-            pr.end();
-            pr.begin(ASD_K_ATTN_MERGE, 0);
-            launch_attn(e, t, nc, true);
+            launch_attn(e, t, nc);
             pr.end();
 
             GemmArgs o = base;
-            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.n_tiles = c.d_model / 16; o.KB = e->KBq;
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.n_tiles = c.d_model / 16; layout(o, e->g_o, c.d_model / 16, e->KBq);
             o.g_next = next_gain(e, mask, 2 * l);
             open_P = e->g_o.grid; open_sub = 2 * l;
             pr.begin(ASD_K_OPROJ, cls_bytes[ASD_K_OPROJ] / L);
@@ -395,14 +417,14 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         if (!(mask && mask[2 * l + 1])) {
             GemmArgs a = base;
             a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb;
-            a.n_tiles = c.d_ffn / 16; a.KB = e->KBd;
+            a.n_tiles = c.d_ffn / 16; layout(a, e->g_gu, c.d_ffn / 16, e->KBd);
             consume(a);
             pr.begin(ASD_K_GATEUP, cls_bytes[ASD_K_GATEUP] / L);
             if (!launch_gemm<EPI_GU>(e, e->g_gu, a)) return fail(e, ASD_E_STATE, "no gate/up kernel for this shape");
             pr.end();
 
             GemmArgs dn = base;
-            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.n_tiles = c.d_model / 16; dn.KB = e->KBf;
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.n_tiles = c.d_model / 16; layout(dn, e->g_down, c.d_model / 16, e->KBf);
             dn.g_next = next_gain(e, mask, 2 * l + 1);
             open_P = e->g_down.grid; open_sub = 2 * l + 1;
             pr.begin(ASD_K_DOWN, cls_bytes[ASD_K_DOWN] / L);
@@ -411,7 +433,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         }
     }
     GemmArgs lm = base;
-    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.n_tiles = c.vocab / 16; lm.KB = e->KBd;
+    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.n_tiles = c.vocab / 16; layout(lm, e->g_lm, c.vocab / 16, e->KBd);
     consume(lm);
     pr.begin(ASD_K_LMHEAD, cls_bytes[ASD_K_LMHEAD]);
     if (!launch_gemm<EPI_LM>(e, e->g_lm, lm)) return fail(e, ASD_E_STATE, "no LM-head kernel for this shape");
@@ -488,7 +510,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->kv = A + p.kv; e->kv_layer_bytes = p.kv_layer; e->page_table = (int32_t*)(A + p.page_table);
     e->xres = (float*)(A + p.xres); e->ssq = (float*)(A + p.ssq); e->part = (float*)(A + p.part);
     e->cos_rows = (float*)(A + p.cos_rows); e->logits = (float*)(A + p.logits); e->o_part = (float*)(A + p.o_part);
-    e->rope = (float*)(A + p.rope); e->ml_part = (float2*)(A + p.ml_part);
+    e->rope = (float*)(A + p.rope); e->ml_part = (float*)(A + p.ml_part); e->arrivals = (unsigned*)(A + p.arrivals);
     e->xb = A + p.xb; e->q = A + p.q; e->attn_out = A + p.attn_out; e->hmid = A + p.hmid;
     e->counters = (unsigned*)(A + p.counters); e->cos_acc = (double*)(A + p.cos_acc);
     e->amax_part = (AmaxPart*)(A + p.amax_part); e->argmax = (int32_t*)(A + p.argmax);
@@ -531,8 +553,8 @@ int asd_set_weight(asd_engine* e, int32_t t, int32_t layer, const void* src, siz
     if (!tensor_is_global(t) && (layer < 0 || layer >= e->c.n_layers)) return fail(e, ASD_E_INVAL, "layer %d out of range", layer);
     const size_t need = (size_t)ti.rows * ti.cols * (ti.norm ? 4 : e->es);
     if (bytes != need) return fail(e, ASD_E_INVAL, "tensor %d needs %zu bytes, got %zu", t, need, bytes);
-    int KB;
-    char* dst = tensor_addr(e, t, layer, &KB);
+    const TensorLoc loc = tensor_loc(e, t, layer);
+    char* dst = loc.base;
     const hipMemcpyKind kind = src_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
     if (!ti.tiled) {
         CK(e, hipMemcpyAsync(dst, src, bytes, kind, e->stream));
@@ -542,8 +564,8 @@ int asd_set_weight(asd_engine* e, int32_t t, int32_t layer, const void* src, siz
             CK(e, hipMemcpyAsync(e->staging, src, bytes, hipMemcpyHostToDevice, e->stream));
             dsrc = e->staging;
         }
-        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, dsrc, dst, ti.rows, ti.cols, KB, false);
-        else launch_tile<F32>(e, dsrc, dst, ti.rows, ti.cols, KB, false);
+        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, dsrc, dst, ti.rows, ti.cols, loc.tm, false);
+        else launch_tile<F32>(e, dsrc, dst, ti.rows, ti.cols, loc.tm, false);
     }
     CK(e, hipStreamSynchronize(e->stream));
     e->have[have_slot(e, t, layer)] = 1;
@@ -558,11 +580,11 @@ int asd_get_weight(asd_engine* e, int32_t t, int32_t layer, void* dst, size_t by
     const size_t need = (size_t)ti.rows * ti.cols * (ti.norm ? 4 : e->es);
     if (bytes != need) return fail(e, ASD_E_INVAL, "tensor %d has %zu bytes, buffer has %zu", t, need, bytes);
     if (!e->have[have_slot(e, t, layer)]) return fail(e, ASD_E_STATE, "tensor %d of layer %d was never set", t, layer);
-    int KB;
-    char* src = tensor_addr(e, t, layer, &KB);
+    const TensorLoc loc = tensor_loc(e, t, layer);
+    char* src = loc.base;
     if (ti.tiled) {
-        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, src, e->staging, ti.rows, ti.cols, KB, true);
-        else launch_tile<F32>(e, src, e->staging, ti.rows, ti.cols, KB, true);
+        if (e->c.dtype == ASD_DT_BF16) launch_tile<BF16>(e, src, e->staging, ti.rows, ti.cols, loc.tm, true);
+        else launch_tile<F32>(e, src, e->staging, ti.rows, ti.cols, loc.tm, true);
         src = e->staging;
     }
     CK(e, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, e->stream));
@@ -592,14 +614,15 @@ int asd_init_synthetic(asd_engine* e, uint64_t seed) {
     };
     auto gen = [&](int t, int layer, double std) {
         TensorInfo ti; tensor_info(c, t, &ti);
-        int KB; char* dst = tensor_addr(e, t, layer, &KB);
+        const TensorLoc loc = tensor_loc(e, t, layer);
+        char* dst = loc.base;
         const uint64_t st = h_stream(seed, (uint32_t)t, (uint32_t)layer);
-        const size_t frags = ti.tiled ? (size_t)(ti.rows / 16) * KB * 64 : ((size_t)ti.rows * ti.cols + e->KE - 1) / e->KE;
+        const size_t frags = ti.tiled ? (size_t)(ti.rows / 16) * loc.tm.KB * 64 : ((size_t)ti.rows * ti.cols + e->KE - 1) / e->KE;
         const unsigned grid = (unsigned)((frags + 255) / 256);
         if (c.dtype == ASD_DT_BF16)
-            synth_weight_kernel<BF16><<<grid, 256, 0, e->stream>>>((uint16_t*)dst, ti.rows, ti.cols, KB, st, cst(std), ti.tiled);
+            synth_weight_kernel<BF16><<<grid, 256, 0, e->stream>>>((uint16_t*)dst, ti.rows, ti.cols, loc.tm, st, cst(std), ti.tiled);
         else
-            synth_weight_kernel<F32><<<grid, 256, 0, e->stream>>>((float*)dst, ti.rows, ti.cols, KB, st, cst(std), ti.tiled);
+            synth_weight_kernel<F32><<<grid, 256, 0, e->stream>>>((float*)dst, ti.rows, ti.cols, loc.tm, st, cst(std), ti.tiled);
     };
     auto ones = [&](float* p) { fill_f32_kernel<<<(c.d_model + 255) / 256, 256, 0, e->stream>>>(p, c.d_model, 1.f); };
     gen(ASD_T_EMBED, 0, 0.02); gen(ASD_T_LM_HEAD, 0, 0.02); ones(e->g_final);

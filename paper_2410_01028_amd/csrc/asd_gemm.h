@@ -1,15 +1,16 @@
 // Weight-streaming small-M GEMM: out[m][n] = sum_k X[m][k] * W[n][k], m < 16, with fused epilogues.
 //
-// One workgroup owns a few 16-row tiles of W; its NW waves split K into contiguous
-// slices, each wave streaming its slice of every tile (1 KiB per load instruction,
-// U steps in flight) through the matrix cores with the 16 activation rows as the
-// other operand.  The slices are then summed through LDS in wave order, so every
-// output element has one fixed reduction order that does not depend on how many of
-// the 16 rows are in use: row i of a (k+1)-row verification pass and the same row
-// run alone give identical bits.  The grid never depends on the row count either.
+// One workgroup owns a few 16-row tiles of W; its NW waves split K (contiguous slices, or
+// interleaved k-blocks), each wave streaming its share of every tile (1 KiB per load
+// instruction, U steps in flight) through the matrix cores with the 16 activation rows as
+// the other operand.  The waves' sums are then added through LDS in wave order, so every
+// output element has one fixed reduction order that does not depend on how many of the 16
+// rows are in use: row i of a (k+1)-row verification pass and the same row run alone give
+// identical bits.  The grid never depends on the row count either.
 //
 // Epilogues (what a decoder sublayer needs right after the contraction):
 //   EPI_QKV  RMSNorm scale, rotary embedding, q -> tiled q buffer, k/v -> paged KV cache
+//            (the fused QKV weight is tiled with each rotary pair's two rows in the same tile)
 //   EPI_RES  y = x + out (residual add), tiled copy of y*gain for the next norm, and the
 //            cosine tap: per-workgroup partials of <x,y> and ||y||^2
 //   EPI_GU   RMSNorm scale, silu(gate) * up -> tiled activation
@@ -32,13 +33,15 @@ struct GemmArgs {
     const u32x4* X;          // tiled activations
     int32_t n_tiles;         // output features / 16
     int32_t KB;              // k-blocks
+    int64_t w_tile_stride, w_kb_stride;   // fragment (KiB) strides of the weight layout: tile-major {KB, 1}, k-major {1, tiles}
+    int32_t k_interleave;    // how the waves of a workgroup split K
     int32_t M;               // rows in use
-    float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap (or the embedding)
+    float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap
     float inv_d, eps;
-    // input side of QKV / GU / LM: partials of the kernel that produced the residual (P_in = 0: use ssq as is)
+    // input side of QKV / GU / LM: partials of the kernel that produced the residual
     const float* part_in;    // [P_in][16][2]
     int32_t P_in;
-    float* fin_cos_rows;     // [16] cosine per row of the producing sublayer (written by workgroup 0)
+    float* fin_cos_rows;     // [16] cosine per row of the producing sublayer (written by workgroup 0); NULL after the embedding
     double* fin_cos_acc;     // its running sum over rows
     // EPI_RES
     float* xres;             // [16][d] fp32 residual stream, updated in place
@@ -62,21 +65,22 @@ struct GemmArgs {
     AmaxPart* amax_part;     // [grid][16] best (logit, index) among this workgroup's features
 };
 
-// Stream the k-blocks [kb0, kb1) of NA weight tiles and the matching activation fragments.
-template <class T, int NA, int U>
-__device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int kb0, int kb1,
-                                           f32x4 (&acc)[NA]) {
+// Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments.
+// `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
+template <class T, int NA, int U, class F>
+__device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int first, int step, int n,
+                                           int64_t wks, f32x4 (&acc)[NA], F between) {
     u32x4 a[U][NA], b[U];
-    const int n = kb1 - kb0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (u < n) {
-            const size_t o = (size_t)(kb0 + u) * ASD_WAVE;
+            const size_t o = (size_t)(first + u * step) * ASD_WAVE;
             b[u] = X[o];
 #pragma unroll
-            for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o);
+            for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
         }
     }
+    between();
     for (int i = 0; i < n; i += U) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -85,10 +89,10 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
                 for (int s = 0; s < NA; ++s) mma16<T>(acc[s], a[u][s], b[u]);
                 const int nx = i + u + U;
                 if (nx < n) {
-                    const size_t o = (size_t)(kb0 + nx) * ASD_WAVE;
+                    const size_t o = (size_t)(first + nx * step) * ASD_WAVE;
                     b[u] = X[o];
 #pragma unroll
-                    for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o);
+                    for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
                 }
             }
         }
@@ -111,79 +115,93 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
 
     int tile[NA];
     bool tval[NA];
-    if constexpr (EPI == EPI_QKV) {
-        static_assert(EPI != EPI_QKV || TN == 2, "rotary pairs need the two half-head tiles together");
-        const int hpt = a.h / 16, half = hpt / 2;
-        tile[0] = (bid / half) * hpt + (bid % half);
-        tile[1] = tile[0] + half;
-        tval[0] = tval[1] = true;
-    } else {
 #pragma unroll
-        for (int t = 0; t < TN; ++t) {
-            tile[t] = bid * TN + t;
-            tval[t] = tile[t] < a.n_tiles;
-            if constexpr (EPI == EPI_GU) { tile[TN + t] = tile[t]; tval[TN + t] = tval[t]; }
-        }
+    for (int t = 0; t < TN; ++t) {
+        tile[t] = bid * TN + t;
+        tval[t] = tile[t] < a.n_tiles;
+        if constexpr (EPI == EPI_GU) { tile[TN + t] = tile[t]; tval[TN + t] = tval[t]; }
     }
 
     const u32x4* A[NA];
 #pragma unroll
     for (int s = 0; s < NA; ++s) {
         const u32x4* base = (EPI == EPI_GU && s >= TN) ? a.W2 : a.W;
-        A[s] = base + (size_t)(tval[s] ? tile[s] : 0) * a.KB * ASD_WAVE + lane;
+        A[s] = base + (size_t)(tval[s] ? tile[s] : 0) * a.w_tile_stride * ASD_WAVE + lane;
     }
-    const int kb0 = (int)((long)w * a.KB / NW), kb1 = (int)((long)(w + 1) * a.KB / NW);
+    // K split over the waves: contiguous slices, or interleaved (wave w takes k-blocks w, w+NW, ...)
+    int k_first, k_step, k_n;
+    if (a.k_interleave) { k_first = w; k_step = NW; k_n = (a.KB - w + NW - 1) / NW; }
+    else { k_first = (int)((long)w * a.KB / NW); k_step = 1; k_n = (int)((long)(w + 1) * a.KB / NW) - k_first; }
+
+    // Work whose loads should hide under the weight stream, run once the first U steps are in flight:
+    // ||y||^2 per row from the producing kernel's partials (same order in every workgroup), and for the
+    // residual epilogue this thread's residual inputs.
+    float syy = 0.f, sxy = 0.f;
+    constexpr int NE = (EPI == EPI_RES) ? (NA * 256 + NT - 1) / NT : 1;
+    float xpre[NE], gpre[NE];
+    auto early = [&]() {
+        if constexpr (kNormed) {
+            constexpr int J = NT / 16;
+            const int m = tid & 15, j = tid >> 4;
+            if (m < a.M) {
+                for (int p = j; p < a.P_in; p += J) {
+                    syy += a.part_in[((size_t)p * 16 + m) * 2 + 1];
+                    if (bid == 0) sxy += a.part_in[((size_t)p * 16 + m) * 2];
+                }
+            }
+        }
+        if constexpr (EPI == EPI_RES) {
+#pragma unroll
+            for (int q = 0; q < NE; ++q) {
+                const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+                xpre[q] = 0.f; gpre[q] = 0.f;
+                if (e < NA * 256 && m < a.M && tval[s]) {
+                    xpre[q] = a.xres[(size_t)m * a.d + tile[s] * 16 + nl];
+                    gpre[q] = a.g_next[tile[s] * 16 + nl];
+                }
+            }
+        }
+    };
 
     f32x4 acc[NA];
 #pragma unroll
     for (int s = 0; s < NA; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    stream_mma<T, NA, U>(A, a.X + lane, kb0, kb1, acc);
+    stream_mma<T, NA, U>(A, a.X + lane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
 
 #pragma unroll
     for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
 
     if constexpr (kNormed) {
-        // ||y||^2 per row from the producing kernel's partials (same order in every workgroup)
         constexpr int J = NT / 16;
-        const int m = tid & 15, j = tid >> 4;
-        float syy = 0.f, sxy = 0.f;
-        if (m < a.M) {
-            for (int p = j; p < a.P_in; p += J) {
-                syy += a.part_in[((size_t)p * 16 + m) * 2 + 1];
-                if (bid == 0) sxy += a.part_in[((size_t)p * 16 + m) * 2];
-            }
-        }
         fin_a[tid] = syy; fin_b[tid] = sxy;
         __syncthreads();
         if (tid < 16) {
             float yy = 0.f, xy = 0.f;
-            if (a.P_in > 0) {
-                for (int jj = 0; jj < J; ++jj) { yy += fin_a[jj * 16 + tid]; xy += fin_b[jj * 16 + tid]; }
-            } else if (tid < a.M) {
-                yy = a.ssq[tid];
-            }
+            for (int jj = 0; jj < J; ++jj) { yy += fin_a[jj * 16 + tid]; xy += fin_b[jj * 16 + tid]; }
             rscale[tid] = rsqrtf(yy * a.inv_d + a.eps);
             float c = 0.f;
-            if (bid == 0 && a.P_in > 0 && tid < a.M) {
-                const float xx = a.ssq[tid];
-                c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
-                c = fminf(1.f, fmaxf(-1.f, c));
+            if (bid == 0 && tid < a.M) {
+                if (a.fin_cos_rows) {            // the partials come from a residual-add kernel: finish its cosine
+                    const float xx = a.ssq[tid];
+                    c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
+                    c = fminf(1.f, fmaxf(-1.f, c));
+                    a.fin_cos_rows[tid] = c;
+                }
                 a.ssq[tid] = yy;
-                a.fin_cos_rows[tid] = c;
             }
-            fin_a[tid] = c;
+            fin_b[tid] = c;
         }
         __syncthreads();
-        if (bid == 0 && a.P_in > 0 && tid == 0) {
+        if (bid == 0 && a.fin_cos_rows && tid == 0) {
             double sum = 0.0;
-            for (int r = 0; r < a.M; ++r) sum += (double)fin_a[r];
+            for (int r = 0; r < a.M; ++r) sum += (double)fin_b[r];
             *a.fin_cos_acc += sum;
         }
     } else {
         __syncthreads();
     }
 
-    // element e of a 16x16 tile: row m = e / 16, local feature nl = e % 16 (consecutive threads -> consecutive features)
+    // element (row m, local feature nl) of tile s summed over the waves in wave order
     auto gather = [&](int s, int m, int nl) -> float {
         const int src = (nl >> 2) * 16 + m, r = nl & 3;
         float v = 0.f;
@@ -193,14 +211,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
     };
 
     if constexpr (EPI == EPI_QKV) {
+        // The fused QKV weight is tiled so that tile j of a head holds head dims 8j..8j+7 in rows 0..7 and
+        // the same dims + h/2, their rotary partners, in rows 8..15.
         using E = typename T::elem;
-        const int hpt = a.h / 16, half = hpt / 2, head = bid / half, j = bid % half;
-        for (int e = tid; e < 256; e += NT) {
-            const int m = e >> 4, nl = e & 15;
-            if (m >= a.M) continue;
+        const int hpt = a.h / 16, hh = a.h / 2;
+        for (int e = tid; e < TN * 128; e += NT) {
+            const int s = e >> 7, m = (e >> 3) & 15, nl = e & 7;
+            if (m >= a.M || !tval[s]) continue;
+            const int head = tile[s] / hpt, j = tile[s] % hpt;
             const float rs = rscale[m];
-            float v0 = gather(0, m, nl) * rs, v1 = gather(1, m, nl) * rs;
-            const int i = j * 16 + nl, hh = a.h / 2;
+            float v0 = gather(s, m, nl) * rs, v1 = gather(s, m, nl + 8) * rs;
+            const int i = j * 8 + nl;
             const int pos = a.st->pos + a.pos_off + m;
             if (head < a.n_h + a.n_kv) {
                 const float c = a.rope[((size_t)pos * hh + i) * 2], sn = a.rope[((size_t)pos * hh + i) * 2 + 1];
@@ -244,15 +265,17 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
 
     if constexpr (EPI == EPI_RES) {
         using E = typename T::elem;
-        for (int e = tid; e < NA * 256; e += NT) {
-            const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+#pragma unroll
+        for (int q = 0; q < NE; ++q) {
+            const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
+            if (e >= NA * 256) break;
             float pxy = 0.f, pyy = 0.f;
             if (m < a.M && tval[s]) {
                 const int n = tile[s] * 16 + nl;
-                const float x = a.xres[(size_t)m * a.d + n];
+                const float x = xpre[q];
                 const float y = x + gather(s, m, nl);
                 a.xres[(size_t)m * a.d + n] = y;
-                ((E*)a.xb)[act_index<T>(n, m)] = T::from_f32(y * a.g_next[n]);
+                ((E*)a.xb)[act_index<T>(n, m)] = T::from_f32(y * gpre[q]);
                 pxy = x * y; pyy = y * y;
             }
             epi_a[e] = pxy; epi_b[e] = pyy;

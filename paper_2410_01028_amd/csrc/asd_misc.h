@@ -4,16 +4,19 @@
 #include "asd_common.h"
 
 // ---------------------------------------------------------------- embedding + first norm statistics
-// One workgroup per row: x = E[token], ||x||^2, and the tiled copy x * gain for the first kept norm.
+// grid (EMBED_SPLIT, rows): x = E[token], the tiled copy x * gain for the first kept norm, and this
+// workgroup's share of ||x||^2 as partial [split][16][2] (slot 1; slot 0 unused) for the next kernel.
+#define EMBED_SPLIT 8
 template <class T>
 __global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
-                                                    const float* g_first, float* xres, void* xb, float* ssq) {
+                                                    const float* g_first, float* xres, void* xb, float* part) {
     using El = typename T::elem;
     __shared__ float red[256];
-    const int m = blockIdx.x, tid = threadIdx.x;
+    const int m = blockIdx.y, sp = blockIdx.x, tid = threadIdx.x;
     const El* row = E + (size_t)tokens[m] * d;
+    const int per = (d + EMBED_SPLIT - 1) / EMBED_SPLIT, lo = sp * per, hi = min(d, lo + per);
     float ss = 0.f;
-    for (int i = tid; i < d; i += 256) {
+    for (int i = lo + tid; i < hi; i += 256) {
         const float x = T::to_f32(row[i]);
         xres[(size_t)m * d + i] = x;
         ((El*)xb)[act_index<T>(i, m)] = T::from_f32(x * g_first[i]);
@@ -25,7 +28,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, c
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) ssq[m] = red[0];
+    if (tid == 0) { part[((size_t)sp * 16 + m) * 2] = 0.f; part[((size_t)sp * 16 + m) * 2 + 1] = red[0]; }
 }
 
 // ---------------------------------------------------------------- decoding state
@@ -45,42 +48,42 @@ __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok
 //               the next cycle's first row.
 enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
 struct AmaxCand { float v; int32_t i; };
+__device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 __global__ __launch_bounds__(256) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
                                                      DevState* st, int32_t* tokbuf, int32_t* out) {
     __shared__ float bv[256];
     __shared__ int bi[256];
-    const int tid = threadIdx.x, m = tid & 15, j = tid >> 4;
-    float v = -INFINITY; int idx = 0x7fffffff;
-    if (m < M)
-        for (int p = j; p < P; p += 16) {
+    __shared__ int win[16];
+    const int tid = threadIdx.x;
+    for (int m = 0; m < M; ++m) {               // candidates are stored [workgroup][16 rows]
+        float v = -INFINITY; int idx = 0x7fffffff;
+        for (int p = tid; p < P; p += 256) {
             const AmaxCand c = cand[(size_t)p * 16 + m];
-            if (c.v > v || (c.v == v && c.i < idx)) { v = c.v; idx = c.i; }
+            if (amax_better(c.v, c.i, v, idx)) { v = c.v; idx = c.i; }
         }
-    bv[tid] = v; bi[tid] = idx;
-    __syncthreads();
-    if (tid < 16 && tid < M) {
-        for (int jj = 0; jj < 16; ++jj) {
-            const float cv = bv[jj * 16 + tid]; const int ci = bi[jj * 16 + tid];
-            if (cv > v || (cv == v && ci < idx)) { v = cv; idx = ci; }
+        bv[tid] = v; bi[tid] = idx;
+        __syncthreads();
+        for (int s = 128; s > 0; s >>= 1) {
+            if (tid < s && amax_better(bv[tid + s], bi[tid + s], bv[tid], bi[tid])) { bv[tid] = bv[tid + s]; bi[tid] = bi[tid + s]; }
+            __syncthreads();
         }
-        argmax[tid] = idx;
-        bi[tid] = idx;
+        if (tid == 0) { win[m] = bi[0]; argmax[m] = bi[0]; }
+        __syncthreads();
     }
-    __syncthreads();
     if (tid != 0) return;
     if (mode == FIN_DRAFT) {
-        tokbuf[j_or_kk + 1] = bi[0];
+        tokbuf[j_or_kk + 1] = win[0];
     } else if (mode == FIN_ACCEPT) {
         const int kk = j_or_kk;
         int a = 0;
-        while (a < kk && tokbuf[a + 1] == bi[a]) ++a;
+        while (a < kk && tokbuf[a + 1] == win[a]) ++a;
         int e = st->emitted;
         for (int q = 1; q <= a && e < st->target; ++q) out[e++] = tokbuf[q];
-        if (e < st->target) out[e++] = bi[a];
+        if (e < st->target) out[e++] = win[a];
         st->emitted = e;
         st->pos += a + 1;
         st->cycles += 1; st->drafted += kk; st->accepted += a;
-        tokbuf[0] = bi[a];
+        tokbuf[0] = win[a];
     }
 }
 
@@ -100,30 +103,51 @@ __global__ void iota_kernel(int32_t* p, int n) {
 }
 
 // ---------------------------------------------------------------- weight tiling
-// dst fragment index f = (tile*KB + kb)*64 + lane; lane = 16g + r -> row 16*tile + r, k = kb*4KE + g*KE .. +KE
-template <class T>
-__global__ void tile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, int KB) {
-    constexpr int KE = T::KE;
-    const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (f >= (size_t)(N / 16) * KB * 64) return;
-    const int lane = (int)(f & 63);
+// A tiled matrix is a set of 1 KiB fragments addressed by (tile, k-block): fragment index =
+// (tile0 + tile) * ts + kb * ks with {ts, ks} = {KB, 1} (tile-major: a tile's K range is contiguous) or
+// {1, total tiles} (k-major: the fragments of all tiles for one k-block are contiguous).  Inside a
+// fragment lane 16g + r holds tile row r, k = kb*4KE + g*KE .. +KE.  rope_h != 0 selects the row order of
+// the fused QKV matrix: tile j of a head holds head dims 8j..8j+7 in rows 0..7 and the same dims + h/2
+// (their rotary partners) in rows 8..15.
+struct TileMap {
+    int64_t ts, ks;
+    int32_t tile0, KB, rope_h;
+};
+__device__ __forceinline__ size_t tm_frag(const TileMap& tm, int tile, int kb) {
+    return (size_t)(tm.tile0 + tile) * tm.ts + (size_t)kb * tm.ks;
+}
+__device__ __forceinline__ int tm_row(const TileMap& tm, int tile, int r) {
+    if (!tm.rope_h) return tile * 16 + r;
+    const int hpt = tm.rope_h / 16, head = tile / hpt, j = tile % hpt;
+    return head * tm.rope_h + 8 * j + (r & 7) + (r >> 3) * (tm.rope_h / 2);
+}
+// f enumerates (tile, kb, lane) of one tensor; returns false when out of range
+__device__ __forceinline__ bool tm_decode(const TileMap& tm, size_t f, int N, int* tile, int* kb, int* lane) {
+    if (f >= (size_t)(N / 16) * tm.KB * 64) return false;
+    *lane = (int)(f & 63);
     const size_t tk = f >> 6;
-    const int kb = (int)(tk % KB), tile = (int)(tk / KB);
-    const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
-#pragma unroll
-    for (int j = 0; j < KE; ++j) dst[f * KE + j] = (k0 + j < K) ? src[(size_t)row * K + k0 + j] : (typename T::elem)0;
+    *kb = (int)(tk % tm.KB); *tile = (int)(tk / tm.KB);
+    return true;
 }
 template <class T>
-__global__ void untile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, int KB) {
+__global__ void tile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, TileMap tm) {
     constexpr int KE = T::KE;
-    const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (f >= (size_t)(N / 16) * KB * 64) return;
-    const int lane = (int)(f & 63);
-    const size_t tk = f >> 6;
-    const int kb = (int)(tk % KB), tile = (int)(tk / KB);
-    const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+    int tile, kb, lane;
+    if (!tm_decode(tm, (size_t)blockIdx.x * blockDim.x + threadIdx.x, N, &tile, &kb, &lane)) return;
+    const int row = tm_row(tm, tile, lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+    typename T::elem* d = dst + (tm_frag(tm, tile, kb) * 64 + lane) * KE;
 #pragma unroll
-    for (int j = 0; j < KE; ++j) if (k0 + j < K) dst[(size_t)row * K + k0 + j] = src[f * KE + j];
+    for (int j = 0; j < KE; ++j) d[j] = (k0 + j < K) ? src[(size_t)row * K + k0 + j] : (typename T::elem)0;
+}
+template <class T>
+__global__ void untile_weight_kernel(const typename T::elem* src, typename T::elem* dst, int N, int K, TileMap tm) {
+    constexpr int KE = T::KE;
+    int tile, kb, lane;
+    if (!tm_decode(tm, (size_t)blockIdx.x * blockDim.x + threadIdx.x, N, &tile, &kb, &lane)) return;
+    const int row = tm_row(tm, tile, lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+    const typename T::elem* sfr = src + (tm_frag(tm, tile, kb) * 64 + lane) * KE;
+#pragma unroll
+    for (int j = 0; j < KE; ++j) if (k0 + j < K) dst[(size_t)row * K + k0 + j] = sfr[j];
 }
 
 // ---------------------------------------------------------------- synthetic weights (counter based)
@@ -145,19 +169,17 @@ __device__ __forceinline__ float synth_value(uint64_t stream, uint64_t i, float 
 }
 // tiled == 0: dst row-major [N][K];  tiled != 0: dst in the tiled weight layout (K padded with zeros)
 template <class T>
-__global__ void synth_weight_kernel(typename T::elem* dst, int N, int K, int KB, uint64_t stream, float cst, int tiled) {
+__global__ void synth_weight_kernel(typename T::elem* dst, int N, int K, TileMap tm, uint64_t stream, float cst, int tiled) {
     constexpr int KE = T::KE;
     const size_t f = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (tiled) {
-        if (f >= (size_t)(N / 16) * KB * 64) return;
-        const int lane = (int)(f & 63);
-        const size_t tk = f >> 6;
-        const int kb = (int)(tk % KB), tile = (int)(tk / KB);
-        const int row = tile * 16 + (lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+        int tile, kb, lane;
+        if (!tm_decode(tm, f, N, &tile, &kb, &lane)) return;
+        const int row = tm_row(tm, tile, lane & 15), k0 = kb * 4 * KE + (lane >> 4) * KE;
+        typename T::elem* d = dst + (tm_frag(tm, tile, kb) * 64 + lane) * KE;
 #pragma unroll
         for (int j = 0; j < KE; ++j)
-            dst[f * KE + j] = (k0 + j < K) ? T::from_f32(synth_value(stream, (uint64_t)row * K + k0 + j, cst))
-                                           : (typename T::elem)0;
+            d[j] = (k0 + j < K) ? T::from_f32(synth_value(stream, (uint64_t)row * K + k0 + j, cst)) : (typename T::elem)0;
     } else {
         if (f >= ((size_t)N * K + KE - 1) / KE) return;
 #pragma unroll
