@@ -38,17 +38,19 @@ __device__ __forceinline__ float2 coherent_load2(const float* p) {          // p
 }
 
 struct AttnArgs {
-    const void* q;            // [n_h][h/KE][16][KE]
+    const void* q;            // [n_h][h/KE][RS][KE], T::NP planes q_plane elements apart
+    int64_t q_plane, out_plane;
     const void* kv;           // this layer's cache pages
     const int32_t* page_table;
     const DevState* st;
-    int32_t pos_off, M;
+    int32_t pos_off, M, RS;   // rows in use, row stride of the activation buffers
     int32_t n_h, n_kv, h, page_tokens;
     int32_t nc_stride;        // chunks per head in the partial buffers
     float scale;              // 1/sqrt(h)
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised chunk outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (chunk max, chunk sum)
     unsigned* arrivals;       // [n_h] chunks finished per head (returns to 0)
+    int32_t fuse_merge;       // the last wave of a head to arrive merges (passes of at most ATT_RB rows)
     void* out;                // tiled activation [n_h*h]
 };
 
@@ -59,121 +61,13 @@ template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
 }
 template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 
+// Merge the chunk partials of rows m0 .. m0+ATT_RB-1 (those below a.M) of one head, in ascending chunk order, and
+// write the normalised output: chunk statistics with one chunk per lane, outputs with two head dims per lane; all
+// loads of a round are requested before any is used.  One wave.
 template <class T, int H>
-__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
-    using E = typename T::elem;
-    constexpr int KE = T::KE;
-    constexpr int HS = H / (4 * KE);            // fragment steps over the head dimension
-    constexpr int HT = H / 16;                  // output tiles over the head dimension
-    constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
-    const int c = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
-    const int g = lane >> 4, m = lane & 15, r = lane & 15;
-    const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
-    if (c * ASD_CHUNK > last) return;                    // no row of this call sees this chunk
-    const int kvh = head / (a.n_h / a.n_kv);
-    const int PT = a.page_tokens;
-    const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
-    const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
-    const E* Vp = Kp + (size_t)PT * H;
-    const E* qp = (const E*)a.q + (size_t)head * H * ASD_ROWS;
-
-    // ---- scores: 4 tiles of 16 keys
-    u32x4 qf[HS];
-#pragma unroll
-    for (int hs = 0; hs < HS; ++hs) qf[hs] = *(const u32x4*)(qp + ((size_t)(hs * 4 + g) * ASD_ROWS + m) * KE);
-    f32x4 s[4];
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-        s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const E* krow = Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE;
-#pragma unroll
-        for (int hs = 0; hs < HS; ++hs) {
-            const u32x4 kf = __builtin_nontemporal_load((const u32x4*)(krow + hs * 4 * KE));
-            mma16<T>(s[kt], kf, qf[hs]);
-        }
-    }
-    // ---- V^T fragments (independent of the scores: issued early)
-    u32x4 vf[HT][KST];
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-            vf[ht][ks] = __builtin_nontemporal_load(
-                (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
-
-    // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
-    const int row_pos = pos0 + m;
-    float mx = -INFINITY;
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
-            const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
-            s[kt][j] = v;
-            mx = fmaxf(mx, v);
-        }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    float l = 0.f;
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
-            p = T::to_f32(T::from_f32(p));          // the value the matrix cores will see
-            s[kt][j] = p;
-            l += p;
-        }
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-
-    // ---- output: O[dim][row] += V^T[dim][keys] * P[keys][row]
-    u32x4 pf[KST];
-    if constexpr (KE == 8) {
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) {
-                const f32x4& t = s[2 * ks + (w2 >> 1)];
-                const uint32_t lo = BF16::from_f32(t[(w2 & 1) * 2]), hi = BF16::from_f32(t[(w2 & 1) * 2 + 1]);
-                pf[ks][w2] = lo | (hi << 16);
-            }
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pf[ks][j] = __float_as_uint(s[ks][j]);
-    }
-    float* op = a.o_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * H;
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) {
-        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks) mma16<T>(o, vf[ht][ks], pf[ks]);
-        if (m < a.M) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) coherent_store(op + ht * 16 + 4 * g + j, o[j]);
-        }
-    }
-    float* mlp = a.ml_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * 2;
-    if (g == 0 && m < a.M) { coherent_store(mlp, mx); coherent_store(mlp + 1, l); }
-
-    // ---- arrival: the wave that completes the head's last chunk merges
-    const int n_chunks = last / ASD_CHUNK + 1;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);                   // this wave's partial stores have completed
-    unsigned old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    old = __shfl(old, 0);
-    if ((int)old != n_chunks - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-    // ---- merge, ATT_RB rows per round: chunk statistics with one chunk per lane, outputs with two head
-    //      dims per lane; all loads of a round are requested before any is used
+__device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int m0, int pos0, int lane) {
     const bool mine = 2 * lane < H;
-    for (int m0 = 0; m0 < a.M; m0 += ATT_RB) {
+    {
         float2 st[ATT_RB][ATT_NCL], v[ATT_RB][ATT_CB];
         int nc[ATT_RB];
 #pragma unroll
@@ -230,9 +124,140 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
                 }
             }
             if (mine) {
-                ((E*)a.out)[act_index<T>(head * H + 2 * lane, mm)] = T::from_f32(acc.x / L);
-                ((E*)a.out)[act_index<T>(head * H + 2 * lane + 1, mm)] = T::from_f32(acc.y / L);
+                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane, mm, acc.x / L);
+                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane + 1, mm, acc.y / L);
             }
         }
     }
+}
+
+template <class T, int H>
+__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
+    using E = typename T::elem;
+    constexpr int KE = T::KE;
+    constexpr int HS = H / (4 * KE);            // fragment steps over the head dimension
+    constexpr int HT = H / 16;                  // output tiles over the head dimension
+    constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
+    const int c = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+    const int g = lane >> 4, m = lane & 15, r = lane & 15;
+    const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
+    if (c * ASD_CHUNK > last) return;                    // no row of this call sees this chunk
+    const int kvh = head / (a.n_h / a.n_kv);
+    const int PT = a.page_tokens;
+    const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
+    const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
+    const E* Vp = Kp + (size_t)PT * H;
+    const E* qp = (const E*)a.q + (size_t)head * H * a.RS;
+
+    // ---- scores: 4 tiles of 16 keys
+    constexpr int NP = T::NP;
+    u32x4 qf[HS][NP];
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl)
+            qf[hs][pl] = m < a.M ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE) : u32x4{0u, 0u, 0u, 0u};
+    f32x4 s[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+        s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        const E* krow = Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE;
+#pragma unroll
+        for (int hs = 0; hs < HS; ++hs) {
+            const u32x4 kf = __builtin_nontemporal_load((const u32x4*)(krow + hs * 4 * KE));
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf, qf[hs][pl]);
+        }
+    }
+    // ---- V^T fragments (independent of the scores: issued early)
+    u32x4 vf[HT][KST];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+            vf[ht][ks] = __builtin_nontemporal_load(
+                (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
+
+    // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
+    const int row_pos = pos0 + m;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
+            const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
+            s[kt][j] = v;
+            mx = fmaxf(mx, v);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float l = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
+            s[kt][j] = p;
+            l += p;
+        }
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    // ---- output: O[dim][row] += V^T[dim][keys] * P[keys][row]; P goes in as hi + lo planes for bf16
+    u32x4 pf[KST][NP];
+    if constexpr (KE == 8) {
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                const f32x4& t = s[2 * ks + (w2 >> 1)];
+                const float p0 = t[(w2 & 1) * 2], p1 = t[(w2 & 1) * 2 + 1];
+                const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
+                const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
+                pf[ks][0][w2] = h0 | (h1 << 16);
+                pf[ks][1][w2] = l0 | (l1 << 16);
+            }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
+    }
+    float* op = a.o_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * H;
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) {
+        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) mma16<T>(o, vf[ht][ks], pf[ks][pl]);
+        if (m < a.M) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) coherent_store(op + ht * 16 + 4 * g + j, o[j]);
+        }
+    }
+    float* mlp = a.ml_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * 2;
+    if (g == 0 && m < a.M) { coherent_store(mlp, mx); coherent_store(mlp + 1, l); }
+
+    if (!a.fuse_merge) return;
+    // ---- arrival: the wave that completes the head's last chunk merges
+    const int n_chunks = last / ASD_CHUNK + 1;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's partial stores have completed
+    unsigned old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __shfl(old, 0);
+    if ((int)old != n_chunks - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+
+    // ---- merge (fused only for passes of at most ATT_RB rows; larger passes launch attn_merge_kernel)
+    attn_merge_rows<T, H>(a, head, 0, pos0, lane);
+}
+
+// Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
+template <class T, int H>
+__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
+    attn_merge_rows<T, H>(a, blockIdx.x, blockIdx.y * ATT_RB, a.st->pos + a.pos_off, threadIdx.x);
 }

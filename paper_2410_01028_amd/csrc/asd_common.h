@@ -7,8 +7,10 @@
 //      lane = 16*g + r holds row 16*tile + r, k = kb*4*KE + g*KE .. +KE   (K padded with 0 to KB*4*KE)
 //    so that one wave reads one contiguous KiB per step and a tile's K range is
 //    one contiguous stream in HBM;
-//  * tiled activation X[16 rows][K] -> [K/KE][16 rows][KE]: the fragment of k-block kb
-//    for lane 16*g + m is the 16 bytes at ((kb*4 + g)*16 + m)*KE, again one KiB per step.
+//  * tiled activation X[rows][K] -> [K/KE][RS][KE] with RS = the pass's row stride (the power of two
+//    >= its row count): the fragment of k-block kb for lane 16*g + m is the 16 bytes at
+//    ((kb*4 + g)*RS + m)*KE; lanes of unused rows supply zeros instead of loading, so a one-row pass
+//    reads 64 bytes of activations per KiB of weights.
 //
 // MFMA operand use: A = weights (16 output features x k-block), B = activations
 // (k-block x 16 rows), D[n][m]: lane 16*g + m holds n = 4*g + j in register j.
@@ -24,9 +26,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 #define ASD_ROWS 16          // rows (MFMA columns) of every forward call
 #define ASD_CHUNK 64         // keys per attention work item; chunk boundaries are absolute positions
 
+// NP = planes of an activation buffer: bf16 activations are kept as hi + lo (x ~ hi + lo, lo = bf16(x - hi)) and
+// contracted plane by plane, so that what the matrix cores see of an activation carries ~16 mantissa bits;
+// weights and the KV cache stay single bf16 values.
 struct BF16 {
     using elem = uint16_t;
     static constexpr int KE = 8;
+    static constexpr int NP = 2;
     static __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
     static __device__ __forceinline__ uint16_t from_f32(float f) {
         return __builtin_bit_cast(uint16_t, (__bf16)f);     // round to nearest even
@@ -35,6 +41,7 @@ struct BF16 {
 struct F32 {
     using elem = float;
     static constexpr int KE = 4;
+    static constexpr int NP = 1;
     static __device__ __forceinline__ float to_f32(float v) { return v; }
     static __device__ __forceinline__ float from_f32(float f) { return f; }
 };
@@ -50,9 +57,17 @@ template <> __device__ __forceinline__ void mma16<F32>(f32x4& acc, const u32x4& 
         acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a[j]), __uint_as_float(b[j]), acc, 0, 0, 0);
 }
 
-// element offset of (row m, feature k) in a tiled activation buffer
-template <class T> __device__ __forceinline__ size_t act_index(int k, int m) {
-    return ((size_t)(k / T::KE) * ASD_ROWS + m) * T::KE + (k % T::KE);
+// element offset of (row m, feature k) in a tiled activation buffer with row stride rs
+template <class T> __device__ __forceinline__ size_t act_index(int k, int m, int rs) {
+    return ((size_t)(k / T::KE) * rs + m) * T::KE + (k % T::KE);
+}
+
+// write value v of (feature k, row m) into every plane of a tiled activation buffer (plane stride in elements)
+template <class T> __device__ __forceinline__ void store_act(void* base, size_t plane, int rs, int k, int m, float v) {
+    typename T::elem* p = (typename T::elem*)base + act_index<T>(k, m, rs);
+    const typename T::elem hi = T::from_f32(v);
+    p[0] = hi;
+    if constexpr (T::NP == 2) p[plane] = T::from_f32(v - T::to_f32(hi));
 }
 
 // Device-resident decoding state, read by kernels so that captured graphs can be replayed unchanged.

@@ -201,10 +201,11 @@ Plan make_plan(const asd_config& c) {
     p.rope = take((size_t)p.n_pages * c.page_tokens * (c.head_dim / 2) * 2 * 4);
     p.ml_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * 8);
     p.arrivals = take((size_t)c.n_heads * 4);
-    p.xb = take((size_t)p.KBd * frag);
-    p.q = take((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es);
-    p.attn_out = take((size_t)p.KBq * frag);
-    p.hmid = take((size_t)p.KBf * frag);
+    const int NPL = c.dtype == ASD_DT_BF16 ? 2 : 1;     // activation planes
+    p.xb = take((size_t)p.KBd * frag * NPL);
+    p.q = take((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es * NPL);
+    p.attn_out = take((size_t)p.KBq * frag * NPL);
+    p.hmid = take((size_t)p.KBf * frag * NPL);
     p.counters = take(256);
     p.cos_acc = take((size_t)2 * c.n_layers * 8);
     p.amax_part = take((size_t)p.g_lm.grid * ASD_ROWS * sizeof(AmaxPart));
@@ -300,15 +301,19 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
     return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
 }
 
-template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc) {
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
     const int H = e->c.head_dim;
-    dim3 gp(nc, e->c.n_heads);
-    if (H == 32) attn_kernel<T, 32><<<gp, 64, 0, e->stream>>>(a);
-    if (H == 64) attn_kernel<T, 64><<<gp, 64, 0, e->stream>>>(a);
-    if (H == 128) attn_kernel<T, 128><<<gp, 64, 0, e->stream>>>(a);
+    const dim3 gp(nc, e->c.n_heads), gm(e->c.n_heads, (a.M + ATT_RB - 1) / ATT_RB);
+#define ATT(h)                                                                  \
+    if (H == h) {                                                               \
+        if (merge) attn_merge_kernel<T, h><<<gm, 64, 0, e->stream>>>(a);        \
+        else attn_kernel<T, h><<<gp, 64, 0, e->stream>>>(a);                    \
+    }
+    ATT(32) ATT(64) ATT(128)
+#undef ATT
 }
-void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
-    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
+void launch_attn(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
+    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc, merge); else launch_attn_t<F32>(e, a, nc, merge);
 }
 
 // ------------------------------------------------------------------ algorithmic bytes
@@ -359,21 +364,25 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
     pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // per-sublayer figures: divide the full-model totals by L
     const double L = c.n_layers;
     const float inv_d = 1.f / (float)c.d_model;
+    int RS = 1;
+    while (RS < M) RS *= 2;
 
     pr.begin(ASD_K_EMBED, 0);
     if (c.dtype == ASD_DT_BF16)
         embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model,
-                                                                        next_gain(e, mask, -1), e->xres, e->xb, e->part);
+                                                                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
     else
         embed_kernel<F32><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model,
-                                                                       next_gain(e, mask, -1), e->xres, e->xb, e->part);
+                                                                       next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
     pr.end();
 
     GemmArgs base{};
-    base.M = M; base.ssq = e->ssq; base.inv_d = inv_d; base.eps = c.rms_eps;
+    base.M = M; base.RS = RS; base.ssq = e->ssq; base.inv_d = inv_d; base.eps = c.rms_eps;
     base.xres = e->xres; base.xb = e->xb; base.part = e->part; base.d = c.d_model;
     base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.q = e->q; base.page_table = e->page_table;
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
+    base.xb_plane = (int64_t)e->KBd * 64 * e->KE; base.hmid_plane = (int64_t)e->KBf * 64 * e->KE;
+    base.q_plane = (int64_t)c.n_heads * c.head_dim * ASD_ROWS;
     base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part;
     // the cosine tap still open: partials of the last residual-add kernel and where its cosine goes
     // (the embedding leaves EMBED_SPLIT partials of ||x||^2 and no cosine to finish)
@@ -390,7 +399,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         const Layer& ly = e->layers[l];
         if (!(mask && mask[2 * l])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.n_tiles = e->qkv_tiles; layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
+            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64; a.n_tiles = e->qkv_tiles; layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
             consume(a);
             pr.begin(ASD_K_QKV, cls_bytes[ASD_K_QKV] / L);
@@ -398,16 +407,22 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
             pr.end();
 
             AttnArgs t{};
-            t.q = e->q; t.kv = a.kv; t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M;
+            t.q = e->q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv; t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
             t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
+            t.fuse_merge = M <= ATT_RB;          // few rows: the last chunk wave of a head merges; else a row-parallel kernel
             pr.begin(ASD_K_ATTN, cls_bytes[ASD_K_ATTN] / L);
-            launch_attn(e, t, nc);
+            launch_attn(e, t, nc, false);
             pr.end();
+            if (!t.fuse_merge) {
+                pr.begin(ASD_K_ATTN_MERGE, 0);
+                launch_attn(e, t, nc, true);
+                pr.end();
+            }
 
             GemmArgs o = base;
-            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.n_tiles = c.d_model / 16; layout(o, e->g_o, c.d_model / 16, e->KBq);
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16; layout(o, e->g_o, c.d_model / 16, e->KBq);
             o.g_next = next_gain(e, mask, 2 * l);
             open_P = e->g_o.grid; open_sub = 2 * l;
             pr.begin(ASD_K_OPROJ, cls_bytes[ASD_K_OPROJ] / L);
@@ -416,7 +431,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         }
         if (!(mask && mask[2 * l + 1])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb;
+            a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64;
             a.n_tiles = c.d_ffn / 16; layout(a, e->g_gu, c.d_ffn / 16, e->KBd);
             consume(a);
             pr.begin(ASD_K_GATEUP, cls_bytes[ASD_K_GATEUP] / L);
@@ -424,7 +439,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
             pr.end();
 
             GemmArgs dn = base;
-            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.n_tiles = c.d_model / 16; layout(dn, e->g_down, c.d_model / 16, e->KBf);
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16; layout(dn, e->g_down, c.d_model / 16, e->KBf);
             dn.g_next = next_gain(e, mask, 2 * l + 1);
             open_P = e->g_down.grid; open_sub = 2 * l + 1;
             pr.begin(ASD_K_DOWN, cls_bytes[ASD_K_DOWN] / L);
@@ -433,13 +448,13 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         }
     }
     GemmArgs lm = base;
-    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.n_tiles = c.vocab / 16; layout(lm, e->g_lm, c.vocab / 16, e->KBd);
+    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.x_plane = (int64_t)e->KBd * 64; lm.n_tiles = c.vocab / 16; layout(lm, e->g_lm, c.vocab / 16, e->KBd);
     consume(lm);
     pr.begin(ASD_K_LMHEAD, cls_bytes[ASD_K_LMHEAD]);
     if (!launch_gemm<EPI_LM>(e, e->g_lm, lm)) return fail(e, ASD_E_STATE, "no LM-head kernel for this shape");
     pr.end();
     pr.begin(ASD_K_FINISH, 0);
-    finish_kernel<<<1, 256, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg, e->st,
+    finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg, e->st,
                                             e->tokbuf, e->out_tokens);
     pr.end();
     hipError_t r = hipGetLastError();

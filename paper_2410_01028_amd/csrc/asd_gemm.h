@@ -30,12 +30,14 @@ struct AmaxPart { float v; int32_t i; };
 struct GemmArgs {
     const u32x4* W;          // tiled weights
     const u32x4* W2;         // EPI_GU: tiled up-projection (W is the gate projection)
-    const u32x4* X;          // tiled activations
+    const u32x4* X;          // tiled activations (row stride RS; T::NP planes, x_plane fragments apart)
+    int64_t x_plane;
     int32_t n_tiles;         // output features / 16
     int32_t KB;              // k-blocks
     int64_t w_tile_stride, w_kb_stride;   // fragment (KiB) strides of the weight layout: tile-major {KB, 1}, k-major {1, tiles}
     int32_t k_interleave;    // how the waves of a workgroup split K
     int32_t M;               // rows in use
+    int32_t RS;              // row stride of every activation buffer in this pass (power of two >= M)
     float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap
     float inv_d, eps;
     // input side of QKV / GU / LM: partials of the kernel that produced the residual
@@ -46,6 +48,7 @@ struct GemmArgs {
     // EPI_RES
     float* xres;             // [16][d] fp32 residual stream, updated in place
     void* xb;                // tiled copy of y * g_next in storage type
+    int64_t xb_plane, q_plane, hmid_plane;   // plane strides (elements) of the activation buffers written here
     const float* g_next;     // gain of the norm that reads y next
     float* part;             // [grid][16][2] partial <x,y>, ||y||^2 of this workgroup's features
     int32_t d;
@@ -53,7 +56,7 @@ struct GemmArgs {
     const DevState* st;
     int32_t pos_off;
     const float* rope;       // [max_seq][h/2][2] cos, sin
-    void* q;                 // [n_h][h/KE][16][KE]
+    void* q;                 // [n_h][h/KE][RS][KE]
     void* kv;                // this layer's cache pages
     const int32_t* page_table;
     int32_t n_h, n_kv, h, page_tokens;
@@ -67,15 +70,19 @@ struct GemmArgs {
 
 // Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments.
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
+// X points at this lane's fragment of k-block 0 (or is NULL for a lane whose row is unused: zeros); consecutive
+// k-blocks are xstep fragments apart.
 template <class T, int NA, int U, class F>
-__device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int first, int step, int n,
+__device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
                                            int64_t wks, f32x4 (&acc)[NA], F between) {
-    u32x4 a[U][NA], b[U];
+    constexpr int NP = T::NP;
+    u32x4 a[U][NA], b[U][NP];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (u < n) {
             const size_t o = (size_t)(first + u * step) * ASD_WAVE;
-            b[u] = X[o];
+#pragma unroll
+            for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? X[(size_t)(first + u * step) * xstep + pl * xpl] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
         }
@@ -86,11 +93,14 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
         for (int u = 0; u < U; ++u) {
             if (i + u < n) {
 #pragma unroll
-                for (int s = 0; s < NA; ++s) mma16<T>(acc[s], a[u][s], b[u]);
+                for (int s = 0; s < NA; ++s)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl) mma16<T>(acc[s], a[u][s], b[u][pl]);
                 const int nx = i + u + U;
                 if (nx < n) {
                     const size_t o = (size_t)(first + nx * step) * ASD_WAVE;
-                    b[u] = X[o];
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? X[(size_t)(first + nx * step) * xstep + pl * xpl] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
                     for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
                 }
@@ -166,7 +176,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
     f32x4 acc[NA];
 #pragma unroll
     for (int s = 0; s < NA; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    stream_mma<T, NA, U>(A, a.X + lane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
+    const u32x4* Xl = (lane & 15) < a.M ? a.X + (lane >> 4) * a.RS + (lane & 15) : nullptr;
+    stream_mma<T, NA, U>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
 
 #pragma unroll
     for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
@@ -229,9 +240,9 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                 v0 = o0; v1 = o1;
             }
             if (head < a.n_h) {
-                E* q = (E*)a.q + (size_t)head * a.h * ASD_ROWS;
-                q[act_index<T>(i, m)] = T::from_f32(v0);
-                q[act_index<T>(i + hh, m)] = T::from_f32(v1);
+                E* q = (E*)a.q + (size_t)head * a.h * a.RS;
+                store_act<T>(q, a.q_plane, a.RS, i, m, v0);
+                store_act<T>(q, a.q_plane, a.RS, i + hh, m, v1);
             } else {
                 const bool isk = head < a.n_h + a.n_kv;
                 const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
@@ -258,7 +269,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             const float rs = rscale[m];
             const float g = gather(s, m, nl) * rs, u = gather(TN + s, m, nl) * rs;
             const float act = g / (1.f + __expf(-g)) * u;
-            ((E*)a.hmid)[act_index<T>(tile[s] * 16 + nl, m)] = T::from_f32(act);
+            store_act<T>(a.hmid, a.hmid_plane, a.RS, tile[s] * 16 + nl, m, act);
         }
         return;
     }
@@ -275,7 +286,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                 const float x = xpre[q];
                 const float y = x + gather(s, m, nl);
                 a.xres[(size_t)m * a.d + n] = y;
-                ((E*)a.xb)[act_index<T>(n, m)] = T::from_f32(y * gpre[q]);
+                store_act<T>(a.xb, a.xb_plane, a.RS, n, m, y * gpre[q]);
                 pxy = x * y; pyy = y * y;
             }
             epi_a[e] = pxy; epi_b[e] = pyy;

@@ -9,7 +9,7 @@
 #define EMBED_SPLIT 8
 template <class T>
 __global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
-                                                    const float* g_first, float* xres, void* xb, float* part) {
+                                                    const float* g_first, float* xres, void* xb, size_t xb_plane, int rs, float* part) {
     using El = typename T::elem;
     __shared__ float red[256];
     const int m = blockIdx.y, sp = blockIdx.x, tid = threadIdx.x;
@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, c
     for (int i = lo + tid; i < hi; i += 256) {
         const float x = T::to_f32(row[i]);
         xres[(size_t)m * d + i] = x;
-        ((El*)xb)[act_index<T>(i, m)] = T::from_f32(x * g_first[i]);
+        store_act<T>(xb, xb_plane, rs, i, m, x * g_first[i]);
         ss += x * x;
     }
     red[tid] = ss;
@@ -49,27 +49,23 @@ __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok
 enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
 struct AmaxCand { float v; int32_t i; };
 __device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
-__global__ __launch_bounds__(256) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
-                                                     DevState* st, int32_t* tokbuf, int32_t* out) {
-    __shared__ float bv[256];
-    __shared__ int bi[256];
+__global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+                                                      DevState* st, int32_t* tokbuf, int32_t* out) {
     __shared__ int win[16];
-    const int tid = threadIdx.x;
-    for (int m = 0; m < M; ++m) {               // candidates are stored [workgroup][16 rows]
+    const int tid = threadIdx.x, lane = tid & 63, m = tid >> 6;      // one wave per row; candidates are [workgroup][16 rows]
+    if (m < M) {
         float v = -INFINITY; int idx = 0x7fffffff;
-        for (int p = tid; p < P; p += 256) {
+        for (int p = lane; p < P; p += 64) {
             const AmaxCand c = cand[(size_t)p * 16 + m];
             if (amax_better(c.v, c.i, v, idx)) { v = c.v; idx = c.i; }
         }
-        bv[tid] = v; bi[tid] = idx;
-        __syncthreads();
-        for (int s = 128; s > 0; s >>= 1) {
-            if (tid < s && amax_better(bv[tid + s], bi[tid + s], bv[tid], bi[tid])) { bv[tid] = bv[tid + s]; bi[tid] = bi[tid + s]; }
-            __syncthreads();
+        for (int o = 32; o > 0; o >>= 1) {
+            const float ov = __shfl_xor(v, o); const int oi = __shfl_xor(idx, o);
+            if (amax_better(ov, oi, v, idx)) { v = ov; idx = oi; }
         }
-        if (tid == 0) { win[m] = bi[0]; argmax[m] = bi[0]; }
-        __syncthreads();
+        if (lane == 0) { win[m] = idx; argmax[m] = idx; }
     }
+    __syncthreads();
     if (tid != 0) return;
     if (mode == FIN_DRAFT) {
         tokbuf[j_or_kk + 1] = win[0];

@@ -1,0 +1,88 @@
+"""Parity at the benchmark's full width and depth (7B shape, bf16) on a short context, plus properties
+that hold at the full benchmark sizes (prompt 512, 256 tokens) in the launch configuration bench.py times."""
+import numpy as np
+import pytest
+
+import asd_inputs as si
+import oracle
+import paper_2410_01028_amd as asd
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def eng7b():
+    s = si.SHAPES["7b"]
+    e = asd.Engine(asd.make_config(s, s.prompt_len + s.n_new + 16, page_tokens=256))
+    e.init_synthetic(0)
+    yield s, e
+    e.close()
+
+
+def test_7b_shape_short_context_against_oracle(eng7b):
+    """Teacher-forced logits and cosines of 6 prompt rows + 2 single rows, all 32 layers, oracle in fp64."""
+    s, eng = eng7b
+    orc = oracle.Oracle(s, 16)
+    for t, l, a in si.all_tensors(s, 0):
+        orc.set_weight(t, l, a)
+    toks = si.prompt(0, 8, s.vocab)
+    eng.reset()
+    for lo, hi in ((0, 6), (6, 7), (7, 8)):
+        g = eng.forward(toks[lo:hi], lo)
+        o = orc.forward(toks[lo:hi], lo)
+        err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
+        assert err.max() < 2e-2, err
+        assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+    mask = si.fixed_keep_mask(s.n_layers, 2)
+    g = eng.forward(toks[:3], 8, mask, commit=False)
+    o = orc.forward(toks[:3], 8, mask, commit=False)
+    err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
+    assert err.max() < 2e-2, err
+    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+    orc.close()
+
+
+def test_7b_full_benchmark_sizes_properties(eng7b):
+    s, eng = eng7b
+    prompt = si.prompt(0, s.prompt_len, s.vocab)
+    N = 64
+    plain, st, _ = eng.generate(prompt, N, 0)
+    L2 = 2 * s.n_layers
+    for k, kw in ((4, dict(alpha=0.985, m=3, n=2)), (6, dict(fixed_mask=si.fixed_keep_mask(s.n_layers, 2))),
+                  (8, dict(fixed_mask=np.zeros(L2, np.uint8)))):
+        out, st, mask = eng.generate(prompt, N, k, **kw)
+        assert np.array_equal(out, plain)
+        assert st["emitted"] == N == st["accepted"] + st["cycles"] + 1
+        assert eng.kv_len == s.prompt_len + N - 1
+    assert st["cycles"] == -(-(N - 1) // 9) and st["accepted"] == st["drafted"]      # all-keep: every draft accepted
+    first, acs, _ = eng.prefill(prompt)
+    assert (acs <= 1.0).all() and (acs >= -1.0).all() and first == plain[0]
+    # determinism: the same pass twice gives the same bits
+    a = eng.forward(prompt[:5], s.prompt_len, commit=False)
+    b = eng.forward(prompt[:5], s.prompt_len, commit=False)
+    assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["cos_rows"], b["cos_rows"])
+    # rows of a verify pass equal single-row passes at the full shape
+    for i in range(5):
+        one = eng.forward(prompt[i:i + 1], s.prompt_len + i)
+        assert np.array_equal(one["logits"][0], a["logits"][i])
+
+
+@pytest.mark.parametrize("name", ["13b", "70b"])
+def test_other_shapes_run_and_keep_invariants(name):
+    """13B and 70B-GQA shapes at full width, reduced depth (4 layers) to keep the test short."""
+    s = si.SHAPES[name].with_(n_layers=4)
+    eng = asd.Engine(asd.make_config(s, 512, page_tokens=256)).init_synthetic(0)
+    orc = oracle.Oracle(s, 16)
+    for t, l, a in si.all_tensors(s, 0):
+        orc.set_weight(t, l, a)
+    toks = si.prompt(0, 200, s.vocab)
+    g = eng.forward(toks[:5], 0)
+    o = orc.forward(toks[:5], 0)
+    err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
+    assert err.max() < 2e-2, err
+    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+    orc.close()
+    plain, _, _ = eng.generate(toks, 24, 0)
+    out, st, _ = eng.generate(toks, 24, 6, fixed_mask=np.array([0, 0, 1, 0, 0, 1, 0, 0], np.uint8))
+    assert np.array_equal(out, plain) and st["emitted"] == 24
+    eng.close()

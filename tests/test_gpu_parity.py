@@ -236,3 +236,64 @@ def test_argument_validation_on_device_engine():
     assert eng.kv_len == 0
     r = eng.forward([1, 2, 3], 0)
     assert eng.kv_len == 3 and r["logits"].shape == (3, s.vocab)
+
+
+def test_long_context_merge_paths():
+    """More than 16 chunks per head (the merge's second loop) and a shuffled page table, bf16 GQA shape."""
+    shape = BF_GQA
+    W = list(si.all_tensors(shape, 11, gain_std=0.1))
+    eng = asd.Engine(asd.make_config(shape, 1536, page_tokens=128)).load(W)
+    rng = np.random.default_rng(3)
+    eng.set_page_table(rng.permutation(12))
+    orc = oracle.Oracle(shape, 1536).load(W)
+    toks = si.prompt(5, 1500, shape.vocab)
+    first, acs, _ = eng.prefill(toks[:1400])                 # 22 chunks
+    o = orc.forward(toks[:1400], 0)
+    assert np.abs(acs - o["cos"]).max() < COS_TOL
+    assert eng.kv_len == orc.kv_len == 1400
+    tol = TOL[shape.dtype]
+    check_forward(eng, orc, toks[1400:1409], 1400, None, tol)             # rows straddle the chunk boundary at 1408
+    check_forward(eng, orc, toks[1409:1410], 1409, None, tol)
+    multi = eng.forward(toks[1410:1417], 1410, commit=False)
+    for i in range(7):
+        one = eng.forward(toks[1410 + i:1411 + i], 1410 + i)
+        assert np.array_equal(one["logits"][0], multi["logits"][i]), i
+
+
+def test_weights_file_roundtrip(tmp_path):
+    shape = BF_GQA
+    W = list(si.all_tensors(shape, 2, gain_std=0.05))
+    path = tmp_path / "w.asdw"
+    order = {t: i for i, t in enumerate((si.T_EMBED, si.T_FINAL_NORM, si.T_LM_HEAD))}
+    lorder = {t: i for i, t in enumerate((si.T_ATTN_NORM, si.T_WQ, si.T_WK, si.T_WV, si.T_WO, si.T_MLP_NORM, si.T_WG, si.T_WU, si.T_WD))}
+    glob = sorted([x for x in W if x[0] in order], key=lambda x: order[x[0]])
+    lay = sorted([x for x in W if x[0] in lorder], key=lambda x: (x[1], lorder[x[0]]))
+    with open(path, "wb") as f:
+        f.write(b"ASDW0001")
+        f.write(np.array([shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                          shape.vocab, shape.dtype], np.int32).tobytes())
+        for _, _, a in glob + lay:
+            f.write(np.ascontiguousarray(a).tobytes())
+    a = asd.Engine(asd.make_config(shape, 128)).load_weights_file(str(path))
+    b = asd.Engine(asd.make_config(shape, 128)).load(W)
+    toks = si.prompt(1, 9, shape.vocab)
+    assert np.array_equal(a.forward(toks, 0)["logits"], b.forward(toks, 0)["logits"])
+    with pytest.raises(asd.AsdError):
+        asd.Engine(asd.make_config(shape, 128)).load_weights_file(str(tmp_path / "missing.asdw"))
+    with pytest.raises(asd.AsdError):
+        asd.Engine(asd.make_config(shape.with_(d_ffn=224), 128)).load_weights_file(str(path))     # shape mismatch
+
+
+def test_graph_replays_match_eager():
+    """Replay captured cycles several times with eager work and synchronisation in between."""
+    shape = MID16
+    eng = asd.Engine(asd.make_config(shape, 256)).init_synthetic(3)
+    prompt = si.prompt(4, 40, shape.vocab)
+    mask = np.zeros(2 * shape.n_layers, np.uint8); mask[2] = 1
+    ref, _, _ = eng.generate(prompt, 30, 3, fixed_mask=mask, use_graphs=False)
+    for _ in range(3):
+        out, _, _ = eng.generate(prompt, 30, 3, fixed_mask=mask, use_graphs=True)
+        assert np.array_equal(out, ref)
+        eng.forward(prompt[:3], eng.kv_len, commit=False)        # eager work between replays
+        ms, _ = eng.time_pass(2, mask, 3, True)
+        assert ms > 0
