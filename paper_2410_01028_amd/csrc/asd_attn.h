@@ -64,7 +64,7 @@ template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { retur
 // Merge the chunk partials of rows m0 .. m0+ATT_RB-1 (those below a.M) of one head, in ascending chunk order, and
 // write the normalised output: chunk statistics with one chunk per lane, outputs with two head dims per lane; all
 // loads of a round are requested before any is used.  One wave.
-template <class T, int H>
+template <class T, int H, bool COH>
 __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int m0, int pos0, int lane) {
     const bool mine = 2 * lane < H;
     {
@@ -124,21 +124,21 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int
                 }
             }
             if (mine) {
-                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane, mm, acc.x / L);
-                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane + 1, mm, acc.y / L);
+                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + 2 * lane, mm, acc.x / L);
+                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + 2 * lane + 1, mm, acc.y / L);
             }
         }
     }
 }
 
-template <class T, int H>
-__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
+// One wave's work item: chunk c of query head `head` (COH as in gemm_block).
+template <class T, int H, bool COH>
+__device__ __forceinline__ void attn_block(const AttnArgs& a, const int c, const int head, const int lane) {
     using E = typename T::elem;
     constexpr int KE = T::KE;
     constexpr int HS = H / (4 * KE);            // fragment steps over the head dimension
     constexpr int HT = H / 16;                  // output tiles over the head dimension
     constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
-    const int c = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
     const int g = lane >> 4, m = lane & 15, r = lane & 15;
     const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
     if (c * ASD_CHUNK > last) return;                    // no row of this call sees this chunk
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
     for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
         for (int pl = 0; pl < NP; ++pl)
-            qf[hs][pl] = m < a.M ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE) : u32x4{0u, 0u, 0u, 0u};
+            qf[hs][pl] = m < a.M ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE)) : u32x4{0u, 0u, 0u, 0u};
     f32x4 s[4];
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
@@ -252,12 +252,17 @@ __global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
     if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    // ---- merge (fused only for passes of at most ATT_RB rows; larger passes launch attn_merge_kernel)
-    attn_merge_rows<T, H>(a, head, 0, pos0, lane);
+    // ---- merge (fused only for passes of at most ATT_RB rows; larger passes run the row-parallel merge)
+    attn_merge_rows<T, H, COH>(a, head, 0, pos0, lane);
+}
+
+template <class T, int H>
+__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
+    attn_block<T, H, false>(a, blockIdx.x, blockIdx.y, threadIdx.x);
 }
 
 // Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
 template <class T, int H>
 __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
-    attn_merge_rows<T, H>(a, blockIdx.x, blockIdx.y * ATT_RB, a.st->pos + a.pos_off, threadIdx.x);
+    attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, a.st->pos + a.pos_off, threadIdx.x);
 }

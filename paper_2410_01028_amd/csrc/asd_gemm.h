@@ -72,7 +72,7 @@ struct GemmArgs {
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
 // X points at this lane's fragment of k-block 0 (or is NULL for a lane whose row is unused: zeros); consecutive
 // k-blocks are xstep fragments apart.
-template <class T, int NA, int U, class F>
+template <class T, int NA, int U, bool COH, class F>
 __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
                                            int64_t wks, f32x4 (&acc)[NA], F between) {
     constexpr int NP = T::NP;
@@ -82,7 +82,7 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
         if (u < n) {
             const size_t o = (size_t)(first + u * step) * ASD_WAVE;
 #pragma unroll
-            for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? X[(size_t)(first + u * step) * xstep + pl * xpl] : u32x4{0u, 0u, 0u, 0u};
+            for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + u * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
         }
@@ -100,7 +100,7 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
                 if (nx < n) {
                     const size_t o = (size_t)(first + nx * step) * ASD_WAVE;
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? X[(size_t)(first + nx * step) * xstep + pl * xpl] : u32x4{0u, 0u, 0u, 0u};
+                    for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + nx * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
                     for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
                 }
@@ -109,8 +109,11 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
     }
 }
 
-template <class T, int EPI, int TN, int NW, int U>
-__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
+// One workgroup's share of the contraction: "virtual block" bid owns tiles bid*TN .. bid*TN+TN-1.  Called once per
+// workgroup by gemm_kernel (bid = blockIdx.x) and in a loop over virtual blocks by the persistent pass kernel
+// (COH = true: every access to data exchanged with other workgroups of the same kernel is coherent).
+template <class T, int EPI, int TN, int NW, int U, bool COH>
+__device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     constexpr int NT = NW * 64;
     constexpr bool kNormed = (EPI != EPI_RES);          // input went through RMSNorm: needs the row scale
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
     __shared__ float fin_b[kNormed ? NT : 1];
     __shared__ float rscale[16];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, bid = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
 
     int tile[NA];
     bool tval[NA];
@@ -155,8 +158,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             const int m = tid & 15, j = tid >> 4;
             if (m < a.M) {
                 for (int p = j; p < a.P_in; p += J) {
-                    syy += a.part_in[((size_t)p * 16 + m) * 2 + 1];
-                    if (bid == 0) sxy += a.part_in[((size_t)p * 16 + m) * 2];
+                    syy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2 + 1]);
+                    if (bid == 0) sxy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2]);
                 }
             }
         }
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                 const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
                 xpre[q] = 0.f; gpre[q] = 0.f;
                 if (e < NA * 256 && m < a.M && tval[s]) {
-                    xpre[q] = a.xres[(size_t)m * a.d + tile[s] * 16 + nl];
+                    xpre[q] = ld_f32<COH>(&a.xres[(size_t)m * a.d + tile[s] * 16 + nl]);
                     gpre[q] = a.g_next[tile[s] * 16 + nl];
                 }
             }
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
 #pragma unroll
     for (int s = 0; s < NA; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
     const u32x4* Xl = (lane & 15) < a.M ? a.X + (lane >> 4) * a.RS + (lane & 15) : nullptr;
-    stream_mma<T, NA, U>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
+    stream_mma<T, NA, U, COH>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
 
 #pragma unroll
     for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
@@ -193,12 +196,12 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             float c = 0.f;
             if (bid == 0 && tid < a.M) {
                 if (a.fin_cos_rows) {            // the partials come from a residual-add kernel: finish its cosine
-                    const float xx = a.ssq[tid];
+                    const float xx = ld_f32<COH>(&a.ssq[tid]);
                     c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
                     c = fminf(1.f, fmaxf(-1.f, c));
                     a.fin_cos_rows[tid] = c;
                 }
-                a.ssq[tid] = yy;
+                st_f32<COH>(&a.ssq[tid], yy);
             }
             fin_b[tid] = c;
         }
@@ -241,20 +244,20 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             }
             if (head < a.n_h) {
                 E* q = (E*)a.q + (size_t)head * a.h * a.RS;
-                store_act<T>(q, a.q_plane, a.RS, i, m, v0);
-                store_act<T>(q, a.q_plane, a.RS, i + hh, m, v1);
+                store_act<T, COH>(q, a.q_plane, a.RS, i, m, v0);
+                store_act<T, COH>(q, a.q_plane, a.RS, i + hh, m, v1);
             } else {
                 const bool isk = head < a.n_h + a.n_kv;
                 const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
                 const int PT = a.page_tokens, page = a.page_table[pos / PT], slot = pos % PT;
                 E* base = (E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * a.h;
                 if (isk) {                       // K[slot][h]
-                    base[(size_t)slot * a.h + i] = T::from_f32(v0);
-                    base[(size_t)slot * a.h + i + hh] = T::from_f32(v1);
+                    st_elem<T, COH>(base + (size_t)slot * a.h + i, T::from_f32(v0));
+                    st_elem<T, COH>(base + (size_t)slot * a.h + i + hh, T::from_f32(v1));
                 } else {                         // V transposed: [h][slot]
                     base += (size_t)PT * a.h;
-                    base[(size_t)i * PT + slot] = T::from_f32(v0);
-                    base[(size_t)(i + hh) * PT + slot] = T::from_f32(v1);
+                    st_elem<T, COH>(base + (size_t)i * PT + slot, T::from_f32(v0));
+                    st_elem<T, COH>(base + (size_t)(i + hh) * PT + slot, T::from_f32(v1));
                 }
             }
         }
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             const float rs = rscale[m];
             const float g = gather(s, m, nl) * rs, u = gather(TN + s, m, nl) * rs;
             const float act = g / (1.f + __expf(-g)) * u;
-            store_act<T>(a.hmid, a.hmid_plane, a.RS, tile[s] * 16 + nl, m, act);
+            store_act<T, COH>(a.hmid, a.hmid_plane, a.RS, tile[s] * 16 + nl, m, act);
         }
         return;
     }
@@ -285,8 +288,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                 const int n = tile[s] * 16 + nl;
                 const float x = xpre[q];
                 const float y = x + gather(s, m, nl);
-                a.xres[(size_t)m * a.d + n] = y;
-                store_act<T>(a.xb, a.xb_plane, a.RS, n, m, y * gpre[q]);
+                st_f32<COH>(&a.xres[(size_t)m * a.d + n], y);
+                store_act<T, COH>(a.xb, a.xb_plane, a.RS, n, m, y * gpre[q]);
                 pxy = x * y; pyy = y * y;
             }
             epi_a[e] = pxy; epi_b[e] = pyy;
@@ -296,8 +299,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
             float sxy = 0.f, syy = 0.f;
             for (int s = 0; s < NA; ++s)
                 for (int nl = 0; nl < 16; ++nl) { sxy += epi_a[s * 256 + tid * 16 + nl]; syy += epi_b[s * 256 + tid * 16 + nl]; }
-            a.part[((size_t)bid * 16 + tid) * 2] = sxy;
-            a.part[((size_t)bid * 16 + tid) * 2 + 1] = syy;
+            st_f32<COH>(&a.part[((size_t)bid * 16 + tid) * 2], sxy);
+            st_f32<COH>(&a.part[((size_t)bid * 16 + tid) * 2 + 1], syy);
         }
     }
 
@@ -319,7 +322,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
                     const float v = epi_a[s * 256 + tid * 16 + nl];
                     if (v > best.v) { best.v = v; best.i = tile[s] * 16 + nl; }
                 }
-            a.amax_part[(size_t)bid * 16 + tid] = best;
+            st_f32<COH>(&a.amax_part[(size_t)bid * 16 + tid].v, best.v);
+            st_f32<COH>((float*)&a.amax_part[(size_t)bid * 16 + tid].i, __int_as_float(best.i));
         }
     }
+}
+
+template <class T, int EPI, int TN, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
+    gemm_block<T, EPI, TN, NW, U, false>(a, blockIdx.x);
 }

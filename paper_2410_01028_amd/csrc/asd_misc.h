@@ -7,28 +7,34 @@
 // grid (EMBED_SPLIT, rows): x = E[token], the tiled copy x * gain for the first kept norm, and this
 // workgroup's share of ||x||^2 as partial [split][16][2] (slot 1; slot 0 unused) for the next kernel.
 #define EMBED_SPLIT 8
-template <class T>
-__global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
-                                                    const float* g_first, float* xres, void* xb, size_t xb_plane, int rs, float* part) {
+template <class T, bool COH>
+__device__ __forceinline__ void embed_block(const typename T::elem* E, const int32_t* tokens, int d, const float* g_first, float* xres,
+                                            void* xb, size_t xb_plane, int rs, float* part, const int sp, const int m, float* red) {
     using El = typename T::elem;
-    __shared__ float red[256];
-    const int m = blockIdx.y, sp = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x, nt = blockDim.x;
     const El* row = E + (size_t)tokens[m] * d;
     const int per = (d + EMBED_SPLIT - 1) / EMBED_SPLIT, lo = sp * per, hi = min(d, lo + per);
     float ss = 0.f;
-    for (int i = lo + tid; i < hi; i += 256) {
+    for (int i = lo + tid; i < hi; i += nt) {
         const float x = T::to_f32(row[i]);
-        xres[(size_t)m * d + i] = x;
-        store_act<T>(xb, xb_plane, rs, i, m, x * g_first[i]);
+        st_f32<COH>(&xres[(size_t)m * d + i], x);
+        store_act<T, COH>(xb, xb_plane, rs, i, m, x * g_first[i]);
         ss += x * x;
     }
     red[tid] = ss;
     __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
+    for (int s = nt / 2; s > 0; s >>= 1) {
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) { part[((size_t)sp * 16 + m) * 2] = 0.f; part[((size_t)sp * 16 + m) * 2 + 1] = red[0]; }
+    if (tid == 0) { st_f32<COH>(&part[((size_t)sp * 16 + m) * 2], 0.f); st_f32<COH>(&part[((size_t)sp * 16 + m) * 2 + 1], red[0]); }
+    __syncthreads();
+}
+template <class T>
+__global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
+                                                    const float* g_first, float* xres, void* xb, size_t xb_plane, int rs, float* part) {
+    __shared__ float red[256];
+    embed_block<T, false>(E, tokens, d, g_first, xres, xb, xb_plane, rs, part, blockIdx.x, blockIdx.y, red);
 }
 
 // ---------------------------------------------------------------- decoding state
@@ -49,14 +55,17 @@ __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok
 enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
 struct AmaxCand { float v; int32_t i; };
 __device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
-__global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
-                                                      DevState* st, int32_t* tokbuf, int32_t* out) {
-    __shared__ int win[16];
-    const int tid = threadIdx.x, lane = tid & 63, m = tid >> 6;      // one wave per row; candidates are [workgroup][16 rows]
-    if (m < M) {
+// one workgroup; wave w handles rows w, w + (waves), ...; candidates are [workgroup][16 rows]
+template <bool COH>
+__device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+                                             DevState* st, int32_t* tokbuf, int32_t* out, int* win) {
+    const int tid = threadIdx.x, lane = tid & 63, nw = blockDim.x >> 6;
+    for (int m = tid >> 6; m < M; m += nw) {
         float v = -INFINITY; int idx = 0x7fffffff;
         for (int p = lane; p < P; p += 64) {
-            const AmaxCand c = cand[(size_t)p * 16 + m];
+            AmaxCand c;
+            c.v = ld_f32<COH>(&cand[(size_t)p * 16 + m].v);
+            c.i = __float_as_int(ld_f32<COH>((const float*)&cand[(size_t)p * 16 + m].i));
             if (amax_better(c.v, c.i, v, idx)) { v = c.v; idx = c.i; }
         }
         for (int o = 32; o > 0; o >>= 1) {
@@ -81,6 +90,11 @@ __global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int 
         st->cycles += 1; st->drafted += kk; st->accepted += a;
         tokbuf[0] = win[a];
     }
+}
+__global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+                                                      DevState* st, int32_t* tokbuf, int32_t* out) {
+    __shared__ int win[16];
+    finish_block<false>(cand, P, M, argmax, mode, j_or_kk, st, tokbuf, out, win);
 }
 
 // ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double

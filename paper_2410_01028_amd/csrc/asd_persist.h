@@ -1,0 +1,118 @@
+// Persistent pass kernel: one launch runs a whole forward pass (embedding, every kept sublayer, LM head,
+// greedy choice / accept) on a grid that is resident all at once; between dependent steps the workgroups
+// meet at a grid barrier instead of ending a kernel.  Each step is the same block function the per-step
+// kernels call, looped over that step's virtual blocks, so both paths produce identical bits.
+//
+// Data exchanged between workgroups inside the kernel is written and read with device-scope relaxed
+// atomics (the per-XCD L2 caches are not coherent with each other); the barrier itself is an arrival
+// counter that only grows (target = arrivals expected so far), polled with a bounded spin: a barrier that
+// does not complete sets an error flag and lets every wave run on to the end, so the grid always drains.
+#pragma once
+#include "asd_attn.h"
+#include "asd_gemm.h"
+#include "asd_misc.h"
+
+enum { OP_EMBED = 0, OP_QKV = 1, OP_ATTN = 2, OP_MERGE = 3, OP_OPROJ = 4, OP_GU = 5, OP_DOWN = 6, OP_LM = 7, OP_FINISH = 8 };
+
+struct PassOp {
+    int32_t type;
+    int32_t grid;        // virtual blocks of a GEMM step
+    int32_t cls;         // ASD_K_* class (profiling / byte accounting on the host)
+    int32_t pad;
+    double bytes;        // algorithmic bytes of the step (host bookkeeping)
+    GemmArgs g;
+    AttnArgs t;
+};
+
+struct PassArgs {
+    const PassOp* ops;
+    int32_t n_ops;
+    int32_t M, RS, d;
+    const void* E;
+    const int32_t* tokens;
+    const float* g_first;
+    float* xres;
+    void* xb;
+    int64_t xb_plane;
+    float* part;
+    const AmaxCand* cand;
+    int32_t P_lm;
+    int32_t fin_mode, fin_arg;
+    int32_t* argmax;
+    DevState* st;
+    int32_t* tokbuf;
+    int32_t* out;
+    unsigned long long* bar;       // arrival counter, never reset
+    unsigned long long bar_base;   // its value when this launch starts
+    int32_t* err;
+};
+
+#define PASS_THREADS 512
+#define PASS_SPIN_LIMIT (1 << 20)
+
+__device__ __forceinline__ void grid_sync(unsigned long long* bar, unsigned long long target, int32_t* err) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0);                 // this wave's stores (all write-through) have completed
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __hip_atomic_fetch_add(bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > PASS_SPIN_LIMIT) { *err = 1; break; }
+        }
+    }
+    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+template <class T, int H>
+__global__ __launch_bounds__(PASS_THREADS) void pass_kernel(const PassArgs P) {
+    __shared__ float red[PASS_THREADS];
+    __shared__ int win[16];
+    using El = typename T::elem;
+    const int wg = blockIdx.x, G = gridDim.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    constexpr int NWV = PASS_THREADS / 64;
+    unsigned long long target = P.bar_base;
+    for (int i = 0; i < P.n_ops; ++i) {
+        const PassOp& op = P.ops[i];
+        switch (op.type) {
+            case OP_EMBED:
+                for (int vb = wg; vb < EMBED_SPLIT * P.M; vb += G)
+                    embed_block<T, true>((const El*)P.E, P.tokens, P.d, P.g_first, P.xres, P.xb, (size_t)P.xb_plane, P.RS, P.part,
+                                         vb % EMBED_SPLIT, vb / EMBED_SPLIT, red);
+                break;
+            case OP_QKV:
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_QKV, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                break;
+            case OP_OPROJ:
+            case OP_DOWN:
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_RES, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                break;
+            case OP_GU:
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_GU, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                break;
+            case OP_LM:
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_LM, 2, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                break;
+            case OP_ATTN: {
+                const int last = op.t.st->pos + op.t.pos_off + op.t.M - 1;
+                const int nc = last / ASD_CHUNK + 1, units = nc * op.t.n_h;
+                for (int u = w * G + wg; u < units; u += G * NWV) attn_block<T, H, true>(op.t, u % nc, u / nc, lane);
+                break;
+            }
+            case OP_MERGE: {
+                const int groups = (op.t.M + ATT_RB - 1) / ATT_RB, units = groups * op.t.n_h;
+                const int pos0 = op.t.st->pos + op.t.pos_off;
+                for (int u = w * G + wg; u < units; u += G * NWV)
+                    attn_merge_rows<T, H, true>(op.t, u % op.t.n_h, (u / op.t.n_h) * ATT_RB, pos0, lane);
+                break;
+            }
+            case OP_FINISH:
+                if (wg == 0)
+                    finish_block<true>(P.cand, P.P_lm, P.M, P.argmax, P.fin_mode, P.fin_arg, P.st, P.tokbuf, P.out, win);
+                break;
+        }
+        if (i + 1 < P.n_ops) { target += G; grid_sync(P.bar, target, P.err); }
+    }
+}
