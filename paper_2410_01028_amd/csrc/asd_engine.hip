@@ -6,6 +6,7 @@
 #include "asd_common.h"
 #include "asd_gemm.h"
 #include "asd_misc.h"
+#include "asd_persist.h"
 
 #include <chrono>
 #include <cmath>
@@ -72,6 +73,15 @@ struct asd_engine {
     bool acs_valid;
     DevState* h_st;                     // pinned
     std::map<std::vector<int>, hipGraphExec_t> graphs;
+    // persistent pass kernel
+    bool persistent;
+    int pass_grid;
+    char* ops_region;
+    size_t ops_bytes, ops_used;
+    std::map<std::vector<int>, std::pair<const PassOp*, int>> op_cache;
+    unsigned long long* bar;
+    unsigned long long bar_count;
+    int32_t* bar_err;
     std::vector<uint8_t> graph_mask;
     std::string err;
 };
@@ -127,10 +137,8 @@ GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     if (epi == EPI_RES && tiles > 1024) g.TN = 2;
     g.kmajor = (cls == ASD_K_QKV || cls == ASD_K_DOWN || cls == ASD_K_LMHEAD) ? 1 : 0;
     g.kint = g.kmajor;
-    const int maxnw = (epi == EPI_RES) ? 16 : 8;
-    g.NW = 4;
-    for (int nw = maxnw; nw > 4; nw /= 2)
-        if ((long)((tiles + g.TN - 1) / g.TN) * nw <= 8192 && KB / nw >= 4) { g.NW = nw; break; }
+    g.NW = 8;     // every class: the persistent pass kernel runs 8-wave workgroups and must reduce in the same order
+    (void)KB;
     static const char* names[] = {"", "qkv", "", "", "o", "gu", "down", "lm"};
     if (const char* env = getenv("ASD_TUNE")) {
         std::string e(env), key = std::string(names[cls]) + "=";
@@ -148,7 +156,7 @@ struct Plan {
     size_t embed, lm, g_final, layer0, layer_stride, wqkv, wo, wg, wu, wd, g_attn, g_mlp;
     size_t kv, kv_layer, page_table;
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
-        argmax, tokbuf, out_tokens, st, staging, staging_bytes, total;
+        argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
 };
@@ -213,6 +221,9 @@ Plan make_plan(const asd_config& c) {
     p.tokbuf = take(64 * 4);
     p.out_tokens = take((size_t)(p.n_pages * c.page_tokens + 64) * 4);
     p.st = take(sizeof(DevState));
+    p.bar = take(16 * 8 * (2 + 2 * 8));      // barrier words of the persistent kernel, one per 128-byte line
+    p.ops_bytes = align_up((size_t)(2 * c.n_layers * 3 + 8) * sizeof(PassOp) * 24);     // ~24 cached step lists
+    p.ops = take(p.ops_bytes);
     size_t biggest = (size_t)c.vocab * c.d_model;
     if ((size_t)c.d_ffn * c.d_model > biggest) biggest = (size_t)c.d_ffn * c.d_model;
     if ((size_t)qd * c.d_model > biggest) biggest = (size_t)qd * c.d_model;
@@ -356,35 +367,34 @@ struct Prof {
     void end() { if (p) hipEventRecord(p->ev.back(), s); }
 };
 
-int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
-                    Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0) {
+// The steps of one forward pass of M rows (first row at cache position st->pos + pos_off) under a skip mask:
+// a removed sublayer contributes no step at all.  The same list drives the per-step kernels and the
+// persistent pass kernel.
+void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_for_bytes, std::vector<PassOp>& ops) {
     const asd_config& c = e->c;
-    Prof pr{profiler, e->stream};
     double cls_bytes[ASD_K_COUNT];
-    pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // per-sublayer figures: divide the full-model totals by L
+    pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // full-model totals; per-sublayer figures divide by L
     const double L = c.n_layers;
-    const float inv_d = 1.f / (float)c.d_model;
     int RS = 1;
     while (RS < M) RS *= 2;
-
-    pr.begin(ASD_K_EMBED, 0);
-    if (c.dtype == ASD_DT_BF16)
-        embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model,
-                                                                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
-    else
-        embed_kernel<F32><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model,
-                                                                       next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
-    pr.end();
+    ops.clear();
+    auto push = [&](int type, int cls, int grid, double bytes) -> PassOp& {
+        PassOp op{};
+        op.type = type; op.cls = cls; op.grid = grid; op.bytes = bytes;
+        ops.push_back(op);
+        return ops.back();
+    };
+    push(OP_EMBED, ASD_K_EMBED, EMBED_SPLIT * M, 0);
 
     GemmArgs base{};
-    base.M = M; base.RS = RS; base.ssq = e->ssq; base.inv_d = inv_d; base.eps = c.rms_eps;
+    base.M = M; base.RS = RS; base.ssq = e->ssq; base.inv_d = 1.f / (float)c.d_model; base.eps = c.rms_eps;
     base.xres = e->xres; base.xb = e->xb; base.part = e->part; base.d = c.d_model;
     base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.q = e->q; base.page_table = e->page_table;
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
     base.xb_plane = (int64_t)e->KBd * 64 * e->KE; base.hmid_plane = (int64_t)e->KBf * 64 * e->KE;
     base.q_plane = (int64_t)c.n_heads * c.head_dim * ASD_ROWS;
     base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part;
-    // the cosine tap still open: partials of the last residual-add kernel and where its cosine goes
+    // the cosine tap still open: partials of the last residual-add step and where its cosine goes
     // (the embedding leaves EMBED_SPLIT partials of ||x||^2 and no cosine to finish)
     int open_P = EMBED_SPLIT, open_sub = -1;
     auto consume = [&](GemmArgs& g) {
@@ -399,67 +409,138 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
         const Layer& ly = e->layers[l];
         if (!(mask && mask[2 * l])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64; a.n_tiles = e->qkv_tiles; layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
+            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64; a.n_tiles = e->qkv_tiles;
+            layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
             consume(a);
-            pr.begin(ASD_K_QKV, cls_bytes[ASD_K_QKV] / L);
-            if (!launch_gemm<EPI_QKV>(e, e->g_qkv, a)) return fail(e, ASD_E_STATE, "no QKV kernel for this shape");
-            pr.end();
+            push(OP_QKV, ASD_K_QKV, e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
 
             AttnArgs t{};
-            t.q = e->q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv; t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
+            t.q = e->q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
+            t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
             t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
-            t.fuse_merge = M <= ATT_RB;          // few rows: the last chunk wave of a head merges; else a row-parallel kernel
-            pr.begin(ASD_K_ATTN, cls_bytes[ASD_K_ATTN] / L);
-            launch_attn(e, t, nc, false);
-            pr.end();
-            if (!t.fuse_merge) {
-                pr.begin(ASD_K_ATTN_MERGE, 0);
-                launch_attn(e, t, nc, true);
-                pr.end();
-            }
+            t.fuse_merge = M <= ATT_RB;          // few rows: the last chunk wave of a head merges; else a row-parallel step
+            push(OP_ATTN, ASD_K_ATTN, 0, cls_bytes[ASD_K_ATTN] / L).t = t;
+            if (!t.fuse_merge) push(OP_MERGE, ASD_K_ATTN_MERGE, 0, 0).t = t;
 
             GemmArgs o = base;
-            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16; layout(o, e->g_o, c.d_model / 16, e->KBq);
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16;
+            layout(o, e->g_o, c.d_model / 16, e->KBq);
             o.g_next = next_gain(e, mask, 2 * l);
             open_P = e->g_o.grid; open_sub = 2 * l;
-            pr.begin(ASD_K_OPROJ, cls_bytes[ASD_K_OPROJ] / L);
-            if (!launch_gemm<EPI_RES>(e, e->g_o, o)) return fail(e, ASD_E_STATE, "no O-projection kernel for this shape");
-            pr.end();
+            push(OP_OPROJ, ASD_K_OPROJ, e->g_o.grid, cls_bytes[ASD_K_OPROJ] / L).g = o;
         }
         if (!(mask && mask[2 * l + 1])) {
             GemmArgs a = base;
             a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64;
             a.n_tiles = c.d_ffn / 16; layout(a, e->g_gu, c.d_ffn / 16, e->KBd);
             consume(a);
-            pr.begin(ASD_K_GATEUP, cls_bytes[ASD_K_GATEUP] / L);
-            if (!launch_gemm<EPI_GU>(e, e->g_gu, a)) return fail(e, ASD_E_STATE, "no gate/up kernel for this shape");
-            pr.end();
+            push(OP_GU, ASD_K_GATEUP, e->g_gu.grid, cls_bytes[ASD_K_GATEUP] / L).g = a;
 
             GemmArgs dn = base;
-            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16; layout(dn, e->g_down, c.d_model / 16, e->KBf);
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16;
+            layout(dn, e->g_down, c.d_model / 16, e->KBf);
             dn.g_next = next_gain(e, mask, 2 * l + 1);
             open_P = e->g_down.grid; open_sub = 2 * l + 1;
-            pr.begin(ASD_K_DOWN, cls_bytes[ASD_K_DOWN] / L);
-            if (!launch_gemm<EPI_RES>(e, e->g_down, dn)) return fail(e, ASD_E_STATE, "no down-projection kernel for this shape");
-            pr.end();
+            push(OP_DOWN, ASD_K_DOWN, e->g_down.grid, cls_bytes[ASD_K_DOWN] / L).g = dn;
         }
     }
     GemmArgs lm = base;
-    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.x_plane = (int64_t)e->KBd * 64; lm.n_tiles = c.vocab / 16; layout(lm, e->g_lm, c.vocab / 16, e->KBd);
+    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.x_plane = (int64_t)e->KBd * 64; lm.n_tiles = c.vocab / 16;
+    layout(lm, e->g_lm, c.vocab / 16, e->KBd);
     consume(lm);
-    pr.begin(ASD_K_LMHEAD, cls_bytes[ASD_K_LMHEAD]);
-    if (!launch_gemm<EPI_LM>(e, e->g_lm, lm)) return fail(e, ASD_E_STATE, "no LM-head kernel for this shape");
-    pr.end();
-    pr.begin(ASD_K_FINISH, 0);
-    finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg, e->st,
-                                            e->tokbuf, e->out_tokens);
-    pr.end();
+    push(OP_LM, ASD_K_LMHEAD, e->g_lm.grid, cls_bytes[ASD_K_LMHEAD]).g = lm;
+    push(OP_FINISH, ASD_K_FINISH, 1, 0);
+}
+
+// Run a pass as one launch per step.
+int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d_tokens, int M, const uint8_t* mask, int nc,
+                 Profiler* profiler, int fin_mode, int fin_arg) {
+    const asd_config& c = e->c;
+    Prof pr{profiler, e->stream};
+    int RS = 1;
+    while (RS < M) RS *= 2;
+    for (const PassOp& op : ops) {
+        pr.begin(op.cls, op.bytes);
+        bool ok = true;
+        switch (op.type) {
+            case OP_EMBED:
+                if (c.dtype == ASD_DT_BF16)
+                    embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model,
+                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
+                else
+                    embed_kernel<F32><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model,
+                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
+                break;
+            case OP_QKV: ok = launch_gemm<EPI_QKV>(e, e->g_qkv, op.g); break;
+            case OP_OPROJ: ok = launch_gemm<EPI_RES>(e, e->g_o, op.g); break;
+            case OP_DOWN: ok = launch_gemm<EPI_RES>(e, e->g_down, op.g); break;
+            case OP_GU: ok = launch_gemm<EPI_GU>(e, e->g_gu, op.g); break;
+            case OP_LM: ok = launch_gemm<EPI_LM>(e, e->g_lm, op.g); break;
+            case OP_ATTN: launch_attn(e, op.t, nc, false); break;
+            case OP_MERGE: launch_attn(e, op.t, nc, true); break;
+            case OP_FINISH:
+                finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg,
+                                                           e->st, e->tokbuf, e->out_tokens);
+                break;
+        }
+        pr.end();
+        if (!ok) return fail(e, ASD_E_STATE, "no kernel instance for step type %d of this shape", op.type);
+    }
     hipError_t r = hipGetLastError();
     if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
     return ASD_OK;
+}
+
+template <class T, int H> const void* pass_kernel_ptr() { return (const void*)pass_kernel<T, H>; }
+const void* pass_kernel_for(const asd_engine* e) {
+    const int H = e->c.head_dim;
+    if (e->c.dtype == ASD_DT_BF16) return H == 32 ? pass_kernel_ptr<BF16, 32>() : H == 64 ? pass_kernel_ptr<BF16, 64>() : pass_kernel_ptr<BF16, 128>();
+    return H == 32 ? pass_kernel_ptr<F32, 32>() : H == 64 ? pass_kernel_ptr<F32, 64>() : pass_kernel_ptr<F32, 128>();
+}
+
+// Run a pass as one persistent launch.  The step list lives in a device-side cache keyed by what it depends on.
+int launch_persistent(asd_engine* e, const std::vector<PassOp>& ops, const std::vector<int>& key, const int32_t* d_tokens, int M,
+                      const uint8_t* mask, int fin_mode, int fin_arg) {
+    const asd_config& c = e->c;
+    auto it = e->op_cache.find(key);
+    if (it == e->op_cache.end()) {
+        const size_t bytes = ops.size() * sizeof(PassOp);
+        if (e->ops_used + bytes > e->ops_bytes) { e->op_cache.clear(); e->ops_used = 0; CK(e, hipStreamSynchronize(e->stream)); }
+        if (bytes > e->ops_bytes) return fail(e, ASD_E_NOMEM, "step list of %zu bytes exceeds the reserved %zu", bytes, e->ops_bytes);
+        char* dst = e->ops_region + e->ops_used;
+        CK(e, hipMemcpyAsync(dst, ops.data(), bytes, hipMemcpyHostToDevice, e->stream));
+        CK(e, hipStreamSynchronize(e->stream));          // the source vector is the caller's
+        it = e->op_cache.emplace(key, std::make_pair((const PassOp*)dst, (int)ops.size())).first;
+        e->ops_used += align_up(bytes);
+    }
+    int RS = 1;
+    while (RS < M) RS *= 2;
+    PassArgs P{};
+    P.ops = it->second.first; P.n_ops = it->second.second; P.M = M; P.RS = RS; P.d = c.d_model;
+    P.E = e->embed; P.tokens = d_tokens; P.g_first = next_gain(e, mask, -1); P.xres = e->xres; P.xb = e->xb;
+    P.xb_plane = (int64_t)e->KBd * 64 * e->KE; P.part = e->part;
+    P.cand = (const AmaxCand*)e->amax_part; P.P_lm = e->g_lm.grid; P.fin_mode = fin_mode; P.fin_arg = fin_arg; P.argmax = e->argmax;
+    P.st = e->st; P.tokbuf = e->tokbuf; P.out = e->out_tokens;
+    P.bar = e->bar; P.bar_base = e->bar_count; P.err = e->bar_err;
+    e->bar_count += (unsigned long long)(P.n_ops - 1);
+    void* args[] = {&P};
+    CK(e, hipLaunchCooperativeKernel(pass_kernel_for(e), dim3(e->pass_grid), dim3(PASS_THREADS), args, 0, e->stream));
+    return ASD_OK;
+}
+
+int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
+                    Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0) {
+    std::vector<PassOp> ops;
+    build_pass(e, M, pos_off, mask, ctx_for_bytes, ops);
+    if (e->persistent && !profiler) {
+        std::vector<int> key{M, pos_off, (int)(d_tokens - e->tokbuf)};
+        for (int j = 0; j < 2 * e->c.n_layers; ++j) key.push_back(mask ? (mask[j] ? 1 : 0) : 0);
+        return launch_persistent(e, ops, key, d_tokens, M, mask, fin_mode, fin_arg);
+    }
+    return launch_steps(e, ops, d_tokens, M, mask, nc, profiler, fin_mode, fin_arg);
 }
 
 bool weights_ready(asd_engine* e) {
@@ -468,6 +549,15 @@ bool weights_ready(asd_engine* e) {
 }
 
 int chunks_for(int last_pos) { return last_pos / ASD_CHUNK + 1; }
+
+// after a synchronisation: did a grid barrier of the persistent kernel give up?
+int check_pass_error(asd_engine* e) {
+    if (!e->persistent) return ASD_OK;
+    int32_t flag = 0;
+    CK(e, hipMemcpy(&flag, e->bar_err, 4, hipMemcpyDeviceToHost));
+    if (flag) return fail(e, ASD_E_HIP, "a grid barrier of the persistent pass kernel timed out");
+    return ASD_OK;
+}
 
 int check_tokens(asd_engine* e, const int32_t* t, int n) {
     for (int i = 0; i < n; ++i)
@@ -531,8 +621,26 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->amax_part = (AmaxPart*)(A + p.amax_part); e->argmax = (int32_t*)(A + p.argmax);
     e->tokbuf = (int32_t*)(A + p.tokbuf); e->out_tokens = (int32_t*)(A + p.out_tokens); e->st = (DevState*)(A + p.st);
     e->staging = A + p.staging; e->staging_bytes = p.staging_bytes;
+    e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
+    e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
     e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_valid = false; e->h_st = nullptr;
+    // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
+    e->persistent = false; e->pass_grid = 0;
+    {
+        const bool shapes_ok = p.g_qkv.TN == 1 && p.g_o.TN == 1 && p.g_gu.TN == 1 && p.g_down.TN == 1 && p.g_lm.TN == 2 &&
+                               p.g_qkv.NW == 8 && p.g_o.NW == 8 && p.g_gu.NW == 8 && p.g_down.NW == 8 && p.g_lm.NW == 8;
+        const char* env = getenv("ASD_PERSIST");
+        int nb = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (shapes_ok && env && atoi(env) > 0 && hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, pass_kernel_for(e), PASS_THREADS, 0) == hipSuccess && nb > 0 &&
+            prop.cooperativeLaunch) {
+            const int per_cu = nb < atoi(env) ? nb : atoi(env);
+            e->pass_grid = prop.multiProcessorCount * per_cu;
+            e->persistent = true;
+        }
+    }
 
     hipError_t r = hipHostMalloc((void**)&e->h_st, sizeof(DevState), hipHostMallocDefault);
     if (r != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(r)); }
@@ -754,6 +862,8 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
         CK(e, hipMemcpyAsync(lg.data(), e->logits, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
     }
     CK(e, hipStreamSynchronize(e->stream));
+    rc = check_pass_error(e);
+    if (rc) return rc;
     if (logits) memcpy(logits, lg.data(), lg.size() * 4);
     for (int j = 0; j < L2; ++j) {
         const bool skipped = mask && mask[j];
@@ -792,6 +902,8 @@ int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_
         CK(e, hipMemcpyAsync(lg.data(), e->logits + (size_t)(rows - 1) * e->c.vocab, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
     }
     CK(e, hipStreamSynchronize(e->stream));
+    rc = check_pass_error(e);
+    if (rc) return rc;
     for (int j = 0; j < L2; ++j) e->acs[j] = (float)(acc[j] / n);
     e->acs_valid = true;
     if (cos_out) memcpy(cos_out, e->acs.data(), (size_t)L2 * 4);
@@ -843,7 +955,7 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
         const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
         const int nc = chunks_for(e->kv_len + kk);
         int rc = ASD_OK;
-        if (p->use_graphs) {
+        if (p->use_graphs && !e->persistent) {
             const std::vector<int> key{kk, nc};
             auto it = e->graphs.find(key);
             if (it == e->graphs.end()) {
@@ -872,6 +984,7 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
     }
     CK(e, hipMemcpyAsync(out, e->out_tokens, (size_t)n_more * 4, hipMemcpyDeviceToHost, e->stream));
     CK(e, hipStreamSynchronize(e->stream));
+    { const int rc2 = check_pass_error(e); if (rc2) return rc2; }
     const auto t1 = std::chrono::steady_clock::now();
     if (stats) {
         stats->cycles = e->h_st->cycles; stats->drafted = e->h_st->drafted; stats->accepted = e->h_st->accepted;
@@ -934,7 +1047,7 @@ int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* mask, int32_t re
     if (rc) return rc;
     const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
     hipGraphExec_t ge = nullptr;
-    if (use_graph) {
+    if (use_graph && !e->persistent) {
         hipGraph_t g = nullptr;
         CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
         rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);

@@ -5,7 +5,7 @@
 //
 // Data exchanged between workgroups inside the kernel is written and read with device-scope relaxed
 // atomics (the per-XCD L2 caches are not coherent with each other); the barrier itself is an arrival
-// counter that only grows (target = arrivals expected so far), polled with a bounded spin: a barrier that
+// counter hierarchy that only grows, polled with a bounded spin: a barrier that
 // does not complete sets an error flag and lets every wave run on to the end, so the grid always drains.
 #pragma once
 #include "asd_attn.h"
@@ -42,23 +42,40 @@ struct PassArgs {
     DevState* st;
     int32_t* tokbuf;
     int32_t* out;
-    unsigned long long* bar;       // arrival counter, never reset
-    unsigned long long bar_base;   // its value when this launch starts
+    unsigned long long* bar;       // barrier words (see grid_sync), never reset
+    unsigned long long bar_base;   // barriers completed before this launch
     int32_t* err;
 };
 
 #define PASS_THREADS 512
 #define PASS_SPIN_LIMIT (1 << 20)
 
-__device__ __forceinline__ void grid_sync(unsigned long long* bar, unsigned long long target, int32_t* err) {
+// Two-level barrier: workgroups arrive on one of BAR_GROUPS group counters (own cache lines); the last of a
+// group arrives on the top counter; the workgroup that completes the top counter publishes the new epoch in
+// every group's release word, which is what the group's members poll.  All counters only grow.
+//   bar[0]                      top arrivals
+//   bar[16 * (1 + g)]           arrivals of group g
+//   bar[16 * (1 + BAR_GROUPS + g)]   release epoch of group g
+#define BAR_GROUPS 8
+__device__ __forceinline__ void grid_sync(unsigned long long* bar, unsigned long long epoch, int32_t* err) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);                 // this wave's stores (all write-through) have completed
     __syncthreads();
     if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned G = gridDim.x, g = blockIdx.x % BAR_GROUPS;
+        const unsigned gsize = G / BAR_GROUPS + (g < G % BAR_GROUPS ? 1u : 0u);
+        unsigned long long* garr = bar + 16 * (1 + g);
+        unsigned long long* grel = bar + 16 * (1 + BAR_GROUPS + g);
+        const unsigned long long old = __hip_atomic_fetch_add(garr, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old + 1 == epoch * gsize) {            // last of the group
+            const unsigned long long t = __hip_atomic_fetch_add(bar, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t + 1 == epoch * BAR_GROUPS)       // last group: release everyone
+                for (int q = 0; q < BAR_GROUPS; ++q)
+                    __hip_atomic_store(bar + 16 * (1 + BAR_GROUPS + q), epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         int spins = 0;
-        while (__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(1);
+        while (__hip_atomic_load(grel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < epoch) {
+            __builtin_amdgcn_s_sleep(4);
             if (++spins > PASS_SPIN_LIMIT) { *err = 1; break; }
         }
     }
@@ -67,13 +84,13 @@ __device__ __forceinline__ void grid_sync(unsigned long long* bar, unsigned long
 }
 
 template <class T, int H>
-__global__ __launch_bounds__(PASS_THREADS) void pass_kernel(const PassArgs P) {
+__global__ __launch_bounds__(PASS_THREADS, 4) void pass_kernel(const PassArgs P) {
     __shared__ float red[PASS_THREADS];
     __shared__ int win[16];
     using El = typename T::elem;
     const int wg = blockIdx.x, G = gridDim.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     constexpr int NWV = PASS_THREADS / 64;
-    unsigned long long target = P.bar_base;
+    unsigned long long epoch = P.bar_base;
     for (int i = 0; i < P.n_ops; ++i) {
         const PassOp& op = P.ops[i];
         switch (op.type) {
@@ -113,6 +130,6 @@ __global__ __launch_bounds__(PASS_THREADS) void pass_kernel(const PassArgs P) {
                     finish_block<true>(P.cand, P.P_lm, P.M, P.argmax, P.fin_mode, P.fin_arg, P.st, P.tokbuf, P.out, win);
                 break;
         }
-        if (i + 1 < P.n_ops) { target += G; grid_sync(P.bar, target, P.err); }
+        if (i + 1 < P.n_ops) { epoch += 1; grid_sync(P.bar, epoch, P.err); }
     }
 }

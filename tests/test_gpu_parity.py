@@ -297,3 +297,23 @@ def test_graph_replays_match_eager():
         eng.forward(prompt[:3], eng.kv_len, commit=False)        # eager work between replays
         ms, _ = eng.time_pass(2, mask, 3, True)
         assert ms > 0
+
+
+def test_persistent_pass_kernel_matches_step_kernels_bitwise(monkeypatch):
+    """The one-launch-per-pass kernel (development switch ASD_PERSIST) runs the same block functions with
+    coherent accesses and grid barriers: logits, cosines and generated tokens must equal the per-step path."""
+    shape = MID16
+    toks = si.prompt(8, 150, shape.vocab)
+    mask = np.zeros(2 * shape.n_layers, np.uint8); mask[1] = mask[4] = 1
+    results = []
+    for persist in ("0", "1"):
+        monkeypatch.setenv("ASD_PERSIST", persist)
+        eng = asd.Engine(asd.make_config(shape, 320)).init_synthetic(5)
+        first, acs, lg = eng.prefill(toks[:140], want_logits=True)
+        a = eng.forward(toks[140:145], 140, commit=False)
+        b = eng.forward(toks[140:141], 140, mask, commit=False)
+        out, st, _ = eng.generate(toks[:100], 20, 3, fixed_mask=mask, use_graphs=False)
+        results.append((first, acs, lg, a["logits"], a["cos_rows"], b["logits"], out, st["accepted"]))
+        eng.close()
+    for x, y in zip(*results):
+        assert np.array_equal(np.asarray(x), np.asarray(y))
