@@ -1,14 +1,15 @@
 // Decode attention over the paged KV cache for up to 16 query rows (split-KV + fixed-order merges).
 //
-// Work item = (query head, chunk of 64 keys at absolute positions [64c, 64c+64)), one wave, so
-// that a head's chunks spread over many compute units (one unit alone cannot pull a head's
-// K/V fast enough).  Scores S[key][row] and the output O[dim][row] are both matrix-core
-// products with the 16 query rows as columns, so a row's result never depends on how many
-// rows the call has; chunk boundaries are absolute.  The wave that finishes a head's last
-// outstanding chunk merges that head's chunk partials in ascending chunk order.  Partials and
-// the arrival counter are exchanged with device-scope relaxed atomic stores / loads (served
-// past the non-coherent per-XCD L2), ordered by waiting for the stores to complete before the
-// counter is bumped; no cache-wide fence is involved.
+// A wave handles one chunk of 64 keys at absolute positions [64c, 64c+64) of one query head; scores
+// S[key][row] and the output O[dim][row] are both matrix-core products with the 16 query rows as
+// columns, so a row's result never depends on how many rows the call has.  Four waves (a group of
+// 4 consecutive chunks = 256 keys, again at absolute positions) merge their results through LDS in
+// ascending chunk order; the groups of a head spread over many compute units (one unit alone cannot
+// pull a head's K/V fast enough).  When the context spans several groups, each group's partial goes to
+// global memory and the groups are merged in ascending order: by the group that arrives last (passes
+// of at most ATT_RB rows) or by a row-parallel merge step.  Partials and the arrival counter are
+// exchanged with device-scope relaxed atomic stores / loads (served past the non-coherent per-XCD
+// L2), ordered by waiting for the stores to complete before the counter is bumped; no cache-wide fence.
 // A row at position p sees keys 0..p (causal among the rows of the call as well).
 //
 // Cache page layout per (page, kv head): K[page_tokens][h] then V transposed [h][page_tokens],
@@ -21,9 +22,12 @@
 #pragma once
 #include "asd_common.h"
 
+#define ATT_GW 4                           // waves (chunks) per group
+#define ATT_GROUP (ATT_GW * ASD_CHUNK)     // keys per group
+#define ATT_RH 4                           // rows per LDS merge pass
 #define ATT_RB 2                           // rows per merge round
-#define ATT_CB 16                          // chunk partials requested per merge round
-#define ATT_NCL 4                          // chunk statistics per lane: up to 256 chunks (16K positions) per head
+#define ATT_CB 16                          // group partials requested per merge round
+#define ATT_NCL 4                          // group statistics per lane: up to 256 groups (64K positions) per head
 
 // device-scope coherent scalar accesses (relaxed atomics: served past the per-XCD L2)
 __device__ __forceinline__ void coherent_store(float* p, float v) {
@@ -45,11 +49,11 @@ struct AttnArgs {
     const DevState* st;
     int32_t pos_off, M, RS;   // rows in use, row stride of the activation buffers
     int32_t n_h, n_kv, h, page_tokens;
-    int32_t nc_stride;        // chunks per head in the partial buffers
+    int32_t nc_stride;        // groups per head in the partial buffers
     float scale;              // 1/sqrt(h)
-    float* o_part;            // [n_h][nc_stride][16][h] unnormalised chunk outputs
-    float* ml_part;           // [n_h][nc_stride][16][2] (chunk max, chunk sum)
-    unsigned* arrivals;       // [n_h] chunks finished per head (returns to 0)
+    float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
+    float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
+    unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
     int32_t fuse_merge;       // the last wave of a head to arrive merges (passes of at most ATT_RB rows)
     void* out;                // tiled activation [n_h*h]
 };
@@ -61,7 +65,7 @@ template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
 }
 template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 
-// Merge the chunk partials of rows m0 .. m0+ATT_RB-1 (those below a.M) of one head, in ascending chunk order, and
+// Merge the group partials of rows m0 .. m0+ATT_RB-1 (those below a.M) of one head, in ascending chunk order, and
 // write the normalised output: chunk statistics with one chunk per lane, outputs with two head dims per lane; all
 // loads of a round are requested before any is used.  One wave.
 template <class T, int H, bool COH>
@@ -73,7 +77,7 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int
 #pragma unroll
         for (int rb = 0; rb < ATT_RB; ++rb) {
             const int mm = m0 + rb;
-            nc[rb] = mm < a.M ? (pos0 + mm) / ASD_CHUNK + 1 : 0;
+            nc[rb] = mm < a.M ? (pos0 + mm) / ATT_GROUP + 1 : 0;
             const float* ml = a.ml_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * 2;
             const float* opm = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * H + 2 * lane;
 #pragma unroll
@@ -131,138 +135,181 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int
     }
 }
 
-// One wave's work item: chunk c of query head `head` (COH as in gemm_block).
+// One group (ATT_GW waves) of one query head.  Every thread of the calling workgroup must call this the same
+// number of times (it synchronises the workgroup); `valid` = false makes the group a no-op, hw is the wave's
+// index inside its group.  so: [ATT_GW][ATT_RH][H] floats, sml: [ATT_GW][16][2] floats, s_old: 1 word, per group.
 template <class T, int H, bool COH>
-__device__ __forceinline__ void attn_block(const AttnArgs& a, const int c, const int head, const int lane) {
+__device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, const int head, const bool valid, const int hw,
+                                           const int lane, float* so, float* sml, unsigned* s_old) {
     using E = typename T::elem;
     constexpr int KE = T::KE;
     constexpr int HS = H / (4 * KE);            // fragment steps over the head dimension
     constexpr int HT = H / 16;                  // output tiles over the head dimension
     constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
+    constexpr int NP = T::NP;
     const int g = lane >> 4, m = lane & 15, r = lane & 15;
     const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
-    if (c * ASD_CHUNK > last) return;                    // no row of this call sees this chunk
-    const int kvh = head / (a.n_h / a.n_kv);
-    const int PT = a.page_tokens;
-    const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
-    const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
-    const E* Vp = Kp + (size_t)PT * H;
-    const E* qp = (const E*)a.q + (size_t)head * H * a.RS;
+    const int n_groups = last / ATT_GROUP + 1;
+    const int c = grp * ATT_GW + hw;
+    const bool active = valid && c * ASD_CHUNK <= last;
 
-    // ---- scores: 4 tiles of 16 keys
-    constexpr int NP = T::NP;
-    u32x4 qf[HS][NP];
+    f32x4 o[HT];
 #pragma unroll
-    for (int hs = 0; hs < HS; ++hs)
-#pragma unroll
-        for (int pl = 0; pl < NP; ++pl)
-            qf[hs][pl] = m < a.M ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE)) : u32x4{0u, 0u, 0u, 0u};
-    f32x4 s[4];
-#pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-        s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        const E* krow = Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE;
-#pragma unroll
-        for (int hs = 0; hs < HS; ++hs) {
-            const u32x4 kf = __builtin_nontemporal_load((const u32x4*)(krow + hs * 4 * KE));
-#pragma unroll
-            for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf, qf[hs][pl]);
-        }
-    }
-    // ---- V^T fragments (independent of the scores: issued early)
-    u32x4 vf[HT][KST];
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-            vf[ht][ks] = __builtin_nontemporal_load(
-                (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
+    for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mx = -INFINITY, l = 0.f;
+    if (active) {
+        const int kvh = head / (a.n_h / a.n_kv);
+        const int PT = a.page_tokens;
+        const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
+        const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
+        const E* Vp = Kp + (size_t)PT * H;
+        const E* qp = (const E*)a.q + (size_t)head * H * a.RS;
 
-    // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
-    const int row_pos = pos0 + m;
-    float mx = -INFINITY;
+        // ---- scores: 4 tiles of 16 keys
+        u32x4 qf[HS][NP];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+        for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
-            const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
-            s[kt][j] = v;
-            mx = fmaxf(mx, v);
-        }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    float l = 0.f;
+            for (int pl = 0; pl < NP; ++pl)
+                qf[hs][pl] = m < a.M ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE))
+                                     : u32x4{0u, 0u, 0u, 0u};
+        f32x4 s[4];
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt)
+        for (int kt = 0; kt < 4; ++kt) {
+            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const E* krow = Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
-            s[kt][j] = p;
-            l += p;
-        }
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-
-    // ---- output: O[dim][row] += V^T[dim][keys] * P[keys][row]; P goes in as hi + lo planes for bf16
-    u32x4 pf[KST][NP];
-    if constexpr (KE == 8) {
+            for (int hs = 0; hs < HS; ++hs) {
+                const u32x4 kf = __builtin_nontemporal_load((const u32x4*)(krow + hs * 4 * KE));
 #pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) {
-                const f32x4& t = s[2 * ks + (w2 >> 1)];
-                const float p0 = t[(w2 & 1) * 2], p1 = t[(w2 & 1) * 2 + 1];
-                const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
-                const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
-                pf[ks][0][w2] = h0 | (h1 << 16);
-                pf[ks][1][w2] = l0 | (l1 << 16);
+                for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf, qf[hs][pl]);
             }
-    } else {
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
-    }
-    float* op = a.o_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * H;
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) {
-        f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-            for (int pl = 0; pl < NP; ++pl) mma16<T>(o, vf[ht][ks], pf[ks][pl]);
-        if (m < a.M) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) coherent_store(op + ht * 16 + 4 * g + j, o[j]);
         }
-    }
-    float* mlp = a.ml_part + (((size_t)head * a.nc_stride + c) * ASD_ROWS + m) * 2;
-    if (g == 0 && m < a.M) { coherent_store(mlp, mx); coherent_store(mlp + 1, l); }
+        // ---- V^T fragments (independent of the scores: issued early)
+        u32x4 vf[HT][KST];
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+                vf[ht][ks] = __builtin_nontemporal_load(
+                    (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
 
-    if (!a.fuse_merge) return;
-    // ---- arrival: the wave that completes the head's last chunk merges
-    const int n_chunks = last / ASD_CHUNK + 1;
+        // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
+        const int row_pos = pos0 + m;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
+                const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
+                s[kt][j] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
+                s[kt][j] = p;
+                l += p;
+            }
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+
+        // ---- output: O[dim][row] += V^T[dim][keys] * P[keys][row]; P goes in as hi + lo planes for bf16
+        u32x4 pf[KST][NP];
+        if constexpr (KE == 8) {
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    const f32x4& t = s[2 * ks + (w2 >> 1)];
+                    const float p0 = t[(w2 & 1) * 2], p1 = t[(w2 & 1) * 2 + 1];
+                    const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
+                    const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
+                    pf[ks][0][w2] = h0 | (h1 << 16);
+                    pf[ks][1][w2] = l0 | (l1 << 16);
+                }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) mma16<T>(o[ht], vf[ht][ks], pf[ks][pl]);
+    }
+    if (g == 0) { sml[(hw * ASD_ROWS + m) * 2] = mx; sml[(hw * ASD_ROWS + m) * 2 + 1] = l; }
+
+    // ---- merge the group's chunks through LDS, ATT_RH rows per pass, ascending chunk order
+    for (int m0 = 0; m0 < a.M; m0 += ATT_RH) {
+        if (m >= m0 && m < m0 + ATT_RH) {
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[((size_t)hw * ATT_RH + (m - m0)) * H + ht * 16 + 4 * g] = o[ht];
+        }
+        __syncthreads();
+        for (int idx = hw * 64 + lane; idx < ATT_RH * H; idx += ATT_GW * 64) {
+            const int rr = idx / H, hd = idx % H, mm = m0 + rr;
+            if (!valid || mm >= a.M) continue;
+            float gmax = -INFINITY;
+#pragma unroll
+            for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + mm) * 2]);
+            float L = 0.f, acc = 0.f;
+            if (gmax != -INFINITY) {
+#pragma unroll
+                for (int ww = 0; ww < ATT_GW; ++ww) {          // a chunk the row does not see has max -inf: weight 0
+                    const float wgt = __expf(sml[(ww * ASD_ROWS + mm) * 2] - gmax);
+                    L += sml[(ww * ASD_ROWS + mm) * 2 + 1] * wgt;
+                    acc += so[((size_t)ww * ATT_RH + rr) * H + hd] * wgt;
+                }
+            }
+            if (n_groups == 1) {
+                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + hd, mm, acc / L);
+            } else {
+                const size_t row = ((size_t)head * a.nc_stride + grp) * ASD_ROWS + mm;
+                coherent_store(a.o_part + row * H + hd, acc);
+                if (hd == 0) { coherent_store(a.ml_part + row * 2, gmax); coherent_store(a.ml_part + row * 2 + 1, L); }
+            }
+        }
+        __syncthreads();
+    }
+    if (n_groups == 1 || !a.fuse_merge) return;
+
+    // ---- arrival: the group that completes the head's last outstanding group merges the groups
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __builtin_amdgcn_s_waitcnt(0);                   // this wave's partial stores have completed
-    unsigned old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    old = __shfl(old, 0);
-    if ((int)old != n_chunks - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-    // ---- merge (fused only for passes of at most ATT_RB rows; larger passes run the row-parallel merge)
-    attn_merge_rows<T, H, COH>(a, head, 0, pos0, lane);
+    __syncthreads();
+    if (hw == 0 && lane == 0) {
+        *s_old = valid ? __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xffffffffu;
+    }
+    __syncthreads();
+    if ((int)*s_old == n_groups - 1 && hw == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        attn_merge_rows<T, H, COH>(a, head, 0, pos0, lane);
+    }
+    __syncthreads();
 }
 
 template <class T, int H>
-__global__ __launch_bounds__(64) void attn_kernel(const AttnArgs a) {
-    attn_block<T, H, false>(a, blockIdx.x, blockIdx.y, threadIdx.x);
+__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
+    __shared__ float so[ATT_GW * ATT_RH * H];
+    __shared__ float sml[ATT_GW * ASD_ROWS * 2];
+    __shared__ unsigned s_old;
+    if ((int)blockIdx.x * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;       // no row of this call sees this group
+    attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
 }
 
 // Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
 template <class T, int H>
 __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
-    attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, a.st->pos + a.pos_off, threadIdx.x);
+    const int pos0 = a.st->pos + a.pos_off;
+    if ((pos0 + a.M - 1) / ATT_GROUP == 0) return;      // a single group: attn_kernel already wrote the output
+    attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, pos0, threadIdx.x);
 }

@@ -171,7 +171,7 @@ Plan make_plan(const asd_config& c) {
     p.KBq = (qd + kblk - 1) / kblk;
     p.KBf = (c.d_ffn + kblk - 1) / kblk;
     p.n_pages = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
-    p.nc_stride = p.n_pages * c.page_tokens / ASD_CHUNK;
+    p.nc_stride = (p.n_pages * c.page_tokens + ATT_GROUP - 1) / ATT_GROUP;
     p.qkv_tiles = (qd + 2 * kvd) / 16;
     p.g_qkv = pick_cfg(EPI_QKV, ASD_K_QKV, p.qkv_tiles, p.KBd);
     p.g_o = pick_cfg(EPI_RES, ASD_K_OPROJ, c.d_model / 16, p.KBq);
@@ -314,11 +314,11 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
 
 template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
     const int H = e->c.head_dim;
-    const dim3 gp(nc, e->c.n_heads), gm(e->c.n_heads, (a.M + ATT_RB - 1) / ATT_RB);
+    const dim3 gp((nc + ATT_GW - 1) / ATT_GW, e->c.n_heads), gm(e->c.n_heads, (a.M + ATT_RB - 1) / ATT_RB);
 #define ATT(h)                                                                  \
     if (H == h) {                                                               \
         if (merge) attn_merge_kernel<T, h><<<gm, 64, 0, e->stream>>>(a);        \
-        else attn_kernel<T, h><<<gp, 64, 0, e->stream>>>(a);                    \
+        else attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                    \
     }
     ATT(32) ATT(64) ATT(128)
 #undef ATT

@@ -87,6 +87,9 @@ template <class T, int H>
 __global__ __launch_bounds__(PASS_THREADS, 4) void pass_kernel(const PassArgs P) {
     __shared__ float red[PASS_THREADS];
     __shared__ int win[16];
+    __shared__ float att_so[(PASS_THREADS / 64) * ATT_RH * H];
+    __shared__ float att_ml[(PASS_THREADS / 64) * ASD_ROWS * 2];
+    __shared__ unsigned att_old[PASS_THREADS / 64 / ATT_GW];
     using El = typename T::elem;
     const int wg = blockIdx.x, G = gridDim.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     constexpr int NWV = PASS_THREADS / 64;
@@ -113,14 +116,24 @@ __global__ __launch_bounds__(PASS_THREADS, 4) void pass_kernel(const PassArgs P)
                 for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_LM, 2, NWV, 4, true>(op.g, vb); __syncthreads(); }
                 break;
             case OP_ATTN: {
+                // two groups of ATT_GW waves per workgroup; every wave makes the same number of trips (the group
+                // function synchronises the workgroup), idle groups pass valid = false
+                constexpr int GPW = NWV / ATT_GW;
                 const int last = op.t.st->pos + op.t.pos_off + op.t.M - 1;
-                const int nc = last / ASD_CHUNK + 1, units = nc * op.t.n_h;
-                for (int u = w * G + wg; u < units; u += G * NWV) attn_block<T, H, true>(op.t, u % nc, u / nc, lane);
+                const int ng = last / ATT_GROUP + 1, units = ng * op.t.n_h;
+                const int half = w / ATT_GW, hw = w % ATT_GW;
+                for (int base = 0; base < units; base += G * GPW) {
+                    const int u = base + half * G + wg;
+                    const bool valid = u < units;
+                    attn_group<T, H, true>(op.t, valid ? u % ng : 0, valid ? u / ng : 0, valid, hw, lane,
+                                           att_so + (size_t)half * ATT_GW * ATT_RH * H, att_ml + half * ATT_GW * ASD_ROWS * 2, att_old + half);
+                }
                 break;
             }
             case OP_MERGE: {
-                const int groups = (op.t.M + ATT_RB - 1) / ATT_RB, units = groups * op.t.n_h;
                 const int pos0 = op.t.st->pos + op.t.pos_off;
+                if ((pos0 + op.t.M - 1) / ATT_GROUP == 0) break;     // a single group: the attention step wrote the output
+                const int groups = (op.t.M + ATT_RB - 1) / ATT_RB, units = groups * op.t.n_h;
                 for (int u = w * G + wg; u < units; u += G * NWV)
                     attn_merge_rows<T, H, true>(op.t, u % op.t.n_h, (u / op.t.n_h) * ATT_RB, pos0, lane);
                 break;
