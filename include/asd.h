@@ -51,11 +51,12 @@ typedef struct asd_engine asd_engine;   /* opaque, library-owned host object */
 
 /*
  * Model and cache shape.  Constraints (else ASD_E_INVAL): d_model, d_ffn, vocab,
- * n_heads*head_dim multiples of 16; head_dim a multiple of 32 (bf16) / 16 (fp32)
- * and <= 256; n_heads a multiple of n_kv_heads; page_tokens a multiple of 64;
- * 1 <= max_rows <= ASD_MAX_ROWS; max_seq >= 1 (rounded up to whole pages).
- * dtype is the storage type of weights, activations fed to the matrix cores and
- * the KV cache; the residual stream and every accumulation are fp32.
+ * n_heads*head_dim multiples of 16; head_dim 32, 64 or 128; n_heads a multiple
+ * of n_kv_heads; page_tokens a multiple of 64; 1 <= max_rows <= ASD_MAX_ROWS;
+ * max_seq >= 1 (rounded up to whole pages).
+ * dtype is the storage type of weights and of the KV cache and the operand type
+ * of the matrix cores (with bf16, activations go in as a hi + lo pair of bf16
+ * values); the residual stream and every accumulation are fp32.
  */
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -196,6 +197,11 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
  * by HIP events on the engine's stream (as a captured graph when use_graph != 0);
  * *bytes (optional) = algorithmic bytes one such pass must read.
  * asd_profile_forward: one such pass with an event pair around every launch.
+ * asd_time_step_class: the steps of one kernel class (ASD_K_QKV .. ASD_K_LMHEAD, one per kept layer) of a full-model
+ * pass launched back to back, reps rounds, bracketed by one pair of HIP events on the engine's stream: average
+ * microseconds per launch (weights differ from launch to launch, so no launch finds its weights cached) and the
+ * algorithmic bytes one launch must read.  The steps run out of their usual order: the pass's activations are
+ * scratch afterwards.
  * asd_copy_bench: average milliseconds of a plain device copy kernel moving
  * nbytes (read nbytes + write nbytes) inside the arena's scratch region; used to
  * calibrate byte counters and to report the achievable HBM rate.
@@ -203,6 +209,7 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
 int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, int32_t reps, int32_t use_graph,
                   double* ms_avg, double* bytes);
 int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, asd_kernel_times* out);
+int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps, double* us_avg, double* bytes_per_launch);
 int asd_copy_bench(asd_engine* e, size_t nbytes, int32_t reps, double* ms_avg);
 
 #ifdef __cplusplus

@@ -84,6 +84,7 @@ def lib():
         L.asd_time_pass.argtypes = [vp, i32, vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.asd_profile_forward.argtypes = [vp, i32, vp, ctypes.POINTER(KernelTimes)]
         L.asd_copy_bench.argtypes = [vp, sz, i32, ctypes.POINTER(ctypes.c_double)]
+        L.asd_time_step_class.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
 
@@ -256,6 +257,12 @@ class Engine:
                for i, name in enumerate(KERNEL_CLASSES)}
         out["ms_total"] = kt.ms_total
         return out
+
+    def time_step_class(self, name: str, n_rows: int = 1, reps: int = 10):
+        """(average microseconds per launch, algorithmic bytes per launch) of one kernel class launched back to back."""
+        us, by = ctypes.c_double(), ctypes.c_double()
+        self._ck(lib().asd_time_step_class(self._h, KERNEL_CLASSES.index(name), n_rows, reps, ctypes.byref(us), ctypes.byref(by)))
+        return us.value, by.value
 
     def copy_bench(self, nbytes: int, reps: int = 10) -> float:
         ms = ctypes.c_double()

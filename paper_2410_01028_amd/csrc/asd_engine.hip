@@ -1117,6 +1117,41 @@ int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* mask, asd_
     return ASD_OK;
 }
 
+int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps, double* us_avg, double* bytes_per_launch) {
+    if (!e) return ASD_E_INVAL;
+    if (!us_avg || reps < 1 || cls <= ASD_K_EMBED || cls >= ASD_K_FINISH || cls == ASD_K_ATTN_MERGE)
+        return fail(e, ASD_E_INVAL, "us_avg is NULL, reps < 1 or the class is not a timed step class");
+    int rc = bench_checks(e, n_rows);
+    if (rc) return rc;
+    rc = bench_tokens(e, n_rows);
+    if (rc) return rc;
+    const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
+    std::vector<PassOp> all, sel;
+    build_pass(e, n_rows, 0, nullptr, ctx, all);
+    rc = launch_steps(e, all, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);     // valid inputs for every step
+    if (rc) return rc;
+    double bytes = 0.0;
+    for (const PassOp& op : all) if (op.cls == cls) { sel.push_back(op); bytes += op.bytes; }
+    if (sel.empty()) return fail(e, ASD_E_INVAL, "the pass has no step of class %d", cls);
+    rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);     // warm-up
+    hipEvent_t a = nullptr, b = nullptr;
+    if (!rc) { hipEventCreate(&a); hipEventCreate(&b); hipEventRecord(a, e->stream); }
+    for (int i = 0; i < reps && !rc; ++i) rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);
+    float ms = 0.f;
+    if (!rc) {
+        hipEventRecord(b, e->stream);
+        hipError_t r2 = hipEventSynchronize(b);
+        if (r2 == hipSuccess) r2 = hipEventElapsedTime(&ms, a, b);
+        if (r2 != hipSuccess) rc = fail(e, ASD_E_HIP, "event timing: %s", hipGetErrorString(r2));
+    }
+    if (a) hipEventDestroy(a);
+    if (b) hipEventDestroy(b);
+    if (rc) return rc;
+    *us_avg = (double)ms * 1e3 / ((double)reps * sel.size());
+    if (bytes_per_launch) *bytes_per_launch = bytes / sel.size();
+    return ASD_OK;
+}
+
 int asd_copy_bench(asd_engine* e, size_t nbytes, int32_t reps, double* ms_avg) {
     if (!e) return ASD_E_INVAL;
     if (!ms_avg || reps < 1 || nbytes < 16 || nbytes % 16) return fail(e, ASD_E_INVAL, "nbytes must be a positive multiple of 16, reps >= 1");
