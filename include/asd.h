@@ -157,13 +157,19 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
                 int32_t commit, float* logits, float* cos, float* cos_rows, int32_t* argmax);
 
 /*
- * Prompt pass (Section 3.2): resets the cache, runs all n prompt tokens through the
- * full model in chunks of max_rows rows, returns the first generated token, the
- * ACS of every sublayer over the n rows (cos_out [2L], optional) and the logits of
- * the last row (last_logits [vocab], optional).  The ACS is kept in the engine for
- * a following asd_decode with mask_mode 0.
+ * Prompt pass (Section 3.2, Eq. 1-2): resets the cache, runs all n prompt tokens
+ * through the full model, returns the first generated token, the ACS of every
+ * sublayer over the n rows (cos_out [2L], optional) and the logits of the last row
+ * (last_logits [vocab], optional).  The ACS is kept in the engine for a following
+ * asd_decode with mask_mode 0.  Prompts longer than max_rows are processed in blocks
+ * of up to 512 rows, layer by layer, with large-M matrix-core contractions (every
+ * weight is read once per block); shorter ones as one pass of the decode kernels.
+ * asd_prefill_chunked always takes the decode kernels, max_rows rows at a time (the
+ * same results up to rounding; kept for cross-checks and as the reference for timing).
+ * All pointers are host memory.
  */
 int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits);
+int asd_prefill_chunked(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits);
 
 /*
  * Algorithm 1 (ADMG), a pure host function: c_attn [L] are the attention sublayers'

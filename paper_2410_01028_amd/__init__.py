@@ -78,6 +78,7 @@ def lib():
         L.asd_kv_len.argtypes = [vp]
         L.asd_forward.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
         L.asd_prefill.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.asd_prefill_chunked.argtypes = [vp, vp, i32, vp, vp, vp]
         L.asd_admg.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, vp]
         L.asd_decode.argtypes = [vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
         L.asd_generate.argtypes = [vp, vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
@@ -203,12 +204,13 @@ class Engine:
                                    cos.ctypes.data, cos_rows.ctypes.data, am.ctypes.data))
         return {"logits": logits, "cos": cos, "cos_rows": cos_rows, "argmax": am}
 
-    def prefill(self, tokens, want_logits: bool = False):
+    def prefill(self, tokens, want_logits: bool = False, chunked: bool = False):
         tok = np.ascontiguousarray(tokens, dtype=np.int32)
         first = ctypes.c_int32()
         cos = np.empty(self.L2, dtype=np.float32)
         lg = np.empty(self.cfg.vocab, dtype=np.float32) if want_logits else None
-        self._ck(lib().asd_prefill(self._h, tok.ctypes.data, tok.size, ctypes.byref(first), cos.ctypes.data, _ptr(lg)))
+        fn = lib().asd_prefill_chunked if chunked else lib().asd_prefill
+        self._ck(fn(self._h, tok.ctypes.data, tok.size, ctypes.byref(first), cos.ctypes.data, _ptr(lg)))
         return int(first.value), cos, lg
 
     @staticmethod

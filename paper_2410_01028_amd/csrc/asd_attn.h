@@ -56,7 +56,26 @@ struct AttnArgs {
     unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
     int32_t fuse_merge;       // the last wave of a head to arrive merges (passes of at most ATT_RB rows)
     void* out;                // tiled activation [n_h*h]
+    // prompt processing: blockIdx.z = 16-row chunk of a block of batch_rows rows (0 = a single call); element /
+    // float strides from one chunk's buffers to the next.  Needs fuse_merge == 0.
+    int32_t batch_rows;
+    int64_t zq, zout, zopart, zml;
 };
+
+// the arguments of chunk z of a batched call (rows 16z .. of the block), or `a` itself for a single call
+template <class T> __device__ __forceinline__ AttnArgs attn_item(const AttnArgs& a, int z) {
+    AttnArgs b = a;
+    if (a.batch_rows) {
+        using E = typename T::elem;
+        b.q = (const E*)a.q + (size_t)z * a.zq;
+        b.out = (E*)a.out + (size_t)z * a.zout;
+        b.o_part = a.o_part + (size_t)z * a.zopart;
+        b.ml_part = a.ml_part + (size_t)z * a.zml;
+        b.pos_off = a.pos_off + 16 * z;
+        b.M = min(16, a.batch_rows - 16 * z);
+    }
+    return b;
+}
 
 // key (0..63, relative to the chunk) held by score tile kt, tile row r
 template <class T> __device__ __forceinline__ int score_key(int kt, int r);
@@ -298,7 +317,8 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
 }
 
 template <class T, int H>
-__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a0) {
+    const AttnArgs a = attn_item<T>(a0, blockIdx.z);
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
@@ -308,7 +328,8 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
 
 // Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
 template <class T, int H>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a0) {
+    const AttnArgs a = attn_item<T>(a0, blockIdx.z);
     const int pos0 = a.st->pos + a.pos_off;
     if ((pos0 + a.M - 1) / ATT_GROUP == 0) return;      // a single group: attn_kernel already wrote the output
     attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, pos0, threadIdx.x);

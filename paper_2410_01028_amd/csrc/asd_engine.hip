@@ -7,6 +7,7 @@
 #include "asd_gemm.h"
 #include "asd_misc.h"
 #include "asd_persist.h"
+#include "asd_prefill.h"
 
 #include <chrono>
 #include <cmath>
@@ -23,6 +24,7 @@ namespace {
 thread_local std::string g_create_error;
 
 struct GemmCfg { int TN, NW, grid, kmajor, kint; };
+struct PfCfg { int NC, KS; };      // prompt GEMM: 16-row chunks per workgroup, K slices
 
 struct Layer {
     char *wqkv, *wo, *wg, *wu, *wd;
@@ -65,6 +67,11 @@ struct asd_engine {
     DevState* st;
     char* staging;
     size_t staging_bytes;
+    // prompt-block workspace
+    int32_t* pf_tok;
+    float *pf_xres, *pf_raw, *pf_ssq, *pf_rscale, *pf_cos_rows, *pf_o_part, *pf_ml_part;
+    void *pf_xb, *pf_q, *pf_attn_out, *pf_hmid;
+    PfCfg pf_qkv, pf_o, pf_gu, pf_down;
     // launch shapes
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
     // host state
@@ -157,6 +164,7 @@ struct Plan {
     size_t kv, kv_layer, page_table;
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
         argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total;
+    size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_o_part, pf_ml_part, pf_xb, pf_q, pf_attn_out, pf_hmid;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
 };
@@ -229,6 +237,19 @@ Plan make_plan(const asd_config& c) {
     if ((size_t)qd * c.d_model > biggest) biggest = (size_t)qd * c.d_model;
     p.staging_bytes = align_up(biggest * p.es + 4096);
     p.staging = take(p.staging_bytes);
+    // prompt-block workspace: PF_ROWS rows as PF_CHUNKS chunks of 16
+    p.pf_tok = take((size_t)PF_ROWS * 4);
+    p.pf_xres = take((size_t)PF_ROWS * c.d_model * 4);
+    p.pf_raw = take((size_t)PF_MAX_KSPLIT * PF_ROWS * c.d_model * 4);
+    p.pf_ssq = take((size_t)PF_ROWS * 4);
+    p.pf_rscale = take((size_t)PF_ROWS * 4);
+    p.pf_cos_rows = take((size_t)2 * c.n_layers * PF_ROWS * 4);
+    p.pf_o_part = take((size_t)PF_CHUNKS * c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
+    p.pf_ml_part = take((size_t)PF_CHUNKS * c.n_heads * p.nc_stride * ASD_ROWS * 8);
+    p.pf_xb = take((size_t)PF_CHUNKS * p.KBd * frag * NPL);
+    p.pf_q = take((size_t)PF_CHUNKS * p.KBq * frag * NPL);
+    p.pf_attn_out = take((size_t)PF_CHUNKS * p.KBq * frag * NPL);
+    p.pf_hmid = take((size_t)PF_CHUNKS * p.KBf * frag * NPL);
     p.total = off;
     return p;
 }
@@ -574,6 +595,156 @@ void drop_graphs(asd_engine* e) {
 
 int capacity(const asd_engine* e) { return e->n_pages * e->c.page_tokens; }
 
+// ------------------------------------------------------------------ prompt blocks
+// Launch shape of a prompt GEMM class: NC 16-row chunks per workgroup and K slices (slices only for the two
+// residual-add GEMMs).  ASD_PF_TUNE (development aid) overrides, e.g. "qkv=8,1;o=8,2;gu=4,1;down=8,4".
+PfCfg pf_pick(const char* name, int nc, int ks) {
+    PfCfg g{nc, ks};
+    if (const char* env = getenv("ASD_PF_TUNE")) {
+        std::string e(env), key = std::string(name) + "=";
+        size_t pos = (";" + e).find(";" + key);
+        if (pos != std::string::npos) {
+            int a, b;
+            if (sscanf(e.c_str() + pos + key.size(), "%d,%d", &a, &b) == 2 && (a == 2 || a == 4 || a == 8) && b >= 1 && b <= PF_MAX_KSPLIT) { g.NC = a; g.KS = b; }
+        }
+    }
+    return g;
+}
+
+constexpr int PF_NW = 4;                 // waves per workgroup of a prompt GEMM
+template <int EPI> constexpr int pf_na() { return EPI == PF_GU ? 2 : 4; }     // weight tiles per wave (gate and up each, for PF_GU)
+
+template <class T, int EPI> bool launch_pf_gemm_t(hipStream_t s, const PfCfg& g, PfArgs a, int n_chunks) {
+    constexpr int NA = pf_na<EPI>();
+    a.n_fb = (a.n_tiles + PF_NW * NA - 1) / (PF_NW * NA);
+    a.n_rb = (n_chunks + g.NC - 1) / g.NC;
+    a.ksplit = EPI == PF_RAW ? g.KS : 1;
+    if (a.ksplit > a.KB) a.ksplit = a.KB;
+    const unsigned grid = (unsigned)((a.n_fb + 7) / 8 * 8 * a.n_rb * a.ksplit);
+    switch (g.NC) {
+        case 2: pf_gemm_kernel<T, EPI, NA, 2, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
+        case 4: pf_gemm_kernel<T, EPI, NA, 4, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
+        case 8: pf_gemm_kernel<T, EPI, NA, 8, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
+    }
+    return false;
+}
+template <int EPI> bool launch_pf_gemm(asd_engine* e, const PfCfg& g, const PfArgs& a, int n_chunks) {
+    return e->c.dtype == ASD_DT_BF16 ? launch_pf_gemm_t<BF16, EPI>(e->stream, g, a, n_chunks) : launch_pf_gemm_t<F32, EPI>(e->stream, g, a, n_chunks);
+}
+
+template <class T> void launch_attn_batch_t(asd_engine* e, const AttnArgs& a, int n_chunks, int last_pos) {
+    const int H = e->c.head_dim, groups = last_pos / ATT_GROUP + 1;
+    const dim3 gp(groups, e->c.n_heads, n_chunks), gm(e->c.n_heads, (ASD_ROWS + ATT_RB - 1) / ATT_RB, n_chunks);
+#define ATT(h)                                                                  \
+    if (H == h) {                                                               \
+        attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                \
+        if (groups > 1) attn_merge_kernel<T, h><<<gm, 64, 0, e->stream>>>(a);   \
+    }
+    ATT(32) ATT(64) ATT(128)
+#undef ATT
+}
+
+template <class T> void launch_pf_rows_t(asd_engine* e, int what, int rows, int n_chunks, int ksplit, const float* gain, float* cos_row, int tail_row) {
+    const asd_config& c = e->c;
+    using El = typename T::elem;
+    const int64_t xb_plane = (int64_t)PF_CHUNKS * e->KBd * 64 * e->KE, xb_chunk = (int64_t)e->KBd * 64 * e->KE;
+    const float inv_d = 1.f / (float)c.d_model;
+    if (what == 0)
+        pf_embed_kernel<T><<<n_chunks * 16, 256, 0, e->stream>>>((const El*)e->embed, e->pf_tok, rows, c.d_model, gain, e->pf_xres, e->pf_xb,
+                                                                 xb_plane, xb_chunk, e->pf_ssq, e->pf_rscale, inv_d, c.rms_eps);
+    else if (what == 1)
+        pf_resid_kernel<T><<<rows, 256, 0, e->stream>>>(e->pf_raw, ksplit, c.d_model, e->pf_xres, e->pf_xb, xb_plane, xb_chunk, gain, e->pf_ssq,
+                                                        e->pf_rscale, cos_row, inv_d, c.rms_eps);
+    else
+        pf_tail_kernel<T><<<1, 256, 0, e->stream>>>(e->pf_xres, e->pf_ssq, tail_row, c.d_model, e->g_final, e->xres, e->xb,
+                                                    (int64_t)e->KBd * 64 * e->KE, e->part);
+}
+void launch_pf_rows(asd_engine* e, int what, int rows, int n_chunks, int ksplit, const float* gain, float* cos_row, int tail_row) {
+    if (e->c.dtype == ASD_DT_BF16) launch_pf_rows_t<BF16>(e, what, rows, n_chunks, ksplit, gain, cos_row, tail_row);
+    else launch_pf_rows_t<F32>(e, what, rows, n_chunks, ksplit, gain, cos_row, tail_row);
+}
+
+// The whole prompt, block by block and layer by layer; leaves the last row's logits / greedy token in row 0 of the
+// decode buffers and the cosine sums of all rows in cos_acc (the caller cleared it).  Enqueue only.
+int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
+    const asd_config& c = e->c;
+    const int L = c.n_layers, KE = e->KE;
+    const int qd = c.n_heads * c.head_dim;
+    auto wl = [&](PfArgs& a, const GemmCfg& cfg, int total_tiles, int KB) {
+        a.n_tiles = total_tiles; a.KB = KB; a.w_tile_stride = cfg.kmajor ? 1 : KB; a.w_kb_stride = cfg.kmajor ? total_tiles : 1;
+    };
+    int rows = 0;
+    for (int r0 = 0; r0 < n; r0 += rows) {
+        rows = n - r0 < PF_ROWS ? n - r0 : PF_ROWS;
+        const int n_chunks = (rows + 15) / 16;
+        CK(e, hipMemcpyAsync(e->pf_tok, tokens + r0, (size_t)rows * 4, hipMemcpyHostToDevice, e->stream));
+        set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, r0, 0, 0, 0);
+        launch_pf_rows(e, 0, rows, n_chunks, 1, e->layers[0].g_attn, nullptr, 0);
+
+        PfArgs base{};
+        base.rows = rows; base.rscale = e->pf_rscale; base.raw = e->pf_raw;
+        base.pos0 = r0; base.rope = e->rope; base.q = e->pf_q; base.page_table = e->page_table;
+        base.q_plane = (int64_t)PF_CHUNKS * e->KBq * 64 * KE; base.q_chunk = (int64_t)e->KBq * 64 * KE;
+        base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
+        base.hmid = e->pf_hmid; base.hmid_plane = (int64_t)PF_CHUNKS * e->KBf * 64 * KE; base.hmid_chunk = (int64_t)e->KBf * 64 * KE;
+        for (int l = 0; l < L; ++l) {
+            const Layer& ly = e->layers[l];
+            bool ok = true;
+            PfArgs a = base;
+            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->pf_xb; a.x_plane = (int64_t)PF_CHUNKS * e->KBd * 64; a.x_chunk = (int64_t)e->KBd * 64;
+            wl(a, e->g_qkv, e->qkv_tiles, e->KBd);
+            a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
+            ok = ok && launch_pf_gemm<PF_QKV>(e, e->pf_qkv, a, n_chunks);
+
+            AttnArgs t{};
+            t.q = e->pf_q; t.q_plane = base.q_plane; t.out_plane = base.q_plane; t.kv = a.kv;
+            t.page_table = e->page_table; t.st = e->st; t.pos_off = 0; t.M = ASD_ROWS; t.RS = ASD_ROWS;
+            t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
+            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
+            t.o_part = e->pf_o_part; t.ml_part = e->pf_ml_part; t.arrivals = e->arrivals; t.out = e->pf_attn_out; t.fuse_merge = 0;
+            t.batch_rows = rows; t.zq = base.q_chunk; t.zout = base.q_chunk;
+            t.zopart = (int64_t)c.n_heads * e->nc_stride * ASD_ROWS * c.head_dim; t.zml = (int64_t)c.n_heads * e->nc_stride * ASD_ROWS * 2;
+            if (c.dtype == ASD_DT_BF16) launch_attn_batch_t<BF16>(e, t, n_chunks, r0 + rows - 1);
+            else launch_attn_batch_t<F32>(e, t, n_chunks, r0 + rows - 1);
+
+            PfArgs o = base;
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->pf_attn_out; o.x_plane = (int64_t)PF_CHUNKS * e->KBq * 64; o.x_chunk = (int64_t)e->KBq * 64;
+            wl(o, e->g_o, c.d_model / 16, e->KBq);
+            ok = ok && launch_pf_gemm<PF_RAW>(e, e->pf_o, o, n_chunks);
+            launch_pf_rows(e, 1, rows, n_chunks, e->pf_o.KS < e->KBq ? e->pf_o.KS : e->KBq, ly.g_mlp, e->pf_cos_rows + (size_t)(2 * l) * PF_ROWS, 0);
+
+            PfArgs gu = base;
+            gu.W = (const u32x4*)ly.wg; gu.W2 = (const u32x4*)ly.wu; gu.X = (const u32x4*)e->pf_xb; gu.x_plane = a.x_plane; gu.x_chunk = a.x_chunk;
+            wl(gu, e->g_gu, c.d_ffn / 16, e->KBd);
+            ok = ok && launch_pf_gemm<PF_GU>(e, e->pf_gu, gu, n_chunks);
+
+            PfArgs dn = base;
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->pf_hmid; dn.x_plane = (int64_t)PF_CHUNKS * e->KBf * 64; dn.x_chunk = (int64_t)e->KBf * 64;
+            wl(dn, e->g_down, c.d_model / 16, e->KBf);
+            ok = ok && launch_pf_gemm<PF_RAW>(e, e->pf_down, dn, n_chunks);
+            launch_pf_rows(e, 1, rows, n_chunks, e->pf_down.KS < e->KBf ? e->pf_down.KS : e->KBf, l + 1 < L ? e->layers[l + 1].g_attn : e->g_final,
+                           e->pf_cos_rows + (size_t)(2 * l + 1) * PF_ROWS, 0);
+            if (!ok) return fail(e, ASD_E_STATE, "no prompt GEMM instance for this launch shape");
+        }
+        pf_cos_sum_kernel<<<2 * L, 256, 0, e->stream>>>(e->pf_cos_rows, rows, e->cos_acc);
+        e->kv_len = r0 + rows;
+    }
+    // the last prompt row through the final norm and the LM head, as row 0 of a one-row pass
+    launch_pf_rows(e, 2, rows, 0, 1, nullptr, nullptr, rows - 1);
+    std::vector<PassOp> ops;
+    build_pass(e, 1, 0, nullptr, n, ops);
+    for (PassOp& op : ops) {
+        if (op.type != OP_LM) continue;
+        op.g.part_in = e->part; op.g.P_in = 1; op.g.fin_cos_rows = nullptr; op.g.fin_cos_acc = nullptr;
+        if (!launch_gemm<EPI_LM>(e, e->g_lm, op.g)) return fail(e, ASD_E_STATE, "no kernel instance for the LM head");
+    }
+    finish_kernel<<<1, 64, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, 1, e->argmax, FIN_NONE, 0, e->st, e->tokbuf, e->out_tokens);
+    hipError_t r = hipGetLastError();
+    if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
+    (void)qd;
+    return ASD_OK;
+}
+
 }  // namespace
 
 // =================================================================== C ABI
@@ -621,6 +792,11 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->amax_part = (AmaxPart*)(A + p.amax_part); e->argmax = (int32_t*)(A + p.argmax);
     e->tokbuf = (int32_t*)(A + p.tokbuf); e->out_tokens = (int32_t*)(A + p.out_tokens); e->st = (DevState*)(A + p.st);
     e->staging = A + p.staging; e->staging_bytes = p.staging_bytes;
+    e->pf_tok = (int32_t*)(A + p.pf_tok); e->pf_xres = (float*)(A + p.pf_xres); e->pf_raw = (float*)(A + p.pf_raw);
+    e->pf_ssq = (float*)(A + p.pf_ssq); e->pf_rscale = (float*)(A + p.pf_rscale); e->pf_cos_rows = (float*)(A + p.pf_cos_rows);
+    e->pf_o_part = (float*)(A + p.pf_o_part); e->pf_ml_part = (float*)(A + p.pf_ml_part);
+    e->pf_xb = A + p.pf_xb; e->pf_q = A + p.pf_q; e->pf_attn_out = A + p.pf_attn_out; e->pf_hmid = A + p.pf_hmid;
+    e->pf_qkv = pf_pick("qkv", 4, 1); e->pf_o = pf_pick("o", 8, 4); e->pf_gu = pf_pick("gu", 4, 1); e->pf_down = pf_pick("down", 8, 4);
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
@@ -875,7 +1051,7 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
     return ASD_OK;
 }
 
-int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits) {
+static int prefill_impl(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits, bool blocks) {
     if (!e) return ASD_E_INVAL;
     if (!tokens || !first_token) return fail(e, ASD_E_INVAL, "tokens or first_token is NULL");
     if (n < 1 || n > capacity(e)) return fail(e, ASD_E_INVAL, "prompt length %d outside [1, %d]", n, capacity(e));
@@ -885,12 +1061,19 @@ int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_
     const int L2 = 2 * e->c.n_layers;
     e->kv_len = 0; e->acs_valid = false;
     CK(e, hipMemsetAsync(e->cos_acc, 0, (size_t)L2 * 8, e->stream));
-    int rows = 0;
-    for (int p = 0; p < n; p += rows) {
-        rows = n - p < e->c.max_rows ? n - p : e->c.max_rows;
-        rc = forward_rows(e, tokens + p, rows, nullptr, nullptr);
+    int last_row = 0;
+    if (blocks) {
+        rc = prefill_blocks(e, tokens, n);
         if (rc) return rc;
-        e->kv_len = p + rows;
+    } else {
+        int rows = 0;
+        for (int p = 0; p < n; p += rows) {
+            rows = n - p < e->c.max_rows ? n - p : e->c.max_rows;
+            rc = forward_rows(e, tokens + p, rows, nullptr, nullptr);
+            if (rc) return rc;
+            e->kv_len = p + rows;
+        }
+        last_row = rows - 1;
     }
     std::vector<double> acc(L2);
     int32_t am[ASD_ROWS];
@@ -899,7 +1082,7 @@ int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_
     std::vector<float> lg;
     if (last_logits) {
         lg.resize(e->c.vocab);
-        CK(e, hipMemcpyAsync(lg.data(), e->logits + (size_t)(rows - 1) * e->c.vocab, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
+        CK(e, hipMemcpyAsync(lg.data(), e->logits + (size_t)last_row * e->c.vocab, lg.size() * 4, hipMemcpyDeviceToHost, e->stream));
     }
     CK(e, hipStreamSynchronize(e->stream));
     rc = check_pass_error(e);
@@ -908,8 +1091,16 @@ int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_
     e->acs_valid = true;
     if (cos_out) memcpy(cos_out, e->acs.data(), (size_t)L2 * 4);
     if (last_logits) memcpy(last_logits, lg.data(), lg.size() * 4);
-    *first_token = am[rows - 1];
+    *first_token = am[last_row];
     return ASD_OK;
+}
+
+int asd_prefill(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits) {
+    return prefill_impl(e, tokens, n, first_token, cos_out, last_logits, e && n > e->c.max_rows);
+}
+
+int asd_prefill_chunked(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits) {
+    return prefill_impl(e, tokens, n, first_token, cos_out, last_logits, false);
 }
 
 // one draft/verify/accept cycle, enqueue only: kk draft steps with the masked model, then a (kk+1)-row verify

@@ -1,0 +1,62 @@
+"""GPU parity of the prompt pass taken in blocks (large-M contractions) against the CPU oracle.
+
+What is checked after a prompt of n tokens: the ACS of every sublayer (Eq. 2; 1e-3 absolute), the last row's
+logits (2e-2 bf16 / 1e-4 fp32, inf-norm relative), the first greedy token where the oracle's top-2 gap is clear,
+and the KV cache the pass wrote, through a teacher-forced multi-row pass right behind it.  Prompt lengths
+cover a ragged last 16-row chunk, a ragged last workgroup row block, contexts that span several 256-key
+attention groups, and a prompt longer than one 512-row block.
+"""
+import numpy as np
+import pytest
+
+import asd_inputs as si
+from helpers import SMALL_GQA
+from test_gpu_parity import BF_GQA, MID16, MID32, TOL, COS_TOL, build_pair, check_forward, rel_err
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(si.SHAPES["tiny"], 37), (si.SHAPES["tiny"], 100), (SMALL_GQA, 77), (BF_GQA, 77), (BF_GQA, 130),
+         (MID32, 150), (MID16, 300), (MID16, 600)]
+
+
+@pytest.mark.parametrize("shape,n", CASES, ids=[f"{s.name}-{n}" for s, n in CASES])
+def test_blocked_prompt_pass_against_oracle(shape, n):
+    eng, orc = build_pair(shape, seed=4, max_seq=n + 40)
+    toks = si.prompt(5, n + 6, shape.vocab)
+    first, acs, lg = eng.prefill(toks[:n], want_logits=True)
+    assert eng.kv_len == n
+    o = orc.forward(toks[:n], 0)
+    assert np.abs(acs - o["cos"]).max() < COS_TOL
+    assert rel_err(lg, o["logits"][-1]) < TOL[shape.dtype]
+    top2 = np.sort(o["logits"][-1])[-2:]
+    if top2[1] - top2[0] > 2 * TOL[shape.dtype] * np.abs(o["logits"][-1]).max():
+        assert first == o["argmax"][-1]
+    check_forward(eng, orc, toks[n:n + 6], n, None, TOL[shape.dtype])
+
+
+@pytest.mark.parametrize("shape", [si.SHAPES["tiny"], MID16], ids=lambda s: s.name)
+def test_blocked_and_chunked_prompt_pass_agree(shape):
+    n = 210
+    eng = eng2 = None
+    W = list(si.all_tensors(shape, 9))
+    import paper_2410_01028_amd as asd
+    eng = asd.Engine(asd.make_config(shape, 256)).load(W)
+    eng2 = asd.Engine(asd.make_config(shape, 256)).load(W)
+    toks = si.prompt(1, n + 4, shape.vocab)
+    f1, acs1, lg1 = eng.prefill(toks[:n], want_logits=True)
+    f2, acs2, lg2 = eng2.prefill(toks[:n], want_logits=True, chunked=True)
+    tol = TOL[shape.dtype]
+    assert np.abs(acs1 - acs2).max() < COS_TOL
+    assert rel_err(lg1, lg2) < tol
+    a = eng.forward(toks[n:n + 4], n)["logits"]
+    b = eng2.forward(toks[n:n + 4], n)["logits"]
+    assert rel_err(a, b).max() < tol
+
+
+def test_short_prompts_take_the_decode_kernels():
+    shape = si.SHAPES["tiny"]
+    eng, orc = build_pair(shape, seed=2, max_seq=64)
+    toks = si.prompt(8, 16, shape.vocab)
+    first, acs, lg = eng.prefill(toks, want_logits=True)
+    first2, acs2, lg2 = eng.prefill(toks, want_logits=True, chunked=True)
+    assert first == first2 and np.array_equal(acs, acs2) and np.array_equal(lg, lg2)
