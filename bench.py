@@ -96,10 +96,13 @@ def main():
     prompt = si.prompt(seed, P, shape.vocab)
     L2 = 2 * shape.n_layers
 
-    t0 = time.time()
-    first, acs, _ = eng.prefill(prompt)
+    first, acs, _ = eng.prefill(prompt)          # untimed: first touch of every weight, lazy runtime set-up
     torch.cuda.synchronize()
-    t_prefill = time.time() - t0
+    t0 = time.time()
+    for _ in range(3):
+        first, acs, _ = eng.prefill(prompt)
+    torch.cuda.synchronize()
+    t_prefill = (time.time() - t0) / 3
 
     def decode_step(draft_len, **kw):
         eng.truncate(P)
@@ -126,9 +129,18 @@ def main():
                                f"({shape.n_kv_heads} KV) x {shape.head_dim}, FFN {shape.d_ffn}, vocab {shape.vocab}; "
                                f"batch 1, prompt {P}, {N} greedy tokens",
                    "mode": "plain greedy (draft length 0), decode phase after the prompt pass", "draft_len_spec": k},
-        "prefill_ms": round(t_prefill * 1e3, 1),
+        "prefill_ms": round(t_prefill * 1e3, 2),
         "e2e_tokens_per_s": round(N / (t_prefill + ms_per_step / 1e3), 2),
     }
+    # the prompt pass is the one matrix-core-bound step: flops of the weight contractions (each counted once, although
+    # bf16 activations go through the matrix cores as two planes) plus causal attention, against the dense bf16 peak
+    qd, kvd = shape.n_heads * shape.head_dim, shape.n_kv_heads * shape.head_dim
+    w_flop = 2.0 * P * shape.n_layers * (shape.d_model * (qd + 2 * kvd) + qd * shape.d_model + 3 * shape.d_model * shape.d_ffn)
+    a_flop = 2.0 * 2.0 * shape.n_layers * qd * P * (P + 1) / 2
+    out["prefill"] = {"ms": round(t_prefill * 1e3, 2), "prompt_tokens_per_s": round(P / t_prefill, 1),
+                      "model_TFLOPs": round((w_flop + a_flop) / t_prefill / 1e12, 1),
+                      "frac_of_bf16_mfma_peak": round((w_flop + a_flop) / t_prefill / 2.5e15, 4),
+                      "matrix_core_planes": 2 if shape.dtype else 1}
 
     # ---- roofline of the dominant kernel (gate/up projection GEMM), HIP events on the engine's stream
     reps = 5
@@ -172,15 +184,20 @@ def main():
         cp = eng.copy_bench(192 << 20, 10)
         out["copy_kernel_GBps"] = round(2 * (192 << 20) / cp / 1e6, 1)
         spec = {}
+        # Table 2's setting for Llama-2-7B; a cosine-only setting (no periodic rule) with the threshold moved to where
+        # this random-init model's ACS values lie; and the all-keep bracket (every draft accepted, no layer skipped)
         for name, kw in (("admg_a0.985_m3_n2", dict(alpha=0.985, m=3, n=2)),
+                         ("admg_a0.9999_m0_n0", dict(alpha=0.9999, m=0, n=0)),
                          ("all_keep", dict(fixed_mask=np.zeros(L2, np.uint8)))):
             decode_step(k, **kw)
             torch.cuda.synchronize()
             t0 = time.time()
             toks, st, used = decode_step(k, **kw)
             dt = time.time() - t0
-            spec[name] = {"tokens_per_s": round((N - 1) / dt, 2), "cycles": st["cycles"], "drafted": st["drafted"],
-                          "accepted": st["accepted"], "tokens_equal_plain": bool(np.array_equal(toks, plain))}
+            spec[name] = {"tokens_per_s": round((N - 1) / dt, 2), "speedup_vs_plain": round((N - 1) / dt / value, 3),
+                          "cycles": st["cycles"], "drafted": st["drafted"], "accepted": st["accepted"],
+                          "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()),
+                          "tokens_equal_plain": bool(np.array_equal(toks, plain))}
         out["speculative"] = spec
 
     eng.close()

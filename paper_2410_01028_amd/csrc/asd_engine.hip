@@ -24,7 +24,7 @@ namespace {
 thread_local std::string g_create_error;
 
 struct GemmCfg { int TN, NW, grid, kmajor, kint; };
-struct PfCfg { int NC, KS; };      // prompt GEMM: 16-row chunks per workgroup, K slices
+struct PfCfg { int NC, KS, PD; };      // prompt GEMM: 16-row chunks per workgroup, K slices
 
 struct Layer {
     char *wqkv, *wo, *wg, *wu, *wd;
@@ -599,13 +599,14 @@ int capacity(const asd_engine* e) { return e->n_pages * e->c.page_tokens; }
 // Launch shape of a prompt GEMM class: NC 16-row chunks per workgroup and K slices (slices only for the two
 // residual-add GEMMs).  ASD_PF_TUNE (development aid) overrides, e.g. "qkv=8,1;o=8,2;gu=4,1;down=8,4".
 PfCfg pf_pick(const char* name, int nc, int ks) {
-    PfCfg g{nc, ks};
+    PfCfg g{nc, ks, 1};
     if (const char* env = getenv("ASD_PF_TUNE")) {
         std::string e(env), key = std::string(name) + "=";
         size_t pos = (";" + e).find(";" + key);
         if (pos != std::string::npos) {
-            int a, b;
-            if (sscanf(e.c_str() + pos + key.size(), "%d,%d", &a, &b) == 2 && (a == 2 || a == 4 || a == 8) && b >= 1 && b <= PF_MAX_KSPLIT) { g.NC = a; g.KS = b; }
+            int a, b, d = 1;
+            if (sscanf(e.c_str() + pos + key.size(), "%d,%d,%d", &a, &b, &d) >= 2 && (a == 2 || a == 4 || a == 8) && b >= 1 && b <= PF_MAX_KSPLIT &&
+                (d == 1 || d == 2)) { g.NC = a; g.KS = b; g.PD = d; }
         }
     }
     return g;
@@ -621,11 +622,9 @@ template <class T, int EPI> bool launch_pf_gemm_t(hipStream_t s, const PfCfg& g,
     a.ksplit = EPI == PF_RAW ? g.KS : 1;
     if (a.ksplit > a.KB) a.ksplit = a.KB;
     const unsigned grid = (unsigned)((a.n_fb + 7) / 8 * 8 * a.n_rb * a.ksplit);
-    switch (g.NC) {
-        case 2: pf_gemm_kernel<T, EPI, NA, 2, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
-        case 4: pf_gemm_kernel<T, EPI, NA, 4, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
-        case 8: pf_gemm_kernel<T, EPI, NA, 8, PF_NW><<<grid, PF_NW * 64, 0, s>>>(a); return true;
-    }
+#define PFK(nc, pd) if (g.NC == nc && g.PD == pd) { pf_gemm_kernel<T, EPI, NA, nc, PF_NW, pd><<<grid, PF_NW * 64, 0, s>>>(a); return true; }
+    PFK(2, 1) PFK(4, 1) PFK(8, 1) PFK(2, 2) PFK(4, 2) PFK(8, 2)
+#undef PFK
     return false;
 }
 template <int EPI> bool launch_pf_gemm(asd_engine* e, const PfCfg& g, const PfArgs& a, int n_chunks) {
@@ -796,7 +795,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->pf_ssq = (float*)(A + p.pf_ssq); e->pf_rscale = (float*)(A + p.pf_rscale); e->pf_cos_rows = (float*)(A + p.pf_cos_rows);
     e->pf_o_part = (float*)(A + p.pf_o_part); e->pf_ml_part = (float*)(A + p.pf_ml_part);
     e->pf_xb = A + p.pf_xb; e->pf_q = A + p.pf_q; e->pf_attn_out = A + p.pf_attn_out; e->pf_hmid = A + p.pf_hmid;
-    e->pf_qkv = pf_pick("qkv", 4, 1); e->pf_o = pf_pick("o", 8, 4); e->pf_gu = pf_pick("gu", 4, 1); e->pf_down = pf_pick("down", 8, 4);
+    e->pf_qkv = pf_pick("qkv", 4, 1); e->pf_o = pf_pick("o", 4, 4); e->pf_gu = pf_pick("gu", 4, 1); e->pf_down = pf_pick("down", 4, 4);
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;

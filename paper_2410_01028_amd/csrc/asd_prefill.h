@@ -73,7 +73,7 @@ template <class T> __device__ __forceinline__ void store_elem4(typename T::elem*
     }
 }
 
-template <class T, int EPI, int NA, int NC, int NW>
+template <class T, int EPI, int NA, int NC, int NW, int PD>
 __global__ __launch_bounds__(NW * 64) void pf_gemm_kernel(const PfArgs a) {
     using E = typename T::elem;
     constexpr int NP = T::NP;
@@ -114,33 +114,42 @@ __global__ __launch_bounds__(NW * 64) void pf_gemm_kernel(const PfArgs a) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[s][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    u32x4 an[NAT], xg[XW];
-    auto issue = [&](int kb) {
+    // weight and activation fragments are requested PD k-blocks ahead of their use (register ring)
+    u32x4 an[PD][NAT], xg[PD][XW];
+    auto issue = [&](int slot, int kb) {
 #pragma unroll
         for (int i = 0; i < XW; ++i)
-            if (w + NW * i < XF) xg[i] = Xp[i][(size_t)kb * ASD_WAVE];
+            if (w + NW * i < XF) xg[slot][i] = Xp[i][(size_t)kb * ASD_WAVE];
 #pragma unroll
-        for (int s = 0; s < NAT; ++s) an[s] = A[s][(size_t)kb * a.w_kb_stride * ASD_WAVE];
+        for (int s = 0; s < NAT; ++s) an[slot][s] = A[s][(size_t)kb * a.w_kb_stride * ASD_WAVE];
     };
-    if (kb0 < kb1) issue(kb0);
-    for (int kb = kb0; kb < kb1; ++kb) {
-        const int buf = (kb - kb0) & 1;
-        u32x4 ac[NAT];
 #pragma unroll
-        for (int s = 0; s < NAT; ++s) ac[s] = an[s];
+    for (int p = 0; p < PD; ++p)
+        if (kb0 + p < kb1) issue(p, kb0 + p);
+    for (int kbb = kb0; kbb < kb1; kbb += PD) {
 #pragma unroll
-        for (int i = 0; i < XW; ++i)
-            if (w + NW * i < XF) xs[buf][w + NW * i][lane] = xg[i];
-        __syncthreads();
-        if (kb + 1 < kb1) issue(kb + 1);
+        for (int p = 0; p < PD; ++p) {
+            const int kb = kbb + p;
+            if (kb < kb1) {
+                const int buf = (kb - kb0) & 1;
+                u32x4 ac[NAT];
 #pragma unroll
-        for (int c = 0; c < NC; ++c)
+                for (int s = 0; s < NAT; ++s) ac[s] = an[p][s];
 #pragma unroll
-            for (int pl = 0; pl < NP; ++pl) {
-                const u32x4 b = xs[buf][c * NP + pl][lane];
+                for (int i = 0; i < XW; ++i)
+                    if (w + NW * i < XF) xs[buf][w + NW * i][lane] = xg[p][i];
+                __syncthreads();
+                if (kb + PD < kb1) issue(p, kb + PD);
 #pragma unroll
-                for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], ac[s], b);
+                for (int c = 0; c < NC; ++c)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl) {
+                        const u32x4 b = xs[buf][c * NP + pl][lane];
+#pragma unroll
+                        for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], ac[s], b);
+                    }
             }
+        }
     }
 
     // ---- epilogues, straight from the accumulators: lane 16g + m holds features 4g..4g+3 of each tile for row m
