@@ -6,8 +6,8 @@
 // 4 consecutive chunks = 256 keys, again at absolute positions) merge their results through LDS in
 // ascending chunk order; the groups of a head spread over many compute units (one unit alone cannot
 // pull a head's K/V fast enough).  When the context spans several groups, each group's partial goes to
-// global memory and the groups are merged in ascending order: by the group that arrives last (passes
-// of at most ATT_RB rows) or by a row-parallel merge step.  Partials and the arrival counter are
+// global memory and the groups are merged in ascending order by the group that arrives last (its four waves
+// share the rows), or, for the batched chunks of a prompt block, by a row-parallel merge step.  Partials and the arrival counter are
 // exchanged with device-scope relaxed atomic stores / loads (served past the non-coherent per-XCD
 // L2), ordered by waiting for the stores to complete before the counter is bumped; no cache-wide fence.
 // A row at position p sees keys 0..p (causal among the rows of the call as well).
@@ -54,7 +54,7 @@ struct AttnArgs {
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
     unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
-    int32_t fuse_merge;       // the last wave of a head to arrive merges (passes of at most ATT_RB rows)
+    int32_t fuse_merge;       // the last group of a head to arrive merges the groups (else: attn_merge_kernel does)
     void* out;                // tiled activation [n_h*h]
     // prompt processing: blockIdx.z = 16-row chunk of a block of batch_rows rows (0 = a single call); element /
     // float strides from one chunk's buffers to the next.  Needs fuse_merge == 0.
@@ -308,10 +308,10 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         *s_old = valid ? __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xffffffffu;
     }
     __syncthreads();
-    if ((int)*s_old == n_groups - 1 && hw == 0) {
+    if ((int)*s_old == n_groups - 1) {                // the group's waves share the rows, ATT_RB rows per wave and trip
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-        if (lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        attn_merge_rows<T, H, COH>(a, head, 0, pos0, lane);
+        if (hw == 0 && lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int m0 = hw * ATT_RB; m0 < a.M; m0 += ATT_GW * ATT_RB) attn_merge_rows<T, H, COH>(a, head, m0, pos0, lane);
     }
     __syncthreads();
 }

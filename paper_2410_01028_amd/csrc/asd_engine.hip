@@ -442,7 +442,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
             t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
-            t.fuse_merge = M <= ATT_RB;          // few rows: the last chunk wave of a head merges; else a row-parallel step
+            t.fuse_merge = 1;                    // the last group of a head to arrive merges that head's groups
             push(OP_ATTN, ASD_K_ATTN, 0, cls_bytes[ASD_K_ATTN] / L).t = t;
             if (!t.fuse_merge) push(OP_MERGE, ASD_K_ATTN_MERGE, 0, 0).t = t;
 
