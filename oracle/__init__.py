@@ -39,6 +39,19 @@ class _GenStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("cycles", "drafted", "accepted", "emitted")]
 
 
+class _AdaptParams(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_double), ("m", ctypes.c_int32), ("n", ctypes.c_int32), ("use_cs", ctypes.c_int32),
+                ("alpha_mlp", ctypes.c_double), ("use_cs_mlp", ctypes.c_int32), ("refresh", ctypes.c_int32),
+                ("fixed_mask", ctypes.c_void_p), ("draft_len", ctypes.c_int32), ("exit_mode", ctypes.c_int32),
+                ("gamma0", ctypes.c_double), ("ar0", ctypes.c_double), ("ar_target", ctypes.c_double),
+                ("eps", ctypes.c_double), ("beta1", ctypes.c_double), ("beta2", ctypes.c_double)]
+
+
+class _AdaptStats(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int64) for n in ("cycles", "drafted", "accepted", "emitted", "mask_changes")] + \
+               [("gamma", ctypes.c_double), ("ar", ctypes.c_double)]
+
+
 _lib = None
 
 
@@ -63,6 +76,14 @@ def _L():
         L.orc_generate_plain.argtypes = [vp, vp, i32, i32, vp]
         L.orc_generate_spec.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_GenParams), vp,
                                         ctypes.POINTER(_GenStats), vp, vp]
+        L.orc_top1_prob.restype = ctypes.c_double
+        L.orc_top1_prob.argtypes = [vp, i32]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.orc_exit_update.restype = None
+        L.orc_exit_update.argtypes = [dp, dp, i32, i32] + [ctypes.c_double] * 4
+        L.orc_admg2.argtypes = [vp, i32, ctypes.c_double, i32, i32, i32, ctypes.c_double, i32, vp]
+        L.orc_generate_adaptive.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_AdaptParams), vp,
+                                            ctypes.POINTER(_AdaptStats), vp, vp, vp]
         _lib = L
     return _lib
 
@@ -81,6 +102,29 @@ def admg(C_attn, alpha: float, m: int, n: int, use_cs: bool = True) -> np.ndarra
     if rc:
         raise ValueError("orc_admg: invalid argument")
     return mask
+
+
+def admg2(C_all, alpha: float, m: int, n: int, use_cs: bool = True, alpha_mlp: float = 2.0,
+          use_cs_mlp: bool = False) -> np.ndarray:
+    """Algorithm 1 plus CS thresholding of the MLP sublayers; C_all [2L] (attention, MLP interleaved)."""
+    C = np.ascontiguousarray(C_all, dtype=np.float64)
+    mask = np.zeros(C.size, dtype=np.uint8)
+    rc = _L().orc_admg2(C.ctypes.data, C.size // 2, alpha, m, n, int(use_cs), alpha_mlp, int(use_cs_mlp), mask.ctypes.data)
+    if rc:
+        raise ValueError("orc_admg2: invalid argument")
+    return mask
+
+
+def top1_prob(logits) -> float:
+    lg = np.ascontiguousarray(logits, dtype=np.float64)
+    return float(_L().orc_top1_prob(lg.ctypes.data, lg.size))
+
+
+def exit_update(ar: float, gamma: float, a: int, d: int, ar_target: float, eps: float, beta1: float, beta2: float):
+    """One threshold update of the adaptive draft exit; returns (ar, gamma)."""
+    x, y = ctypes.c_double(ar), ctypes.c_double(gamma)
+    _L().orc_exit_update(ctypes.byref(x), ctypes.byref(y), a, d, ar_target, eps, beta1, beta2)
+    return x.value, y.value
 
 
 def acs(cos_rows) -> np.ndarray:
@@ -175,3 +219,27 @@ class Oracle:
             raise ValueError(f"orc_generate_spec failed ({rc})")
         stats = {k: int(getattr(st, k)) for k in ("cycles", "drafted", "accepted", "emitted")}
         return out, stats, mask, C
+
+    def generate_adaptive(self, prompt, n_new: int, draft_len: int, alpha=0.985, m=3, n=2, use_cs=True,
+                          alpha_mlp=2.0, use_cs_mlp=False, refresh=False, fixed_mask=None, exit_mode=0,
+                          gamma0=0.0, ar0=1.0, ar_target=0.9, eps=0.01, beta1=0.5, beta2=0.9):
+        """Speculative loop with a variable draft length and optional mask refresh.
+        Returns (tokens, stats, last mask, running ACS [2L], per-cycle (drafted, accepted) [cycles, 2])."""
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.empty(n_new, dtype=np.int32)
+        fm = None if fixed_mask is None else np.ascontiguousarray(fixed_mask, dtype=np.uint8)
+        gp = _AdaptParams(alpha, m, n, int(use_cs), alpha_mlp, int(use_cs_mlp), int(refresh),
+                          None if fm is None else fm.ctypes.data, draft_len, exit_mode,
+                          gamma0, ar0, ar_target, eps, beta1, beta2)
+        st = _AdaptStats()
+        L2 = 2 * self.shape.n_layers
+        mask = np.zeros(L2, dtype=np.uint8)
+        C = np.zeros(L2, dtype=np.float64)
+        per = np.zeros((n_new, 2), dtype=np.int32)
+        rc = _L().orc_generate_adaptive(self._h, p.ctypes.data, p.size, n_new, ctypes.byref(gp), out.ctypes.data,
+                                        ctypes.byref(st), mask.ctypes.data, C.ctypes.data, per.ctypes.data)
+        if rc:
+            raise ValueError(f"orc_generate_adaptive failed ({rc})")
+        stats = {k: int(getattr(st, k)) for k in ("cycles", "drafted", "accepted", "emitted", "mask_changes")}
+        stats["gamma"], stats["ar"] = float(st.gamma), float(st.ar)
+        return out, stats, mask, C, per[:stats["cycles"]]

@@ -22,7 +22,10 @@
  * Parity status: decoder, cosine, ADMG and the speculative loop are pinned by
  * the CPU tests (independent Llama implementation, closed forms, invariants,
  * brute force).  The paper's own speed-ups and ACS statistics need trained
- * weights and datasets: parity unpinned for those.
+ * weights and datasets: parity unpinned for those.  The extensions at the end
+ * of this file (adaptive draft exit, MLP-side thresholding, mask refresh) are
+ * pinned by invariants and special cases only; the draft-exit rule itself is
+ * not printed in the paper: parity unpinned against the paper for it.
  */
 #include <math.h>
 #include <stdint.h>
@@ -457,5 +460,155 @@ done:
         if (C_prompt) memcpy(C_prompt, C, sizeof(double) * 2 * L);
     }
     free(C); free(Ca); free(mask); free(rows); free(g);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ extensions around the loop
+ *
+ * None of what follows is defined by the paper's text; each item states the reading it implements.
+ * Whatever the parameters, the emitted tokens equal plain greedy decoding of the full model
+ * (the verification pass decides every emitted token), which is what pins these functions.
+ */
+
+/* Largest softmax probability of a logit row: 1 / sum_i exp(l_i - max l). */
+double orc_top1_prob(const double* logits, int32_t V) {
+    double mx = logits[0], s = 0.0;
+    for (int i = 1; i < V; ++i) if (logits[i] > mx) mx = logits[i];
+    for (int i = 0; i < V; ++i) s += exp(logits[i] - mx);
+    return 1.0 / s;
+}
+
+/*
+ * Draft-exit threshold update after a verification that accepted a of d drafts (d >= 1).  Section 4
+ * takes the adaptive draft-exiting mechanism from the Draft & Verify paper and prints neither the
+ * rule nor its constants; this is that mechanism as published there, with every constant a parameter:
+ *   AR     <- beta1 * AR + (1 - beta1) * a / d          (smoothed acceptance rate)
+ *   gamma~  = gamma + eps if AR <= ar_target, else gamma - eps
+ *   gamma  <- beta2 * gamma + (1 - beta2) * gamma~
+ */
+void orc_exit_update(double* ar, double* gamma, int32_t a, int32_t d, double ar_target, double eps,
+                     double beta1, double beta2) {
+    *ar = beta1 * *ar + (1.0 - beta1) * ((double)a / (double)d);
+    const double gt = (*ar <= ar_target) ? *gamma + eps : *gamma - eps;
+    *gamma = beta2 * *gamma + (1.0 - beta2) * gt;
+}
+
+/*
+ * Algorithm 1 with one more rule: CS thresholding applied to the MLP sublayers as well (the paper
+ * thresholds attention sublayers only; Table 1 is its reason).  C2 holds all 2L ACS values
+ * (index 2(l-1) attention, 2(l-1)+1 MLP of layer l).  With use_cs_mlp == 0 the result equals
+ * orc_admg on the attention half.
+ *   remove_MLP  = { l : l = j*m } U { l : C_mlp,l >= alpha_mlp },   l <= L - n
+ *   remove_ATTN = { l : C_attn,l >= alpha, l <= L - n } U { l : l = j*m, l <= L - n }
+ */
+int orc_admg2(const double* C2, int32_t L, double alpha, int32_t m, int32_t n, int32_t use_cs,
+              double alpha_mlp, int32_t use_cs_mlp, uint8_t* mask) {
+    if (!C2 || !mask || L < 1 || m < 0 || n < 0) return -1;
+    memset(mask, 0, (size_t)(2 * L));
+    for (int l = 1; l <= L; ++l) {
+        const int freed = l <= L - n;
+        const int periodic = m > 0 && l % m == 0;
+        const int attn_cs = use_cs && C2[2 * (l - 1)] >= alpha;
+        const int mlp_cs = use_cs_mlp && C2[2 * (l - 1) + 1] >= alpha_mlp;
+        mask[2 * (l - 1)] = (uint8_t)(freed && (attn_cs || periodic));
+        mask[2 * (l - 1) + 1] = (uint8_t)(freed && (periodic || mlp_cs));
+    }
+    return 0;
+}
+
+typedef struct {
+    double alpha;               /* attention CS threshold                                       */
+    int32_t m, n, use_cs;
+    double alpha_mlp;           /* MLP CS threshold (use_cs_mlp != 0)                           */
+    int32_t use_cs_mlp;
+    int32_t refresh;            /* 0: mask from the prompt's ACS, once; 1: rebuilt after every  */
+                                /* verification from the running ACS over the prompt rows and   */
+                                /* all rows committed since (full-model passes only)            */
+    const uint8_t* fixed_mask;  /* non-NULL: used as given (no ADMG, no refresh)                */
+    int32_t draft_len;          /* most drafts per cycle                                        */
+    int32_t exit_mode;          /* 0: always draft_len; 1: stop after a draft whose top-1       */
+                                /* probability under the draft model is below gamma             */
+    double gamma0, ar0, ar_target, eps, beta1, beta2;
+} orc_adapt_params;
+
+typedef struct {
+    int64_t cycles, drafted, accepted, emitted, mask_changes;
+    double gamma, ar;           /* final values */
+} orc_adapt_stats;
+
+/*
+ * The speculative loop of orc_generate_spec with a variable draft length and an optional mask
+ * refresh.  A draft whose confidence falls below gamma is still kept as the cycle's last draft.
+ * C_run [2L] receives the final running ACS (the prompt's ACS when refresh == 0); per_cycle,
+ * when non-NULL, receives (drafted, accepted) pairs, at most N of them.
+ */
+int orc_generate_adaptive(orc_model* M, const int32_t* prompt, int32_t P, int32_t N,
+                          const orc_adapt_params* gp, int32_t* out, orc_adapt_stats* st,
+                          uint8_t* mask_last, double* C_run, int32_t* per_cycle) {
+    if (!M || !prompt || !out || !gp || P < 1 || N < 1 || gp->draft_len < 0) return -1;
+    if (P + N + gp->draft_len > M->c.max_seq) return -1;
+    const int L = M->c.n_layers, L2 = 2 * L, k = gp->draft_len, V = M->c.vocab;
+    double* S = (double*)malloc(sizeof(double) * L2);          /* running sums of row cosines */
+    double* C = (double*)malloc(sizeof(double) * L2);
+    double* cr = (double*)malloc(sizeof(double) * (size_t)(k + 1) * L2);
+    double* lg = (double*)malloc(sizeof(double) * V);
+    uint8_t* mask = (uint8_t*)calloc((size_t)L2, 1);
+    uint8_t* mnew = (uint8_t*)calloc((size_t)L2, 1);
+    int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (k + 1));
+    int32_t* g = (int32_t*)malloc(sizeof(int32_t) * (k + 1));
+    orc_adapt_stats s = {0, 0, 0, 0, 0, gp->gamma0, gp->ar0};
+    int64_t n_rows = P;
+    int32_t last;
+    int rc = prefill(M, prompt, P, &last, C);
+    if (rc) goto done;
+    for (int j = 0; j < L2; ++j) S[j] = C[j] * (double)P;
+    if (gp->fixed_mask) memcpy(mask, gp->fixed_mask, (size_t)L2);
+    else {
+        rc = orc_admg2(C, L, gp->alpha, gp->m, gp->n, gp->use_cs, gp->alpha_mlp, gp->use_cs_mlp, mask);
+        if (rc) goto done;
+    }
+    out[0] = last; s.emitted = 1;
+    int32_t p = P;
+    while (s.emitted < N) {
+        const int kk = k < N - (int)s.emitted - 1 ? k : N - (int)s.emitted - 1;
+        rows[0] = last;
+        int d = 0;
+        while (d < kk) {                          /* draft with D until the limit or a low-confidence draft */
+            rc = orc_forward(M, &rows[d], 1, p + d, mask, 1, lg, NULL, &rows[d + 1], NULL);
+            if (rc) goto done;
+            ++d;
+            if (gp->exit_mode == 1 && orc_top1_prob(lg, V) < s.gamma) break;
+        }
+        orc_truncate(M, p);
+        rc = orc_forward(M, rows, d + 1, p, NULL, 1, NULL, cr, g, NULL);          /* verify with M */
+        if (rc) goto done;
+        int a = 0;
+        while (a < d && rows[a + 1] == g[a]) ++a;
+        for (int j = 1; j <= a; ++j) out[s.emitted++] = rows[j];
+        out[s.emitted++] = g[a];
+        last = g[a];
+        p += a + 1;
+        orc_truncate(M, p);
+        if (per_cycle && s.cycles < N) { per_cycle[2 * s.cycles] = d; per_cycle[2 * s.cycles + 1] = a; }
+        s.cycles++; s.drafted += d; s.accepted += a;
+        if (gp->exit_mode == 1 && d > 0)
+            orc_exit_update(&s.ar, &s.gamma, a, d, gp->ar_target, gp->eps, gp->beta1, gp->beta2);
+        if (gp->refresh && !gp->fixed_mask) {     /* rows 0..a of the verification are now part of the sequence */
+            for (int i = 0; i <= a; ++i)
+                for (int j = 0; j < L2; ++j) S[j] += cr[(size_t)i * L2 + j];
+            n_rows += a + 1;
+            for (int j = 0; j < L2; ++j) C[j] = S[j] / (double)n_rows;
+            rc = orc_admg2(C, L, gp->alpha, gp->m, gp->n, gp->use_cs, gp->alpha_mlp, gp->use_cs_mlp, mnew);
+            if (rc) goto done;
+            if (memcmp(mask, mnew, (size_t)L2)) { memcpy(mask, mnew, (size_t)L2); s.mask_changes++; }
+        }
+    }
+done:
+    if (rc == 0) {
+        if (st) *st = s;
+        if (mask_last) memcpy(mask_last, mask, (size_t)L2);
+        if (C_run) memcpy(C_run, C, sizeof(double) * L2);
+    }
+    free(S); free(C); free(cr); free(lg); free(mask); free(mnew); free(rows); free(g);
     return rc;
 }
