@@ -188,15 +188,22 @@ def main():
         # this random-init model's ACS values lie; and the all-keep bracket (every draft accepted, no layer skipped)
         for name, kw in (("admg_a0.985_m3_n2", dict(alpha=0.985, m=3, n=2)),
                          ("admg_a0.9999_m0_n0", dict(alpha=0.9999, m=0, n=0)),
-                         ("all_keep", dict(fixed_mask=np.zeros(L2, np.uint8)))):
-            decode_step(k, **kw)
+                         ("all_keep", dict(fixed_mask=np.zeros(L2, np.uint8))),
+                         # loop extensions on the cosine-only setting: running-ACS mask refresh; adaptive draft exit with
+                         # at most 6 drafts and a threshold at this model's (tiny, random-init) draft confidences
+                         ("admg_a0.9999_m0_n0_refresh", dict(alpha=0.9999, m=0, n=0, refresh=True)),
+                         ("admg_a0.9999_m0_n0_adaptive_exit_kmax6", dict(alpha=0.9999, m=0, n=0, exit_mode=1, gamma0=0.003, ar0=1.0,
+                                                                        ar_target=0.9, eps=0.0005, beta1=0.5, beta2=0.9, kmax=6))):
+            kw = dict(kw)
+            kk = kw.pop("kmax", k)
+            decode_step(kk, **kw)
             torch.cuda.synchronize()
             t0 = time.time()
-            toks, st, used = decode_step(k, **kw)
+            toks, st, used = decode_step(kk, **kw)
             dt = time.time() - t0
             spec[name] = {"tokens_per_s": round((N - 1) / dt, 2), "speedup_vs_plain": round((N - 1) / dt / value, 3),
                           "cycles": st["cycles"], "drafted": st["drafted"], "accepted": st["accepted"],
-                          "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()),
+                          "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()), "mask_changes": st["mask_changes"],
                           "tokens_equal_plain": bool(np.array_equal(toks, plain))}
         out["speculative"] = spec
 

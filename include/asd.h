@@ -71,8 +71,25 @@ typedef struct {
  * CS thresholding (the rule subsets of the ablation, Table 5).
  * draft_len = k >= 0 drafted tokens per cycle (0 = plain greedy decoding).
  * mask_mode 0: skip mask = ADMG of the prompt's ACS (the paper's method);
- * mask_mode 1: fixed_mask [2L] is used as given.
+ * mask_mode 1: fixed_mask [2L] is used as given;
+ * mask_mode 2: as 0, then the mask is rebuilt after every verification pass from
+ *   the running ACS over the prompt rows and all rows committed since (the
+ *   verification pass is a full-model pass, so its accepted rows extend Eq. 2's
+ *   average); an extension, the paper builds the draft model once per prompt.
  * use_graphs != 0 replays each draft/verify cycle as a captured HIP graph.
+ * use_cs_mlp != 0 also removes MLP sublayers whose ACS reaches alpha_mlp (subject
+ *   to rule 2); an extension, Algorithm 1 thresholds attention sublayers only.
+ * exit_mode 0: every cycle drafts draft_len tokens (fewer only at the end).
+ * exit_mode 1: adaptive draft exit (Section 4 takes it from the Draft & Verify
+ *   paper and prints neither the rule nor its constants, so all constants are
+ *   the caller's): a cycle stops drafting after a token whose softmax probability
+ *   under the draft model is below gamma (that token is still verified), at
+ *   draft_len tokens at the latest; after a verification that accepted a of d
+ *   drafts, AR <- beta1*AR + (1-beta1)*a/d, gamma~ = gamma + eps if AR <= ar_target
+ *   else gamma - eps, gamma <- beta2*gamma + (1-beta2)*gamma~, starting from
+ *   gamma0, ar0.  The host decides, in double, on the fp32 probability the device
+ *   computed; one device-to-host read per draft step.
+ * Whatever these say, the emitted tokens equal plain greedy decoding.
  */
 typedef struct {
     float alpha;
@@ -81,12 +98,19 @@ typedef struct {
     int32_t mask_mode;
     const uint8_t* fixed_mask;
     int32_t use_graphs;
+    float alpha_mlp;
+    int32_t use_cs_mlp;
+    int32_t exit_mode;
+    double gamma0, ar0, ar_target, eps, beta1, beta2;
 } asd_gen_params;
 
-/* Counters of one asd_decode / asd_generate call (emitted includes the first token for asd_generate). */
+/* Counters of one asd_decode / asd_generate call (emitted includes the first token for asd_generate);
+ * gamma, ar: final values of the adaptive draft exit; mask_changes: rebuilds that changed the mask. */
 typedef struct {
     int64_t cycles, drafted, accepted, emitted;
     double ms_prefill, ms_decode;
+    int64_t mask_changes;
+    double gamma, ar;
 } asd_gen_stats;
 
 /* Per-kernel-class GPU time of one profiled forward pass, from HIP events on the engine's stream. */
@@ -179,6 +203,15 @@ int asd_prefill_chunked(asd_engine* e, const int32_t* tokens, int32_t n, int32_t
  * when c_attn[l] >= alpha (compared in fp32).
  */
 int asd_admg(const float* c_attn, int32_t n_layers, float alpha, int32_t m, int32_t n, int32_t use_cs, uint8_t* skip_mask);
+
+/*
+ * Algorithm 1 plus CS thresholding of the MLP sublayers (an extension): c_all [2L] holds
+ * every sublayer's ACS (attention at even, MLP at odd indices); MLP l is also removed when
+ * use_cs_mlp != 0, c_all[2l+1] >= alpha_mlp and rule 2 does not protect it.  With
+ * use_cs_mlp == 0 the result equals asd_admg on the attention half.  Host function.
+ */
+int asd_admg2(const float* c_all, int32_t n_layers, float alpha, int32_t m, int32_t n, int32_t use_cs, float alpha_mlp,
+              int32_t use_cs_mlp, uint8_t* skip_mask);
 
 /*
  * Greedy speculative decoding from the current cache state (Section 1): last_token

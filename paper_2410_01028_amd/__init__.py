@@ -36,12 +36,15 @@ class Config(ctypes.Structure):
 class GenParams(ctypes.Structure):
     _fields_ = [("alpha", ctypes.c_float), ("m", ctypes.c_int32), ("n", ctypes.c_int32), ("use_cs", ctypes.c_int32),
                 ("draft_len", ctypes.c_int32), ("mask_mode", ctypes.c_int32), ("fixed_mask", ctypes.c_void_p),
-                ("use_graphs", ctypes.c_int32)]
+                ("use_graphs", ctypes.c_int32), ("alpha_mlp", ctypes.c_float), ("use_cs_mlp", ctypes.c_int32),
+                ("exit_mode", ctypes.c_int32)] + \
+               [(n, ctypes.c_double) for n in ("gamma0", "ar0", "ar_target", "eps", "beta1", "beta2")]
 
 
 class GenStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("cycles", "drafted", "accepted", "emitted")] + \
-               [("ms_prefill", ctypes.c_double), ("ms_decode", ctypes.c_double)]
+               [("ms_prefill", ctypes.c_double), ("ms_decode", ctypes.c_double), ("mask_changes", ctypes.c_int64),
+                ("gamma", ctypes.c_double), ("ar", ctypes.c_double)]
 
 
 class KernelTimes(ctypes.Structure):
@@ -79,6 +82,7 @@ def lib():
         L.asd_forward.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
         L.asd_prefill.argtypes = [vp, vp, i32, vp, vp, vp]
         L.asd_prefill_chunked.argtypes = [vp, vp, i32, vp, vp, vp]
+        L.asd_admg2.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, ctypes.c_float, i32, vp]
         L.asd_admg.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, vp]
         L.asd_decode.argtypes = [vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
         L.asd_generate.argtypes = [vp, vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
@@ -107,6 +111,16 @@ def admg(c_attn, alpha: float, m: int, n: int, use_cs: bool = True) -> np.ndarra
     rc = lib().asd_admg(c.ctypes.data, c.size, alpha, m, n, int(use_cs), mask.ctypes.data)
     if rc:
         raise AsdError(rc, "asd_admg: invalid argument")
+    return mask
+
+
+def admg2(c_all, alpha: float, m: int, n: int, use_cs: bool = True, alpha_mlp: float = 0.0, use_cs_mlp: bool = False) -> np.ndarray:
+    """Algorithm 1 plus CS thresholding of the MLP sublayers, from all 2L ACS values (attention, MLP interleaved)."""
+    c = np.ascontiguousarray(c_all, dtype=np.float32)
+    mask = np.zeros(c.size, dtype=np.uint8)
+    rc = lib().asd_admg2(c.ctypes.data, c.size // 2, alpha, m, n, int(use_cs), alpha_mlp, int(use_cs_mlp), mask.ctypes.data)
+    if rc:
+        raise AsdError(rc, "asd_admg2: invalid argument")
     return mask
 
 
@@ -214,14 +228,19 @@ class Engine:
         return int(first.value), cos, lg
 
     @staticmethod
-    def _params(draft_len, alpha, m, n, use_cs, fixed_mask, use_graphs):
+    def _params(draft_len, alpha=0.985, m=3, n=2, use_cs=True, fixed_mask=None, use_graphs=True, refresh=False,
+                alpha_mlp=0.0, use_cs_mlp=False, exit_mode=0, gamma0=0.0, ar0=1.0, ar_target=0.9, eps=0.01, beta1=0.5,
+                beta2=0.9):
         fm = None if fixed_mask is None else np.ascontiguousarray(fixed_mask, dtype=np.uint8)
-        gp = GenParams(alpha, m, n, int(use_cs), draft_len, 0 if fm is None else 1, _ptr(fm), int(use_graphs))
+        mode = 1 if fm is not None else (2 if refresh else 0)
+        gp = GenParams(alpha, m, n, int(use_cs), draft_len, mode, _ptr(fm), int(use_graphs), alpha_mlp, int(use_cs_mlp),
+                       exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2)
         return gp, fm
 
-    def decode(self, last_token: int, n_more: int, draft_len: int, alpha=0.985, m=3, n=2, use_cs=True,
-               fixed_mask=None, use_graphs=True):
-        gp, fm = self._params(draft_len, alpha, m, n, use_cs, fixed_mask, use_graphs)
+    def decode(self, last_token: int, n_more: int, draft_len: int, **kw):
+        """Speculative decode from the current cache; kw: alpha, m, n, use_cs, fixed_mask, use_graphs, refresh
+        (mask rebuilt from the running ACS), alpha_mlp / use_cs_mlp, exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2."""
+        gp, fm = self._params(draft_len, **kw)
         out = np.empty(n_more, dtype=np.int32)
         st = GenStats()
         mask = np.zeros(self.L2, dtype=np.uint8)
@@ -229,10 +248,9 @@ class Engine:
                                   mask.ctypes.data))
         return out, self._stats(st), mask
 
-    def generate(self, prompt, n_new: int, draft_len: int, alpha=0.985, m=3, n=2, use_cs=True, fixed_mask=None,
-                 use_graphs=True):
+    def generate(self, prompt, n_new: int, draft_len: int, **kw):
         p = np.ascontiguousarray(prompt, dtype=np.int32)
-        gp, fm = self._params(draft_len, alpha, m, n, use_cs, fixed_mask, use_graphs)
+        gp, fm = self._params(draft_len, **kw)
         out = np.empty(n_new, dtype=np.int32)
         st = GenStats()
         mask = np.zeros(self.L2, dtype=np.uint8)
@@ -242,7 +260,8 @@ class Engine:
 
     @staticmethod
     def _stats(st: GenStats) -> dict:
-        return {k: getattr(st, k) for k in ("cycles", "drafted", "accepted", "emitted", "ms_prefill", "ms_decode")}
+        return {k: getattr(st, k) for k in ("cycles", "drafted", "accepted", "emitted", "ms_prefill", "ms_decode",
+                                            "mask_changes", "gamma", "ar")}
 
     # ---- measurement
     def time_pass(self, n_rows: int, skip=None, reps: int = 20, use_graph: bool = True):

@@ -103,5 +103,6 @@ struct DevState {
     int32_t emitted;    // tokens written to the output buffer so far
     int32_t target;     // tokens to emit in this decode call
     int32_t cycles, drafted, accepted;
-    int32_t pad[2];
+    float conf;         // top-1 probability of the token the last draft step produced (softmax of its logits)
+    int32_t pad;
 };

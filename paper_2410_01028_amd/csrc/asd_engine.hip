@@ -15,6 +15,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
 #include <map>
 #include <string>
 #include <vector>
@@ -77,6 +78,8 @@ struct asd_engine {
     // host state
     int kv_len;
     std::vector<float> acs;
+    std::vector<double> acs_sum;         // per sublayer: sum of the prompt rows' cosines
+    int acs_rows;
     bool acs_valid;
     DevState* h_st;                     // pinned
     std::map<std::vector<int>, hipGraphExec_t> graphs;
@@ -799,7 +802,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
-    e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_valid = false; e->h_st = nullptr;
+    e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
     // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
     e->persistent = false; e->pass_grid = 0;
     {
@@ -991,17 +994,27 @@ int asd_truncate(asd_engine* e, int32_t n) {
 }
 int32_t asd_kv_len(const asd_engine* e) { return e ? e->kv_len : ASD_E_INVAL; }
 
-int asd_admg(const float* C, int32_t L, float alpha, int32_t m, int32_t n, int32_t use_cs, uint8_t* mask) {
-    if (!C || !mask || L < 1 || m < 0 || n < 0) return ASD_E_INVAL;
+int asd_admg2(const float* C2, int32_t L, float alpha, int32_t m, int32_t n, int32_t use_cs, float alpha_mlp, int32_t use_cs_mlp,
+              uint8_t* mask) {
+    if (!C2 || !mask || L < 1 || m < 0 || n < 0) return ASD_E_INVAL;
     if (use_cs && !(alpha > 0.f && alpha < 1.f)) return ASD_E_INVAL;
+    if (use_cs_mlp && !(alpha_mlp > 0.f && alpha_mlp < 1.f)) return ASD_E_INVAL;
     for (int i = 0; i < L; ++i) {
         const bool free_to_go = i < L - n;                       // rule 2 keeps the last n layers
         const bool periodic = m > 0 && (i + 1) % m == 0;         // rule 1, layers counted from 1
-        const bool similar = use_cs && C[i] >= alpha;            // CS thresholding
-        mask[2 * i + 1] = free_to_go && periodic;
+        const bool similar = use_cs && C2[2 * i] >= alpha;       // CS thresholding
+        const bool similar_mlp = use_cs_mlp && C2[2 * i + 1] >= alpha_mlp;
+        mask[2 * i + 1] = free_to_go && (periodic || similar_mlp);
         mask[2 * i] = free_to_go && (similar || periodic);
     }
     return ASD_OK;
+}
+
+int asd_admg(const float* C, int32_t L, float alpha, int32_t m, int32_t n, int32_t use_cs, uint8_t* mask) {
+    if (!C || L < 1) return ASD_E_INVAL;
+    std::vector<float> c2(2 * (size_t)L, 0.f);
+    for (int i = 0; i < L; ++i) c2[2 * i] = C[i];
+    return asd_admg2(c2.data(), L, alpha, m, n, use_cs, 0.f, 0, mask);
 }
 
 // run rows [tokens, tokens+n) at the current cache end; results stay on the device
@@ -1086,7 +1099,8 @@ static int prefill_impl(asd_engine* e, const int32_t* tokens, int32_t n, int32_t
     CK(e, hipStreamSynchronize(e->stream));
     rc = check_pass_error(e);
     if (rc) return rc;
-    for (int j = 0; j < L2; ++j) e->acs[j] = (float)(acc[j] / n);
+    for (int j = 0; j < L2; ++j) { e->acs[j] = (float)(acc[j] / n); e->acs_sum[j] = acc[j]; }
+    e->acs_rows = n;
     e->acs_valid = true;
     if (cos_out) memcpy(cos_out, e->acs.data(), (size_t)L2 * 4);
     if (last_logits) memcpy(last_logits, lg.data(), lg.size() * 4);
@@ -1111,66 +1125,119 @@ static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int
     return enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, kk);
 }
 
+// Run `enqueue` on the engine's stream: eagerly, or (use_graphs) as a HIP graph captured once per key.
+static int run_captured(asd_engine* e, bool use_graphs, const std::vector<int>& key, const std::function<int()>& enqueue) {
+    if (!use_graphs || e->persistent) return enqueue();
+    auto it = e->graphs.find(key);
+    if (it == e->graphs.end()) {
+        hipGraph_t g = nullptr;
+        hipGraphExec_t ge = nullptr;
+        CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
+        const int rc = enqueue();
+        hipError_t r2 = hipStreamEndCapture(e->stream, &g);
+        if (rc) { if (g) hipGraphDestroy(g); return rc; }
+        if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(r2));
+        r2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+        hipGraphDestroy(g);
+        if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(r2));
+        it = e->graphs.emplace(key, ge).first;
+    }
+    CK(e, hipGraphLaunch(it->second, e->stream));
+    return ASD_OK;
+}
+
+static int check_gen_params(asd_engine* e, const asd_gen_params* p) {
+    if (p->mask_mode < 0 || p->mask_mode > 2) return fail(e, ASD_E_INVAL, "mask_mode must be 0, 1 or 2");
+    if (p->mask_mode == 1 && !p->fixed_mask) return fail(e, ASD_E_INVAL, "mask_mode 1 needs fixed_mask");
+    if (p->exit_mode != 0 && p->exit_mode != 1) return fail(e, ASD_E_INVAL, "exit_mode must be 0 or 1");
+    if (p->exit_mode == 1) {
+        const bool ok = p->beta1 >= 0.0 && p->beta1 <= 1.0 && p->beta2 >= 0.0 && p->beta2 <= 1.0 && p->eps >= 0.0 && std::isfinite(p->eps) &&
+                        std::isfinite(p->gamma0) && std::isfinite(p->ar0) && std::isfinite(p->ar_target);
+        if (!ok) return fail(e, ASD_E_INVAL, "adaptive draft exit: beta1, beta2 in [0, 1], eps >= 0, finite gamma0 / ar0 / ar_target");
+    }
+    return ASD_OK;
+}
+
 int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_params* p, int32_t* out, asd_gen_stats* stats,
                uint8_t* mask_used) {
     if (!e) return ASD_E_INVAL;
     if (!p || !out) return fail(e, ASD_E_INVAL, "params or out_tokens is NULL");
     if (n_more < 1) return fail(e, ASD_E_INVAL, "n_more must be >= 1");
-    const int k = p->draft_len, L = e->c.n_layers;
+    const int k = p->draft_len, L = e->c.n_layers, L2 = 2 * L;
     if (k < 0 || k + 1 > e->c.max_rows) return fail(e, ASD_E_INVAL, "draft_len %d outside [0, %d]", k, e->c.max_rows - 1);
     if (last_token < 0 || last_token >= e->c.vocab) return fail(e, ASD_E_INVAL, "last_token outside the vocabulary");
     if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
     if (e->kv_len + n_more + k > capacity(e))
         return fail(e, ASD_E_INVAL, "cache capacity %d too small for %d + %d + %d positions", capacity(e), e->kv_len, n_more, k);
-    std::vector<uint8_t> mask(2 * (size_t)L, 0);
+    int rc = check_gen_params(e, p);
+    if (rc) return rc;
+    std::vector<uint8_t> mask(L2, 0), mnew(L2, 0);
+    const bool refresh = p->mask_mode == 2;
+    std::vector<double> S;              // running sums of row cosines (mask refresh)
+    std::vector<float> C(L2), cr;
+    long n_rows = 0;
     if (p->mask_mode == 1) {
-        if (!p->fixed_mask) return fail(e, ASD_E_INVAL, "mask_mode 1 needs fixed_mask");
-        for (int j = 0; j < 2 * L; ++j) mask[j] = p->fixed_mask[j] ? 1 : 0;
-    } else if (p->mask_mode == 0) {
-        if (!e->acs_valid) return fail(e, ASD_E_STATE, "mask_mode 0 needs the ACS of a preceding asd_prefill");
-        std::vector<float> ca(L);
-        for (int l = 0; l < L; ++l) ca[l] = e->acs[2 * l];
-        if (asd_admg(ca.data(), L, p->alpha, p->m, p->n, p->use_cs, mask.data()))
-            return fail(e, ASD_E_INVAL, "invalid ADMG parameters (alpha in (0,1), m >= 0, n >= 0)");
+        for (int j = 0; j < L2; ++j) mask[j] = p->fixed_mask[j] ? 1 : 0;
     } else {
-        return fail(e, ASD_E_INVAL, "mask_mode must be 0 or 1");
+        if (!e->acs_valid) return fail(e, ASD_E_STATE, "mask_mode 0 / 2 needs the ACS of a preceding asd_prefill");
+        if (asd_admg2(e->acs.data(), L, p->alpha, p->m, p->n, p->use_cs, p->alpha_mlp, p->use_cs_mlp, mask.data()))
+            return fail(e, ASD_E_INVAL, "invalid ADMG parameters (thresholds in (0,1), m >= 0, n >= 0)");
+        if (refresh) { S = e->acs_sum; n_rows = e->acs_rows; cr.resize((size_t)L2 * ASD_ROWS); }
     }
     if (mask != e->graph_mask) { drop_graphs(e); e->graph_mask = mask; }
 
     const auto t0 = std::chrono::steady_clock::now();
     set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, n_more, 1);
     set_token_kernel<<<1, 1, 0, e->stream>>>(e->tokbuf, last_token);
-    int emitted = 0;
+    const bool graphs = p->use_graphs != 0;
+    double gamma = p->gamma0, ar = p->ar0;
+    long mask_changes = 0;
+    int emitted = 0, accepted = 0;
     while (emitted < n_more) {
         const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
-        const int nc = chunks_for(e->kv_len + kk);
-        int rc = ASD_OK;
-        if (p->use_graphs && !e->persistent) {
-            const std::vector<int> key{kk, nc};
-            auto it = e->graphs.find(key);
-            if (it == e->graphs.end()) {
-                hipGraph_t g = nullptr;
-                hipGraphExec_t ge = nullptr;
-                CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
-                rc = enqueue_cycle(e, kk, mask.data(), nc, e->kv_len + kk + 1);
-                hipError_t r2 = hipStreamEndCapture(e->stream, &g);
-                if (rc) { if (g) hipGraphDestroy(g); return rc; }
-                if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipStreamEndCapture: %s", hipGetErrorString(r2));
-                r2 = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
-                hipGraphDestroy(g);
-                if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "hipGraphInstantiate: %s", hipGetErrorString(r2));
-                it = e->graphs.emplace(key, ge).first;
-            }
-            CK(e, hipGraphLaunch(it->second, e->stream));
+        const int nc = chunks_for(e->kv_len + kk), ctx = e->kv_len + kk + 1;
+        int d = kk;
+        if (p->exit_mode == 0) {
+            rc = run_captured(e, graphs, {0, kk, nc}, [&] { return enqueue_cycle(e, kk, mask.data(), nc, ctx); });
+            if (rc) return rc;
         } else {
-            rc = enqueue_cycle(e, kk, mask.data(), nc, e->kv_len + kk + 1);
+            // draft until the limit or a low-confidence draft; the host reads the confidence after every step
+            d = 0;
+            while (d < kk) {
+                rc = run_captured(e, graphs, {1, d, nc},
+                                  [&] { return enqueue_forward(e, e->tokbuf + d, 1, d, mask.data(), nc, nullptr, ctx, FIN_DRAFT, d); });
+                if (rc) return rc;
+                ++d;
+                CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
+                CK(e, hipStreamSynchronize(e->stream));
+                if ((double)e->h_st->conf < gamma) break;
+            }
+            rc = run_captured(e, graphs, {2, d, nc},
+                              [&] { return enqueue_forward(e, e->tokbuf, d + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, d); });
             if (rc) return rc;
         }
         CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
+        if (refresh) CK(e, hipMemcpyAsync(cr.data(), e->cos_rows, cr.size() * 4, hipMemcpyDeviceToHost, e->stream));
         CK(e, hipStreamSynchronize(e->stream));
         if (e->h_st->emitted <= emitted) return fail(e, ASD_E_STATE, "decode cycle made no progress");
+        const int a = e->h_st->accepted - accepted;
+        accepted = e->h_st->accepted;
         emitted = e->h_st->emitted;
         e->kv_len = e->h_st->pos;
+        if (p->exit_mode == 1 && d > 0) {
+            ar = p->beta1 * ar + (1.0 - p->beta1) * ((double)a / (double)d);
+            const double gt = ar <= p->ar_target ? gamma + p->eps : gamma - p->eps;
+            gamma = p->beta2 * gamma + (1.0 - p->beta2) * gt;
+        }
+        if (refresh) {
+            // rows 0..a of the verification pass (a full-model pass) joined the sequence: extend the average
+            for (int j = 0; j < L2; ++j)
+                for (int i = 0; i <= a; ++i) S[j] += (double)cr[(size_t)j * ASD_ROWS + i];
+            n_rows += a + 1;
+            for (int j = 0; j < L2; ++j) C[j] = (float)(S[j] / (double)n_rows);
+            asd_admg2(C.data(), L, p->alpha, p->m, p->n, p->use_cs, p->alpha_mlp, p->use_cs_mlp, mnew.data());
+            if (mnew != mask) { mask = mnew; ++mask_changes; drop_graphs(e); e->graph_mask = mask; }
+        }
     }
     CK(e, hipMemcpyAsync(out, e->out_tokens, (size_t)n_more * 4, hipMemcpyDeviceToHost, e->stream));
     CK(e, hipStreamSynchronize(e->stream));
@@ -1180,6 +1247,7 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
         stats->cycles = e->h_st->cycles; stats->drafted = e->h_st->drafted; stats->accepted = e->h_st->accepted;
         stats->emitted = emitted; stats->ms_prefill = 0.0;
         stats->ms_decode = std::chrono::duration<double, std::milli>(t1 - t0).count();
+        stats->mask_changes = mask_changes; stats->gamma = gamma; stats->ar = ar;
     }
     if (mask_used) memcpy(mask_used, mask.data(), mask.size());
     return ASD_OK;
@@ -1191,7 +1259,7 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
     if (!p || !out) return fail(e, ASD_E_INVAL, "params or out_tokens is NULL");
     if (n_new < 1) return fail(e, ASD_E_INVAL, "n_new must be >= 1");
     if (p->draft_len + 1 > e->c.max_rows) return fail(e, ASD_E_INVAL, "draft_len %d outside [0, %d]", p->draft_len, e->c.max_rows - 1);
-    if (p->mask_mode == 1 && !p->fixed_mask) return fail(e, ASD_E_INVAL, "mask_mode 1 needs fixed_mask");
+    { const int rcp = check_gen_params(e, p); if (rcp) return rcp; }
     if (p->draft_len < 0 || n_prompt < 1 || n_prompt + n_new + p->draft_len > capacity(e))
         return fail(e, ASD_E_INVAL, "prompt %d + new %d + draft %d exceeds the cache capacity %d", n_prompt, n_new, p->draft_len, capacity(e));
     const auto t0 = std::chrono::steady_clock::now();

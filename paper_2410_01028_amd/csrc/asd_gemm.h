@@ -14,7 +14,7 @@
 //   EPI_RES  y = x + out (residual add), tiled copy of y*gain for the next norm, and the
 //            cosine tap: per-workgroup partials of <x,y> and ||y||^2
 //   EPI_GU   RMSNorm scale, silu(gate) * up -> tiled activation
-//   EPI_LM   RMSNorm scale, logits, per-workgroup argmax candidates
+//   EPI_LM   RMSNorm scale, logits, per-workgroup argmax candidates and softmax partial sums
 // The three epilogues that need the RMSNorm scale are always the next launch after an
 // EPI_RES kernel (or after the embedding): every workgroup sums that kernel's partials in
 // the same fixed order to get ||y||^2, and workgroup 0 also finishes the producing
@@ -25,7 +25,7 @@
 
 enum { EPI_QKV = 0, EPI_RES = 1, EPI_GU = 2, EPI_LM = 3 };
 
-struct AmaxPart { float v; int32_t i; };
+struct AmaxPart { float v; int32_t i; float s; float pad; };   // best logit, its index, sum of exp(logit - v) over the workgroup's features
 
 struct GemmArgs {
     const u32x4* W;          // tiled weights
@@ -65,7 +65,7 @@ struct GemmArgs {
     // EPI_LM
     float* logits;           // [16][V]
     int32_t V;
-    AmaxPart* amax_part;     // [grid][16] best (logit, index) among this workgroup's features
+    AmaxPart* amax_part;     // [grid][16] best (logit, index) among this workgroup's features, and their exp-sum
 };
 
 // Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments.
@@ -322,8 +322,13 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
                     const float v = epi_a[s * 256 + tid * 16 + nl];
                     if (v > best.v) { best.v = v; best.i = tile[s] * 16 + nl; }
                 }
+            float se = 0.f;
+            if (best.v != -INFINITY)
+                for (int s = 0; s < NA; ++s)
+                    for (int nl = 0; nl < 16; ++nl) se += __expf(epi_a[s * 256 + tid * 16 + nl] - best.v);
             st_f32<COH>(&a.amax_part[(size_t)bid * 16 + tid].v, best.v);
             st_f32<COH>((float*)&a.amax_part[(size_t)bid * 16 + tid].i, __int_as_float(best.i));
+            st_f32<COH>(&a.amax_part[(size_t)bid * 16 + tid].s, se);
         }
     }
 }

@@ -47,13 +47,14 @@ __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok
 // After the LM head: pick each row's greedy token from the per-workgroup candidates (largest
 // logit, lowest index on ties), then, by mode,
 //   FIN_NONE    nothing more;
-//   FIN_DRAFT   draft step j: the drafted token becomes row j+1 of the coming verification pass;
+//   FIN_DRAFT   draft step j: the drafted token becomes row j+1 of the coming verification pass, and its
+//               softmax probability goes to the decoding state (what an adaptive draft exit looks at);
 //   FIN_ACCEPT  accept / rollback after a verification pass over rows [last, d_1..d_kk], g_i = the
 //               full model's choice after row i: a = length of the longest prefix with
 //               d_{i+1} == g_i; emit d_1..d_a, g_a; the cache keeps pos + a + 1 positions; g_a is
 //               the next cycle's first row.
 enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
-struct AmaxCand { float v; int32_t i; };
+struct AmaxCand { float v; int32_t i; float s; float pad; };
 __device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 // one workgroup; wave w handles rows w, w + (waves), ...; candidates are [workgroup][16 rows]
 template <bool COH>
@@ -73,6 +74,14 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
             if (amax_better(ov, oi, v, idx)) { v = ov; idx = oi; }
         }
         if (lane == 0) { win[m] = idx; argmax[m] = idx; }
+        if (mode == FIN_DRAFT && m == 0) {
+            // confidence of the drafted token: 1 / sum_i exp(logit_i - max), from the per-workgroup sums
+            float se = 0.f;
+            for (int p = lane; p < P; p += 64)
+                se += ld_f32<COH>(&cand[(size_t)p * 16].s) * __expf(ld_f32<COH>(&cand[(size_t)p * 16].v) - v);
+            for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
+            if (lane == 0) st->conf = 1.f / se;
+        }
     }
     __syncthreads();
     if (tid != 0) return;

@@ -81,3 +81,18 @@ def test_null_engine_is_refused():
     assert L.asd_truncate(None, 0) == asd.E_INVAL
     assert L.asd_forward(None, None, 1, 0, None, 1, None, None, None, None) == asd.E_INVAL
     assert L.asd_generate(None, None, 1, 1, None, None, None, None) == asd.E_INVAL
+
+
+def test_admg2_matches_oracle_and_reduces_to_admg():
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        L = int(rng.integers(1, 40))
+        C = rng.uniform(0.9, 1.0, 2 * L).astype(np.float32)
+        alpha, amlp = float(np.float32(rng.uniform(0.9, 0.999))), float(np.float32(rng.uniform(0.9, 0.999)))
+        m, n = int(rng.integers(0, 6)), int(rng.integers(0, 5))
+        cs, csm = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        want = oracle.admg2(C.astype(np.float64), alpha, m, n, cs, amlp, csm)
+        assert np.array_equal(asd.admg2(C, alpha, m, n, cs, amlp, csm), want)
+        assert np.array_equal(asd.admg2(C, alpha, m, n, cs), asd.admg(C[0::2], alpha, m, n, cs))
+    with pytest.raises(asd.AsdError):
+        asd.admg2(np.zeros(8, np.float32), 0.9, 1, 1, True, 1.5, True)
