@@ -167,6 +167,14 @@ def prompt(seed: int, n: int, vocab: int) -> np.ndarray:
     return out
 
 
+T_SAMPLING = 102      # stream id of the uniforms drawn by sampled decoding
+
+
+def sampling_uniform(seed: int, index: int, purpose: int) -> float:
+    """Uniform in [0, 1) of the sampling stream for output index `index` (purpose 0 draft, 1 accept test, 2 token draw)."""
+    return float(lib().synth_uniform(seed, T_SAMPLING, 0, 3 * index + purpose))
+
+
 def bf16_to_f32(a: np.ndarray) -> np.ndarray:
     """Widen bf16 bit patterns (uint16) to fp32 values (exact)."""
     return (a.astype(np.uint32) << 16).view(np.float32)

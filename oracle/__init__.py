@@ -84,6 +84,13 @@ def _L():
         L.orc_admg2.argtypes = [vp, i32, ctypes.c_double, i32, i32, i32, ctypes.c_double, i32, vp]
         L.orc_generate_adaptive.argtypes = [vp, vp, i32, i32, ctypes.POINTER(_AdaptParams), vp,
                                             ctypes.POINTER(_AdaptStats), vp, vp, vp]
+        u64, f64 = ctypes.c_uint64, ctypes.c_double
+        L.orc_uniform.restype = f64
+        L.orc_uniform.argtypes = [u64, ctypes.c_int64, i32]
+        L.orc_sample_weights.argtypes = [vp, i32, f64, dp]
+        L.orc_sample_logits.argtypes = [vp, i32, f64, f64, dp]
+        L.orc_spec_accept.argtypes = [vp, vp, vp, i32, i32, f64, vp, vp, ctypes.POINTER(i32), dp]
+        L.orc_generate_sampled.argtypes = [vp, vp, i32, i32, i32, vp, f64, u64, vp, ctypes.POINTER(_GenStats), dp]
         _lib = L
     return _lib
 
@@ -125,6 +132,40 @@ def exit_update(ar: float, gamma: float, a: int, d: int, ar_target: float, eps: 
     x, y = ctypes.c_double(ar), ctypes.c_double(gamma)
     _L().orc_exit_update(ctypes.byref(x), ctypes.byref(y), a, d, ar_target, eps, beta1, beta2)
     return x.value, y.value
+
+
+def uniform(seed: int, index: int, purpose: int) -> float:
+    """The sampling stream's uniform for output index `index`: purpose 0 draft, 1 accept test, 2 replacement / extra / plain."""
+    return float(_L().orc_uniform(seed, index, purpose))
+
+
+def sample_weights(w, u: float):
+    """Inverse-CDF draw from non-negative weights; returns (index, relative margin to the nearer bin boundary)."""
+    w = np.ascontiguousarray(w, dtype=np.float64)
+    mg = ctypes.c_double()
+    return int(_L().orc_sample_weights(w.ctypes.data, w.size, u, ctypes.byref(mg))), mg.value
+
+
+def sample_logits(logits, T: float, u: float):
+    lg = np.ascontiguousarray(logits, dtype=np.float64)
+    mg = ctypes.c_double()
+    return int(_L().orc_sample_logits(lg.ctypes.data, lg.size, T, u, ctypes.byref(mg))), mg.value
+
+
+def spec_accept(q_logits, p_logits, x, T: float, u_acc, u_res):
+    """Speculative-sampling verification of drafts x [kk]; returns (accepted count, next token, smallest margin)."""
+    q = np.ascontiguousarray(q_logits, dtype=np.float64)
+    p = np.ascontiguousarray(p_logits, dtype=np.float64)
+    xs = np.ascontiguousarray(x, dtype=np.int32)
+    kk, V = xs.size, p.shape[-1]
+    assert p.shape == (kk + 1, V) and (kk == 0 or q.shape == (kk, V))
+    ua = np.ascontiguousarray(u_acc, dtype=np.float64)
+    ur = np.ascontiguousarray(u_res, dtype=np.float64)
+    assert ua.size >= kk and ur.size >= kk + 1
+    nxt, mg = ctypes.c_int32(), ctypes.c_double()
+    a = _L().orc_spec_accept(q.ctypes.data, p.ctypes.data, xs.ctypes.data, kk, V, T, ua.ctypes.data, ur.ctypes.data,
+                             ctypes.byref(nxt), ctypes.byref(mg))
+    return int(a), int(nxt.value), mg.value
 
 
 def acs(cos_rows) -> np.ndarray:
@@ -243,3 +284,16 @@ class Oracle:
         stats = {k: int(getattr(st, k)) for k in ("cycles", "drafted", "accepted", "emitted", "mask_changes")}
         stats["gamma"], stats["ar"] = float(st.gamma), float(st.ar)
         return out, stats, mask, C, per[:stats["cycles"]]
+
+    def generate_sampled(self, prompt, n_new: int, draft_len: int, T: float, seed: int, mask=None):
+        """Sampled (temperature T) self-speculative decoding; returns (tokens, stats, smallest decision margin)."""
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        out = np.empty(n_new, dtype=np.int32)
+        mk = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+        st = _GenStats()
+        mg = ctypes.c_double()
+        rc = _L().orc_generate_sampled(self._h, p.ctypes.data, p.size, n_new, draft_len, None if mk is None else mk.ctypes.data,
+                                       T, seed, out.ctypes.data, ctypes.byref(st), ctypes.byref(mg))
+        if rc:
+            raise ValueError(f"orc_generate_sampled failed ({rc})")
+        return out, {k: int(getattr(st, k)) for k in ("cycles", "drafted", "accepted", "emitted")}, mg.value

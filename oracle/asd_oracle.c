@@ -10,7 +10,7 @@
  *   - the Adaptive Draft Model Generator (Algorithm 1),
  *   - plain greedy decoding and greedy speculative decoding with a
  *     layer-skipping draft model (Section 1, the draft / verify / replace-the-
- *     first-rejected-token protocol).
+ *     first-rejected-token protocol), and its sampled form at temperature > 0.
  *
  * It shares no code with the HIP engine and must never be used by it: only the
  * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
@@ -25,7 +25,10 @@
  * weights and datasets: parity unpinned for those.  The extensions at the end
  * of this file (adaptive draft exit, MLP-side thresholding, mask refresh) are
  * pinned by invariants and special cases only; the draft-exit rule itself is
- * not printed in the paper: parity unpinned against the paper for it.
+ * not printed in the paper: parity unpinned against the paper for it.  Sampled
+ * decoding (speculative sampling, cited but not printed) is pinned by the
+ * property that defines it: exhaustive enumeration of the uniforms shows that
+ * the emitted tokens follow the full model's distribution.
  */
 #include <math.h>
 #include <stdint.h>
@@ -610,5 +613,168 @@ done:
         if (C_run) memcpy(C_run, C, sizeof(double) * L2);
     }
     free(S); free(C); free(cr); free(lg); free(mask); free(mnew); free(rows); free(g);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ sampling verification (temperature > 0)
+ *
+ * Section 1 describes verification for greedy decoding and cites the speculative-sampling rule for
+ * sampled decoding (used at temperatures 0.2 and 0.6 in the experiments) without printing it.  What
+ * follows is that published rule: a draft token x ~ q is kept with probability min(1, p(x)/q(x));
+ * the first rejected draft is replaced by a sample of the normalised residual max(0, p - q); when all
+ * drafts are kept one more token is sampled from the target's next distribution.  The emitted
+ * sequence is then distributed exactly as sampling from the full model alone, which is the pin.
+ *
+ * Randomness is counter based so that both implementations draw the same numbers: the uniform for
+ * output index e and purpose c (0 draft, 1 accept test, 2 replacement / extra / plain sample) is
+ *   U(e, c) = (mix64(stream + (3e + c + 1) * GOLD) >> 11) * 2^-53,
+ *   stream  = mix64(mix64(seed + GOLD) ^ (102 << 32)).
+ */
+static uint64_t s_mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27; z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31; return z;
+}
+double orc_uniform(uint64_t seed, int64_t index, int32_t purpose) {
+    const uint64_t G = 0x9E3779B97F4A7C15ULL;
+    const uint64_t stream = s_mix64(s_mix64(seed + G) ^ ((uint64_t)102 << 32));
+    const uint64_t c = (uint64_t)(3 * index + purpose);
+    return (double)(s_mix64(stream + (c + 1) * G) >> 11) * (1.0 / 9007199254740992.0);
+}
+
+/* Unnormalised softmax weights at temperature T: w_i = exp((l_i - max l) / T); returns their sum. */
+static double softmax_weights(const double* logits, int32_t V, double T, double* w) {
+    double mx = logits[0], Z = 0.0;
+    for (int i = 1; i < V; ++i) if (logits[i] > mx) mx = logits[i];
+    for (int i = 0; i < V; ++i) { w[i] = exp((logits[i] - mx) / T); Z += w[i]; }
+    return Z;
+}
+
+/*
+ * Inverse-CDF draw from non-negative weights (sum Z > 0): the smallest j whose running sum exceeds
+ * u * Z; if rounding leaves none, the last index with a positive weight.  margin (optional) receives
+ * the distance of u * Z to the nearer boundary of the chosen bin, relative to Z: how close the draw
+ * was to choosing a neighbour.
+ */
+int32_t orc_sample_weights(const double* w, int32_t V, double u, double* margin) {
+    double Z = 0.0;
+    for (int i = 0; i < V; ++i) Z += w[i];
+    const double t = u * Z;
+    double cum = 0.0;
+    int32_t last = 0;
+    for (int i = 0; i < V; ++i) {
+        if (w[i] > 0.0) last = i;
+        const double lo = cum;
+        cum += w[i];
+        if (cum > t) {
+            if (margin) *margin = fmin(t - lo, cum - t) / Z;
+            return i;
+        }
+    }
+    if (margin) *margin = 0.0;
+    return last;
+}
+
+/* Sample one token from softmax(logits / T) with the uniform u. */
+int32_t orc_sample_logits(const double* logits, int32_t V, double T, double u, double* margin) {
+    double* w = (double*)malloc(sizeof(double) * V);
+    softmax_weights(logits, V, T, w);
+    const int32_t tok = orc_sample_weights(w, V, u, margin);
+    free(w);
+    return tok;
+}
+
+/*
+ * One verification by speculative sampling.  q_logits [kk][V]: the draft model's logits that produced
+ * the drafts x[0..kk-1]; p_logits [kk+1][V]: the full model's logits for the same positions plus the
+ * one after.  u_acc [kk] and u_res [kk+1] are the uniforms of each position's accept test and
+ * replacement / extra draw.  Returns the number of accepted drafts a; *next receives the token that
+ * follows them (replacement of draft a, or the extra token when a == kk).  margin (optional) receives
+ * the smallest relative distance of any decision taken to its boundary.
+ */
+int32_t orc_spec_accept(const double* q_logits, const double* p_logits, const int32_t* x, int32_t kk, int32_t V, double T,
+                        const double* u_acc, const double* u_res, int32_t* next, double* margin) {
+    double* wq = (double*)malloc(sizeof(double) * V);
+    double* wp = (double*)malloc(sizeof(double) * V);
+    double mg = 1.0, m1 = 1.0;
+    int32_t a = 0;
+    for (; a < kk; ++a) {
+        const double Zq = softmax_weights(q_logits + (size_t)a * V, V, T, wq);
+        const double Zp = softmax_weights(p_logits + (size_t)a * V, V, T, wp);
+        const double q = wq[x[a]] / Zq, p = wp[x[a]] / Zp;
+        if (p < q) mg = fmin(mg, fabs(u_acc[a] - p / q));       /* else the ratio is >= 1 and u < 1 always passes */
+        if (u_acc[a] * q < p) continue;                         /* keep draft a */
+        /* rejected: replacement from the normalised residual (from p itself should the residual vanish) */
+        double R = 0.0;
+        for (int i = 0; i < V; ++i) { wq[i] = fmax(0.0, wp[i] / Zp - wq[i] / Zq); R += wq[i]; }
+        *next = R > 0.0 ? orc_sample_weights(wq, V, u_res[a], &m1) : orc_sample_weights(wp, V, u_res[a], &m1);
+        mg = fmin(mg, m1);
+        goto done;
+    }
+    softmax_weights(p_logits + (size_t)kk * V, V, T, wp);
+    *next = orc_sample_weights(wp, V, u_res[kk], &m1);
+    mg = fmin(mg, m1);
+done:
+    if (margin) *margin = mg;
+    free(wq); free(wp);
+    return a;
+}
+
+/*
+ * Sampled self-speculative decoding: the loop of orc_generate_spec with sampling.  The prompt pass's
+ * token (output index 0) is a plain draw U(0, 2) from the last prompt row; a cycle that starts at
+ * output index e drafts token e+j with U(e+j, 0) from the masked model, verifies with U(e+j, 1) and
+ * draws the token after the accepted prefix with U(e+a, 2).  With draft_len 0 this is plain sampling
+ * from the full model with U(e, 2).  min_margin (optional): smallest decision margin met.
+ */
+int orc_generate_sampled(orc_model* M, const int32_t* prompt, int32_t P, int32_t N, int32_t draft_len,
+                         const uint8_t* mask, double T, uint64_t seed, int32_t* out, orc_gen_stats* st, double* min_margin) {
+    if (!M || !prompt || !out || P < 1 || N < 1 || draft_len < 0 || !(T > 0.0)) return -1;
+    if (P + N + draft_len > M->c.max_seq) return -1;
+    const int V = M->c.vocab, k = draft_len;
+    double* ql = (double*)malloc(sizeof(double) * (size_t)(k > 0 ? k : 1) * V);
+    double* pl = (double*)malloc(sizeof(double) * (size_t)(k + 1) * V);
+    double* lp = (double*)malloc(sizeof(double) * V);
+    double* ua = (double*)malloc(sizeof(double) * (k + 1));
+    double* ur = (double*)malloc(sizeof(double) * (k + 1));
+    int32_t* rows = (int32_t*)malloc(sizeof(int32_t) * (k + 1));
+    orc_gen_stats s = {0, 0, 0, 0};
+    double mg = 1.0, m1 = 1.0;
+    M->kv_len = 0;
+    int rc = P > 1 ? orc_forward(M, prompt, P - 1, 0, NULL, 1, NULL, NULL, NULL, NULL) : 0;
+    if (rc) goto done;
+    rc = orc_forward(M, prompt + P - 1, 1, P - 1, NULL, 1, lp, NULL, NULL, NULL);
+    if (rc) goto done;
+    int32_t last = orc_sample_logits(lp, V, T, orc_uniform(seed, 0, 2), &m1);
+    mg = fmin(mg, m1);
+    out[0] = last; s.emitted = 1;
+    int32_t p = P;
+    while (s.emitted < N) {
+        const int e = (int)s.emitted;
+        const int kk = k < N - e - 1 ? k : N - e - 1;
+        rows[0] = last;
+        for (int j = 0; j < kk; ++j) {                 /* draft with D: token of output index e + j */
+            rc = orc_forward(M, &rows[j], 1, p + j, mask, 1, ql + (size_t)j * V, NULL, NULL, NULL);
+            if (rc) goto done;
+            rows[j + 1] = orc_sample_logits(ql + (size_t)j * V, V, T, orc_uniform(seed, e + j, 0), &m1);
+            mg = fmin(mg, m1);
+        }
+        orc_truncate(M, p);
+        rc = orc_forward(M, rows, kk + 1, p, NULL, 1, pl, NULL, NULL, NULL);      /* verify with M */
+        if (rc) goto done;
+        for (int j = 0; j <= kk; ++j) { ua[j] = orc_uniform(seed, e + j, 1); ur[j] = orc_uniform(seed, e + j, 2); }
+        int32_t nxt;
+        const int a = orc_spec_accept(ql, pl, rows + 1, kk, V, T, ua, ur, &nxt, &m1);
+        mg = fmin(mg, m1);
+        for (int j = 1; j <= a; ++j) out[s.emitted++] = rows[j];
+        out[s.emitted++] = nxt;
+        last = nxt;
+        p += a + 1;
+        orc_truncate(M, p);
+        s.cycles++; s.drafted += kk; s.accepted += a;
+    }
+done:
+    if (rc == 0) { if (st) *st = s; if (min_margin) *min_margin = mg; }
+    free(ql); free(pl); free(lp); free(ua); free(ur); free(rows);
     return rc;
 }
