@@ -206,6 +206,20 @@ def main():
                           "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()), "mask_changes": st["mask_changes"],
                           "tokens_equal_plain": bool(np.array_equal(toks, plain))}
         out["speculative"] = spec
+        # sampled decoding at the paper's higher temperature: plain sampling of the full model against speculative sampling
+        samp = {}
+        for name, kk, kw in (("plain_T0.6", 0, dict(fixed_mask=np.zeros(L2, np.uint8))),
+                             ("admg_a0.9999_m0_n0_T0.6", k, dict(alpha=0.9999, m=0, n=0))):
+            kw = dict(kw, temperature=0.6, seed=1, sample_index0=1)
+            decode_step(kk, **kw)
+            torch.cuda.synchronize()
+            t0 = time.time()
+            toks, st, used = decode_step(kk, **kw)
+            dt = time.time() - t0
+            samp[name] = {"tokens_per_s": round((N - 1) / dt, 2), "cycles": st["cycles"], "drafted": st["drafted"],
+                          "accepted": st["accepted"], "removed_attn": int(used[0::2].sum())}
+        samp["speedup"] = round(samp["admg_a0.9999_m0_n0_T0.6"]["tokens_per_s"] / samp["plain_T0.6"]["tokens_per_s"], 3)
+        out["sampled"] = samp
 
     eng.close()
     del eng

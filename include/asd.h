@@ -89,7 +89,19 @@ typedef struct {
  *   else gamma - eps, gamma <- beta2*gamma + (1-beta2)*gamma~, starting from
  *   gamma0, ar0.  The host decides, in double, on the fp32 probability the device
  *   computed; one device-to-host read per draft step.
- * Whatever these say, the emitted tokens equal plain greedy decoding.
+ * temperature 0: greedy decoding; whatever the fields above say, the emitted tokens
+ *   equal plain greedy decoding of the full model.
+ * temperature > 0: sampled decoding from softmax(logits / temperature).  Section 1 cites
+ *   the speculative-sampling rule for it without printing it: a draft x ~ q is kept with
+ *   probability min(1, p(x)/q(x)), the first rejected draft is replaced by a draw from the
+ *   normalised residual max(0, p - q), and when all drafts are kept one more token is
+ *   drawn from the full model; the emitted tokens are then distributed as samples of the
+ *   full model alone.  Uniforms are counter based on `seed`: output index e uses
+ *   U(e, c) = (mix64(stream + (3e + c + 1) * GOLD) >> 11) * 2^-53, c = 0 draft draw,
+ *   1 accept test, 2 replacement / extra / plain draw, with the synthetic-input
+ *   generator's stream key for tensor id 102.  asd_generate draws the prompt pass's
+ *   token with U(0, 2) and decodes from index 1; asd_decode starts at sample_index0.
+ *   exit_mode must be 0.
  */
 typedef struct {
     float alpha;
@@ -102,6 +114,9 @@ typedef struct {
     int32_t use_cs_mlp;
     int32_t exit_mode;
     double gamma0, ar0, ar_target, eps, beta1, beta2;
+    float temperature;
+    uint64_t seed;
+    int64_t sample_index0;
 } asd_gen_params;
 
 /* Counters of one asd_decode / asd_generate call (emitted includes the first token for asd_generate);
@@ -224,6 +239,17 @@ int asd_admg2(const float* c_all, int32_t n_layers, float alpha, int32_t m, int3
  */
 int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_params* p,
                int32_t* out_tokens, asd_gen_stats* stats, uint8_t* mask_used);
+
+/*
+ * The sampling kernels on caller-given logits (host arrays): q_logits [kk][vocab] are draft-model
+ * logits, p_logits [kk+1][vocab] the full model's for the same positions plus the next.  Draws the
+ * kk draft tokens (drafts_out [kk], output indices index0 .. index0+kk-1), verifies them by
+ * speculative sampling and returns the number kept (*n_accepted) and the token that follows them
+ * (*next_token).  0 <= kk < max_rows, temperature > 0.  Does not touch the KV cache.  For callers
+ * that bring their own logits, and for checking the kernels against the rule on known inputs.
+ */
+int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits, int32_t kk, float temperature, uint64_t seed,
+                    int64_t index0, int32_t* drafts_out, int32_t* n_accepted, int32_t* next_token);
 
 /* asd_prefill + ADMG + asd_decode: out_tokens [n_new], out_tokens[0] is the prompt pass's token. */
 int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t n_new, const asd_gen_params* p,

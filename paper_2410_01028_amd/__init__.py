@@ -38,7 +38,8 @@ class GenParams(ctypes.Structure):
                 ("draft_len", ctypes.c_int32), ("mask_mode", ctypes.c_int32), ("fixed_mask", ctypes.c_void_p),
                 ("use_graphs", ctypes.c_int32), ("alpha_mlp", ctypes.c_float), ("use_cs_mlp", ctypes.c_int32),
                 ("exit_mode", ctypes.c_int32)] + \
-               [(n, ctypes.c_double) for n in ("gamma0", "ar0", "ar_target", "eps", "beta1", "beta2")]
+               [(n, ctypes.c_double) for n in ("gamma0", "ar0", "ar_target", "eps", "beta1", "beta2")] + \
+               [("temperature", ctypes.c_float), ("seed", ctypes.c_uint64), ("sample_index0", ctypes.c_int64)]
 
 
 class GenStats(ctypes.Structure):
@@ -84,6 +85,7 @@ def lib():
         L.asd_prefill_chunked.argtypes = [vp, vp, i32, vp, vp, vp]
         L.asd_admg2.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, ctypes.c_float, i32, vp]
         L.asd_admg.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, vp]
+        L.asd_spec_sample.argtypes = [vp, vp, vp, i32, ctypes.c_float, ctypes.c_uint64, ctypes.c_int64, vp, vp, vp]
         L.asd_decode.argtypes = [vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
         L.asd_generate.argtypes = [vp, vp, i32, i32, ctypes.POINTER(GenParams), vp, ctypes.POINTER(GenStats), vp]
         L.asd_time_pass.argtypes = [vp, i32, vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
@@ -230,16 +232,17 @@ class Engine:
     @staticmethod
     def _params(draft_len, alpha=0.985, m=3, n=2, use_cs=True, fixed_mask=None, use_graphs=True, refresh=False,
                 alpha_mlp=0.0, use_cs_mlp=False, exit_mode=0, gamma0=0.0, ar0=1.0, ar_target=0.9, eps=0.01, beta1=0.5,
-                beta2=0.9):
+                beta2=0.9, temperature=0.0, seed=0, sample_index0=0):
         fm = None if fixed_mask is None else np.ascontiguousarray(fixed_mask, dtype=np.uint8)
         mode = 1 if fm is not None else (2 if refresh else 0)
         gp = GenParams(alpha, m, n, int(use_cs), draft_len, mode, _ptr(fm), int(use_graphs), alpha_mlp, int(use_cs_mlp),
-                       exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2)
+                       exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2, temperature, seed, sample_index0)
         return gp, fm
 
     def decode(self, last_token: int, n_more: int, draft_len: int, **kw):
         """Speculative decode from the current cache; kw: alpha, m, n, use_cs, fixed_mask, use_graphs, refresh
-        (mask rebuilt from the running ACS), alpha_mlp / use_cs_mlp, exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2."""
+        (mask rebuilt from the running ACS), alpha_mlp / use_cs_mlp, exit_mode, gamma0, ar0, ar_target, eps, beta1, beta2,
+        temperature (> 0: sampled decoding by speculative sampling), seed, sample_index0."""
         gp, fm = self._params(draft_len, **kw)
         out = np.empty(n_more, dtype=np.int32)
         st = GenStats()
@@ -257,6 +260,17 @@ class Engine:
         self._ck(lib().asd_generate(self._h, p.ctypes.data, p.size, n_new, ctypes.byref(gp), out.ctypes.data,
                                     ctypes.byref(st), mask.ctypes.data))
         return out, self._stats(st), mask
+
+    def spec_sample(self, q_logits, p_logits, temperature: float, seed: int, index0: int = 0):
+        """The sampling kernels on given logits: q [kk, V] draft, p [kk+1, V] full model; returns (drafts, accepted, next)."""
+        p = np.ascontiguousarray(p_logits, dtype=np.float32)
+        kk = p.shape[0] - 1
+        q = np.ascontiguousarray(q_logits, dtype=np.float32).reshape(kk, p.shape[1]) if kk else None
+        drafts = np.zeros(max(kk, 1), dtype=np.int32)
+        a, nxt = ctypes.c_int32(), ctypes.c_int32()
+        self._ck(lib().asd_spec_sample(self._h, _ptr(q), p.ctypes.data, kk, temperature, seed, index0, drafts.ctypes.data,
+                                       ctypes.byref(a), ctypes.byref(nxt)))
+        return drafts[:kk], int(a.value), int(nxt.value)
 
     @staticmethod
     def _stats(st: GenStats) -> dict:

@@ -104,5 +104,5 @@ struct DevState {
     int32_t target;     // tokens to emit in this decode call
     int32_t cycles, drafted, accepted;
     float conf;         // top-1 probability of the token the last draft step produced (softmax of its logits)
-    int32_t pad;
+    int32_t index_base; // sampled decoding: output index of the first token this decode call emits
 };

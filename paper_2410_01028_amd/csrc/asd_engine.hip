@@ -8,6 +8,7 @@
 #include "asd_misc.h"
 #include "asd_persist.h"
 #include "asd_prefill.h"
+#include "asd_sample.h"
 
 #include <chrono>
 #include <cmath>
@@ -59,6 +60,8 @@ struct asd_engine {
     // workspace
     float *xres, *ssq, *part, *cos_rows, *logits, *o_part, *rope;
     float* ml_part;
+    float* qlogits;                     // [16][vocab] draft-model logits of a sampled cycle
+    int last_logits_row;                // row of `logits` holding the last prompt row after a prompt pass
     unsigned* arrivals;
     void *xb, *q, *attn_out, *hmid;
     unsigned* counters;
@@ -93,6 +96,8 @@ struct asd_engine {
     unsigned long long bar_count;
     int32_t* bar_err;
     std::vector<uint8_t> graph_mask;
+    float graph_T;
+    uint64_t graph_seed;
     std::string err;
 };
 
@@ -166,7 +171,7 @@ struct Plan {
     size_t embed, lm, g_final, layer0, layer_stride, wqkv, wo, wg, wu, wd, g_attn, g_mlp;
     size_t kv, kv_layer, page_table;
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
-        argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total;
+        argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total, qlogits;
     size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_o_part, pf_ml_part, pf_xb, pf_q, pf_attn_out, pf_hmid;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
@@ -216,6 +221,7 @@ Plan make_plan(const asd_config& c) {
     p.part = take((size_t)pmax * ASD_ROWS * 2 * 4);
     p.cos_rows = take((size_t)2 * c.n_layers * ASD_ROWS * 4);
     p.logits = take((size_t)ASD_ROWS * c.vocab * 4);
+    p.qlogits = take((size_t)ASD_ROWS * c.vocab * 4);
     p.o_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
     p.rope = take((size_t)p.n_pages * c.page_tokens * (c.head_dim / 2) * 2 * 4);
     p.ml_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * 8);
@@ -787,7 +793,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     }
     e->kv = A + p.kv; e->kv_layer_bytes = p.kv_layer; e->page_table = (int32_t*)(A + p.page_table);
     e->xres = (float*)(A + p.xres); e->ssq = (float*)(A + p.ssq); e->part = (float*)(A + p.part);
-    e->cos_rows = (float*)(A + p.cos_rows); e->logits = (float*)(A + p.logits); e->o_part = (float*)(A + p.o_part);
+    e->cos_rows = (float*)(A + p.cos_rows); e->logits = (float*)(A + p.logits); e->qlogits = (float*)(A + p.qlogits); e->last_logits_row = 0; e->o_part = (float*)(A + p.o_part);
     e->rope = (float*)(A + p.rope); e->ml_part = (float*)(A + p.ml_part); e->arrivals = (unsigned*)(A + p.arrivals);
     e->xb = A + p.xb; e->q = A + p.q; e->attn_out = A + p.attn_out; e->hmid = A + p.hmid;
     e->counters = (unsigned*)(A + p.counters); e->cos_acc = (double*)(A + p.cos_acc);
@@ -802,7 +808,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
-    e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
+    e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
     // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
     e->persistent = false; e->pass_grid = 0;
     {
@@ -1087,6 +1093,7 @@ static int prefill_impl(asd_engine* e, const int32_t* tokens, int32_t n, int32_t
         }
         last_row = rows - 1;
     }
+    e->last_logits_row = last_row;
     std::vector<double> acc(L2);
     int32_t am[ASD_ROWS];
     CK(e, hipMemcpyAsync(acc.data(), e->cos_acc, (size_t)L2 * 8, hipMemcpyDeviceToHost, e->stream));
@@ -1125,6 +1132,58 @@ static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int
     return enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, kk);
 }
 
+// sampling stream key: the synthetic-input generator's stream derivation for tensor id 102
+static SampleArgs sample_args(asd_engine* e, float temperature, uint64_t seed) {
+    SampleArgs a{};
+    a.logits = e->logits; a.qlogits = e->qlogits; a.V = e->c.vocab; a.inv_T = 1.f / temperature;
+    a.stream = h_stream(seed, 102u, 0u);
+    a.st = e->st; a.tokbuf = e->tokbuf; a.out = e->out_tokens;
+    return a;
+}
+
+// one sampled draft / verify / accept cycle, enqueue only
+static int enqueue_sampled_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx, const SampleArgs& sa) {
+    for (int j = 0; j < kk; ++j) {
+        int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_NONE, 0);
+        if (rc) return rc;
+        sample_draft_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+    }
+    int rc = enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_NONE, 0);
+    if (rc) return rc;
+    sample_accept_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+    return ASD_OK;
+}
+
+int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits, int32_t kk, float temperature, uint64_t seed,
+                    int64_t index0, int32_t* drafts_out, int32_t* n_accepted, int32_t* next_token) {
+    if (!e) return ASD_E_INVAL;
+    if (!p_logits || !n_accepted || !next_token || (kk > 0 && (!q_logits || !drafts_out)))
+        return fail(e, ASD_E_INVAL, "NULL argument");
+    if (kk < 0 || kk + 1 > e->c.max_rows) return fail(e, ASD_E_INVAL, "kk %d outside [0, %d]", kk, e->c.max_rows - 1);
+    if (!(temperature > 0.f) || !std::isfinite(temperature)) return fail(e, ASD_E_INVAL, "temperature must be positive and finite");
+    if (index0 < 0 || index0 > (1 << 30)) return fail(e, ASD_E_INVAL, "index0 out of range");
+    const size_t V = e->c.vocab;
+    const SampleArgs sa = sample_args(e, temperature, seed);
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, kk + 1, 1, (int)index0);
+    for (int j = 0; j < kk; ++j) {                 // each draft row takes the place a draft step's logits would have
+        CK(e, hipMemcpyAsync(e->logits, q_logits + (size_t)j * V, V * 4, hipMemcpyHostToDevice, e->stream));
+        sample_draft_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+    }
+    CK(e, hipMemcpyAsync(e->logits, p_logits, (size_t)(kk + 1) * V * 4, hipMemcpyHostToDevice, e->stream));
+    sample_accept_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+    int32_t tb[ASD_ROWS + 1];
+    CK(e, hipMemcpyAsync(tb, e->tokbuf, sizeof tb, hipMemcpyDeviceToHost, e->stream));
+    CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
+    int32_t drafts[ASD_ROWS];
+    // the accept step overwrote tokbuf[0] with the next token; the drafts are still in rows 1..kk
+    CK(e, hipStreamSynchronize(e->stream));
+    for (int j = 0; j < kk; ++j) drafts[j] = tb[j + 1];
+    if (kk > 0) memcpy(drafts_out, drafts, (size_t)kk * 4);
+    *n_accepted = e->h_st->accepted;
+    *next_token = tb[0];
+    return ASD_OK;
+}
+
 // Run `enqueue` on the engine's stream: eagerly, or (use_graphs) as a HIP graph captured once per key.
 static int run_captured(asd_engine* e, bool use_graphs, const std::vector<int>& key, const std::function<int()>& enqueue) {
     if (!use_graphs || e->persistent) return enqueue();
@@ -1154,6 +1213,11 @@ static int check_gen_params(asd_engine* e, const asd_gen_params* p) {
         const bool ok = p->beta1 >= 0.0 && p->beta1 <= 1.0 && p->beta2 >= 0.0 && p->beta2 <= 1.0 && p->eps >= 0.0 && std::isfinite(p->eps) &&
                         std::isfinite(p->gamma0) && std::isfinite(p->ar0) && std::isfinite(p->ar_target);
         if (!ok) return fail(e, ASD_E_INVAL, "adaptive draft exit: beta1, beta2 in [0, 1], eps >= 0, finite gamma0 / ar0 / ar_target");
+    }
+    if (p->temperature != 0.f) {
+        if (!(p->temperature > 0.f) || !std::isfinite(p->temperature)) return fail(e, ASD_E_INVAL, "temperature must be >= 0 and finite");
+        if (p->exit_mode != 0) return fail(e, ASD_E_INVAL, "the adaptive draft exit is available for greedy decoding only");
+        if (p->sample_index0 < 0 || p->sample_index0 > (1 << 30)) return fail(e, ASD_E_INVAL, "sample_index0 out of range");
     }
     return ASD_OK;
 }
@@ -1187,9 +1251,14 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
     if (mask != e->graph_mask) { drop_graphs(e); e->graph_mask = mask; }
 
     const auto t0 = std::chrono::steady_clock::now();
-    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, n_more, 1);
+    const bool sampled = p->temperature > 0.f;
+    const SampleArgs sa = sampled ? sample_args(e, p->temperature, p->seed) : SampleArgs{};
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, n_more, 1, sampled ? (int)p->sample_index0 : 0);
     set_token_kernel<<<1, 1, 0, e->stream>>>(e->tokbuf, last_token);
     const bool graphs = p->use_graphs != 0;
+    if (sampled && (e->graph_T != p->temperature || e->graph_seed != p->seed)) {        // both are baked into captured launches
+        drop_graphs(e); e->graph_T = p->temperature; e->graph_seed = p->seed;
+    }
     double gamma = p->gamma0, ar = p->ar0;
     long mask_changes = 0;
     int emitted = 0, accepted = 0;
@@ -1197,7 +1266,10 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
         const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
         const int nc = chunks_for(e->kv_len + kk), ctx = e->kv_len + kk + 1;
         int d = kk;
-        if (p->exit_mode == 0) {
+        if (sampled) {
+            rc = run_captured(e, graphs, {3, kk, nc}, [&] { return enqueue_sampled_cycle(e, kk, mask.data(), nc, ctx, sa); });
+            if (rc) return rc;
+        } else if (p->exit_mode == 0) {
             rc = run_captured(e, graphs, {0, kk, nc}, [&] { return enqueue_cycle(e, kk, mask.data(), nc, ctx); });
             if (rc) return rc;
         } else {
@@ -1266,11 +1338,19 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
     int32_t t1 = 0;
     int rc = asd_prefill(e, prompt, n_prompt, &t1, nullptr, nullptr);
     if (rc) return rc;
+    asd_gen_params pp = *p;
+    if (p->temperature > 0.f) {           // the prompt pass's token is a plain draw with U(0, 2); decoding continues at index 1
+        const SampleArgs sa = sample_args(e, p->temperature, p->seed);
+        sample_plain_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, e->last_logits_row, 0);
+        CK(e, hipMemcpyAsync(&t1, e->tokbuf, 4, hipMemcpyDeviceToHost, e->stream));
+        CK(e, hipStreamSynchronize(e->stream));
+        pp.sample_index0 = 1;
+    }
     const double ms_pre = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     out[0] = t1;
     asd_gen_stats st{};
     if (n_new > 1) {
-        rc = asd_decode(e, t1, n_new - 1, p, out + 1, &st, mask_used);
+        rc = asd_decode(e, t1, n_new - 1, &pp, out + 1, &st, mask_used);
         if (rc) return rc;
     } else if (mask_used) {
         memset(mask_used, 0, 2 * (size_t)e->c.n_layers);

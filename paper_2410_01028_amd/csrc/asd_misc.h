@@ -38,8 +38,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, c
 }
 
 // ---------------------------------------------------------------- decoding state
-__global__ void set_state_kernel(DevState* st, int pos, int emitted, int target, int reset_counts) {
-    st->pos = pos; st->emitted = emitted; st->target = target;
+__global__ void set_state_kernel(DevState* st, int pos, int emitted, int target, int reset_counts, int index_base = 0) {
+    st->pos = pos; st->emitted = emitted; st->target = target; st->index_base = index_base;
     if (reset_counts) { st->cycles = 0; st->drafted = 0; st->accepted = 0; }
 }
 __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok; }
