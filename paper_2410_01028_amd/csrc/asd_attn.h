@@ -7,7 +7,7 @@
 // ascending chunk order; the groups of a head spread over many compute units (one unit alone cannot
 // pull a head's K/V fast enough).  When the context spans several groups, each group's partial goes to
 // global memory and the groups are merged in ascending order by the group that arrives last (its four waves
-// share the rows), or, for the batched chunks of a prompt block, by a row-parallel merge step.  Partials and the arrival counter are
+// share the rows), or by a separate row-parallel merge step (fuse_merge == 0).  Partials and the arrival counter are
 // exchanged with device-scope relaxed atomic stores / loads (served past the non-coherent per-XCD
 // L2), ordered by waiting for the stores to complete before the counter is bumped; no cache-wide fence.
 // A row at position p sees keys 0..p (causal among the rows of the call as well).
@@ -56,26 +56,7 @@ struct AttnArgs {
     unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
     int32_t fuse_merge;       // the last group of a head to arrive merges the groups (else: attn_merge_kernel does)
     void* out;                // tiled activation [n_h*h]
-    // prompt processing: blockIdx.z = 16-row chunk of a block of batch_rows rows (0 = a single call); element /
-    // float strides from one chunk's buffers to the next.  Needs fuse_merge == 0.
-    int32_t batch_rows;
-    int64_t zq, zout, zopart, zml;
 };
-
-// the arguments of chunk z of a batched call (rows 16z .. of the block), or `a` itself for a single call
-template <class T> __device__ __forceinline__ AttnArgs attn_item(const AttnArgs& a, int z) {
-    AttnArgs b = a;
-    if (a.batch_rows) {
-        using E = typename T::elem;
-        b.q = (const E*)a.q + (size_t)z * a.zq;
-        b.out = (E*)a.out + (size_t)z * a.zout;
-        b.o_part = a.o_part + (size_t)z * a.zopart;
-        b.ml_part = a.ml_part + (size_t)z * a.zml;
-        b.pos_off = a.pos_off + 16 * z;
-        b.M = min(16, a.batch_rows - 16 * z);
-    }
-    return b;
-}
 
 // key (0..63, relative to the chunk) held by score tile kt, tile row r
 template <class T> __device__ __forceinline__ int score_key(int kt, int r);
@@ -317,8 +298,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
 }
 
 template <class T, int H>
-__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a0) {
-    const AttnArgs a = attn_item<T>(a0, blockIdx.z);
+__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
@@ -328,9 +308,154 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a0) {
 
 // Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
 template <class T, int H>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a0) {
-    const AttnArgs a = attn_item<T>(a0, blockIdx.z);
+__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
     const int pos0 = a.st->pos + a.pos_off;
     if ((pos0 + a.M - 1) / ATT_GROUP == 0) return;      // a single group: attn_kernel already wrote the output
     attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, pos0, threadIdx.x);
+}
+
+// ---------------------------------------------------------------- prompt blocks: causal attention, one wave per 16 query rows
+// Rows 16c .. 16c+15 of a prompt block (cache positions pos0 + 16c ..) of one query head against all keys up to
+// their own positions: the wave walks the 64-key chunks in ascending order with a running maximum and sum per row
+// (the output accumulator is rescaled when the maximum grows), so nothing is exchanged between waves and the
+// result has one fixed order.  Same fragments and key order as the decode kernel above; the next chunk's K and
+// V^T fragments are requested before the current chunk's softmax and output product.  Workgroups are numbered
+// longest row block first.
+struct PfAttnArgs {
+    const void* q;            // [chunk][n_h*h/KE][16][KE], planes q_plane elements apart, chunks q_chunk apart
+    void* out;                // same layout
+    int64_t q_plane, q_chunk;
+    const void* kv;
+    const int32_t* page_table;
+    int32_t pos0, rows;       // cache position of row 0 of the block, valid rows
+    int32_t n_h, n_kv, h, page_tokens;
+    float scale;
+};
+
+template <class T, int H>
+__global__ __launch_bounds__(64) void pf_attn_kernel(const PfAttnArgs a) {
+    using E = typename T::elem;
+    constexpr int KE = T::KE, HS = H / (4 * KE), HT = H / 16, KST = 64 / (4 * KE), NP = T::NP;
+    const int lane = threadIdx.x, g = lane >> 4, m = lane & 15, r = lane & 15;
+    const int n_chunks = (a.rows + 15) / 16;
+    const int c = n_chunks - 1 - (int)blockIdx.x, head = blockIdx.y;
+    const int M = min(16, a.rows - 16 * c);
+    const int p0 = a.pos0 + 16 * c, last = p0 + M - 1, row_pos = p0 + m;
+    const int kvh = head / (a.n_h / a.n_kv), PT = a.page_tokens;
+    const E* qp = (const E*)a.q + (size_t)c * a.q_chunk + (size_t)head * H * 16;
+
+    u32x4 qf[HS][NP];
+#pragma unroll
+    for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+        for (int pl = 0; pl < NP; ++pl)
+            qf[hs][pl] = m < M ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * 16 + m) * KE) : u32x4{0u, 0u, 0u, 0u};
+
+    f32x4 o[HT];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mx = -INFINITY, l = 0.f;
+
+    u32x4 kf[4][HS], vf[HT][KST];
+    auto load = [&](int kc) {
+        const int page = a.page_table[(kc * ASD_CHUNK) / PT], slot0 = (kc * ASD_CHUNK) % PT;
+        const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
+        const E* Vp = Kp + (size_t)PT * H;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs)
+                kf[kt][hs] = *(const u32x4*)(Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE + hs * 4 * KE);
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+                vf[ht][ks] = *(const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE);
+    };
+
+    const int n_kc = last / ASD_CHUNK + 1;
+    load(0);
+    for (int kc = 0; kc < n_kc; ++kc) {
+        f32x4 s[4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf[kt][hs], qf[hs][pl]);
+        }
+        u32x4 vc[HT][KST];
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks) vc[ht][ks] = vf[ht][ks];
+        if (kc + 1 < n_kc) load(kc + 1);
+
+        // causal mask, running maximum and sum per row (= per column m)
+        float cm = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int key = kc * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
+                const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
+                s[kt][j] = v;
+                cm = fmaxf(cm, v);
+            }
+        cm = fmaxf(cm, __shfl_xor(cm, 16));
+        cm = fmaxf(cm, __shfl_xor(cm, 32));
+        const float mn = fmaxf(mx, cm);                         // finite from the first chunk on: key 0 is visible to every row
+        const float alpha = (mx == -INFINITY) ? 0.f : __expf(mx - mn);
+        float cs = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mn);
+                s[kt][j] = p;
+                cs += p;
+            }
+        cs += __shfl_xor(cs, 16);
+        cs += __shfl_xor(cs, 32);
+        l = l * alpha + cs;
+        mx = mn;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) { o[ht][0] *= alpha; o[ht][1] *= alpha; o[ht][2] *= alpha; o[ht][3] *= alpha; }
+
+        u32x4 pf[KST][NP];
+        if constexpr (KE == 8) {
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) {
+                    const f32x4& t = s[2 * ks + (w2 >> 1)];
+                    const float p0v = t[(w2 & 1) * 2], p1v = t[(w2 & 1) * 2 + 1];
+                    const uint32_t h0 = BF16::from_f32(p0v), h1 = BF16::from_f32(p1v);
+                    const uint32_t l0 = BF16::from_f32(p0v - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1v - BF16::to_f32((uint16_t)h1));
+                    pf[ks][0][w2] = h0 | (h1 << 16);
+                    pf[ks][1][w2] = l0 | (l1 << 16);
+                }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
+        }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+            for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) mma16<T>(o[ht], vc[ht][ks], pf[ks][pl]);
+    }
+
+    if (m < M) {
+        const float inv = 1.f / l;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) {
+            const float v[4] = {o[ht][0] * inv, o[ht][1] * inv, o[ht][2] * inv, o[ht][3] * inv};
+            store_act4<T>(a.out, a.q_plane, (int64_t)c * a.q_chunk, head * H + ht * 16 + 4 * g, m, v);
+        }
+    }
 }

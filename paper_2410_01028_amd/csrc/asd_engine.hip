@@ -73,7 +73,7 @@ struct asd_engine {
     size_t staging_bytes;
     // prompt-block workspace
     int32_t* pf_tok;
-    float *pf_xres, *pf_raw, *pf_ssq, *pf_rscale, *pf_cos_rows, *pf_o_part, *pf_ml_part;
+    float *pf_xres, *pf_raw, *pf_ssq, *pf_rscale, *pf_cos_rows;
     void *pf_xb, *pf_q, *pf_attn_out, *pf_hmid;
     PfCfg pf_qkv, pf_o, pf_gu, pf_down;
     // launch shapes
@@ -172,7 +172,7 @@ struct Plan {
     size_t kv, kv_layer, page_table;
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
         argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total, qlogits;
-    size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_o_part, pf_ml_part, pf_xb, pf_q, pf_attn_out, pf_hmid;
+    size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_xb, pf_q, pf_attn_out, pf_hmid;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
 };
@@ -253,8 +253,6 @@ Plan make_plan(const asd_config& c) {
     p.pf_ssq = take((size_t)PF_ROWS * 4);
     p.pf_rscale = take((size_t)PF_ROWS * 4);
     p.pf_cos_rows = take((size_t)2 * c.n_layers * PF_ROWS * 4);
-    p.pf_o_part = take((size_t)PF_CHUNKS * c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
-    p.pf_ml_part = take((size_t)PF_CHUNKS * c.n_heads * p.nc_stride * ASD_ROWS * 8);
     p.pf_xb = take((size_t)PF_CHUNKS * p.KBd * frag * NPL);
     p.pf_q = take((size_t)PF_CHUNKS * p.KBq * frag * NPL);
     p.pf_attn_out = take((size_t)PF_CHUNKS * p.KBq * frag * NPL);
@@ -640,16 +638,12 @@ template <int EPI> bool launch_pf_gemm(asd_engine* e, const PfCfg& g, const PfAr
     return e->c.dtype == ASD_DT_BF16 ? launch_pf_gemm_t<BF16, EPI>(e->stream, g, a, n_chunks) : launch_pf_gemm_t<F32, EPI>(e->stream, g, a, n_chunks);
 }
 
-template <class T> void launch_attn_batch_t(asd_engine* e, const AttnArgs& a, int n_chunks, int last_pos) {
-    const int H = e->c.head_dim, groups = last_pos / ATT_GROUP + 1;
-    const dim3 gp(groups, e->c.n_heads, n_chunks), gm(e->c.n_heads, (ASD_ROWS + ATT_RB - 1) / ATT_RB, n_chunks);
-#define ATT(h)                                                                  \
-    if (H == h) {                                                               \
-        attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                \
-        if (groups > 1) attn_merge_kernel<T, h><<<gm, 64, 0, e->stream>>>(a);   \
-    }
-    ATT(32) ATT(64) ATT(128)
-#undef ATT
+template <class T> void launch_pf_attn_t(asd_engine* e, const PfAttnArgs& a, int n_chunks) {
+    const int H = e->c.head_dim;
+    const dim3 grid(n_chunks, e->c.n_heads);
+    if (H == 32) pf_attn_kernel<T, 32><<<grid, 64, 0, e->stream>>>(a);
+    if (H == 64) pf_attn_kernel<T, 64><<<grid, 64, 0, e->stream>>>(a);
+    if (H == 128) pf_attn_kernel<T, 128><<<grid, 64, 0, e->stream>>>(a);
 }
 
 template <class T> void launch_pf_rows_t(asd_engine* e, int what, int rows, int n_chunks, int ksplit, const float* gain, float* cos_row, int tail_row) {
@@ -704,16 +698,12 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
             ok = ok && launch_pf_gemm<PF_QKV>(e, e->pf_qkv, a, n_chunks);
 
-            AttnArgs t{};
-            t.q = e->pf_q; t.q_plane = base.q_plane; t.out_plane = base.q_plane; t.kv = a.kv;
-            t.page_table = e->page_table; t.st = e->st; t.pos_off = 0; t.M = ASD_ROWS; t.RS = ASD_ROWS;
+            PfAttnArgs t{};
+            t.q = e->pf_q; t.out = e->pf_attn_out; t.q_plane = base.q_plane; t.q_chunk = base.q_chunk; t.kv = a.kv;
+            t.page_table = e->page_table; t.pos0 = r0; t.rows = rows;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
-            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
-            t.o_part = e->pf_o_part; t.ml_part = e->pf_ml_part; t.arrivals = e->arrivals; t.out = e->pf_attn_out; t.fuse_merge = 0;
-            t.batch_rows = rows; t.zq = base.q_chunk; t.zout = base.q_chunk;
-            t.zopart = (int64_t)c.n_heads * e->nc_stride * ASD_ROWS * c.head_dim; t.zml = (int64_t)c.n_heads * e->nc_stride * ASD_ROWS * 2;
-            if (c.dtype == ASD_DT_BF16) launch_attn_batch_t<BF16>(e, t, n_chunks, r0 + rows - 1);
-            else launch_attn_batch_t<F32>(e, t, n_chunks, r0 + rows - 1);
+            t.scale = 1.f / sqrtf((float)c.head_dim);
+            if (c.dtype == ASD_DT_BF16) launch_pf_attn_t<BF16>(e, t, n_chunks); else launch_pf_attn_t<F32>(e, t, n_chunks);
 
             PfArgs o = base;
             o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->pf_attn_out; o.x_plane = (int64_t)PF_CHUNKS * e->KBq * 64; o.x_chunk = (int64_t)e->KBq * 64;
@@ -802,7 +792,6 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->staging = A + p.staging; e->staging_bytes = p.staging_bytes;
     e->pf_tok = (int32_t*)(A + p.pf_tok); e->pf_xres = (float*)(A + p.pf_xres); e->pf_raw = (float*)(A + p.pf_raw);
     e->pf_ssq = (float*)(A + p.pf_ssq); e->pf_rscale = (float*)(A + p.pf_rscale); e->pf_cos_rows = (float*)(A + p.pf_cos_rows);
-    e->pf_o_part = (float*)(A + p.pf_o_part); e->pf_ml_part = (float*)(A + p.pf_ml_part);
     e->pf_xb = A + p.pf_xb; e->pf_q = A + p.pf_q; e->pf_attn_out = A + p.pf_attn_out; e->pf_hmid = A + p.pf_hmid;
     e->pf_qkv = pf_pick("qkv", 4, 1); e->pf_o = pf_pick("o", 4, 4); e->pf_gu = pf_pick("gu", 4, 1); e->pf_down = pf_pick("down", 4, 4);
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;

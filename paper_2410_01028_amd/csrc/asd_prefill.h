@@ -45,24 +45,6 @@ struct PfArgs {
     void* hmid; int64_t hmid_plane, hmid_chunk;
 };
 
-// four consecutive features n0..n0+3 (n0 % 4 == 0) of row m of one chunk, all planes
-template <class T>
-__device__ __forceinline__ void store_act4(void* base, int64_t plane, int64_t chunk_off, int n0, int m, const float (&v)[4]) {
-    using E = typename T::elem;
-    E* p = (E*)base + chunk_off + act_index<T>(n0, m, 16);
-    if constexpr (sizeof(E) == 2) {
-        uint32_t hi[4], lo[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            hi[j] = T::from_f32(v[j]);
-            lo[j] = T::from_f32(v[j] - T::to_f32((uint16_t)hi[j]));
-        }
-        *(uint2*)p = uint2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-        *(uint2*)(p + plane) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
-    } else {
-        *(float4*)p = float4{v[0], v[1], v[2], v[3]};
-    }
-}
 // four consecutive single-plane elements (cache rows)
 template <class T> __device__ __forceinline__ void store_elem4(typename T::elem* p, const float (&v)[4]) {
     if constexpr (sizeof(typename T::elem) == 2) {
