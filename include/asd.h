@@ -129,8 +129,8 @@ typedef struct {
 } asd_gen_stats;
 
 /* Per-kernel-class GPU time of one profiled forward pass, from HIP events on the engine's stream. */
-enum { ASD_K_EMBED = 0, ASD_K_QKV = 1, ASD_K_ATTN = 2, ASD_K_ATTN_MERGE = 3, ASD_K_OPROJ = 4, ASD_K_GATEUP = 5,
-       ASD_K_DOWN = 6, ASD_K_LMHEAD = 7, ASD_K_FINISH = 8, ASD_K_COUNT = 9 };
+enum { ASD_K_EMBED = 0, ASD_K_QKV = 1, ASD_K_ATTN = 2, ASD_K_OPROJ = 3, ASD_K_GATEUP = 4,
+       ASD_K_DOWN = 5, ASD_K_LMHEAD = 6, ASD_K_FINISH = 7, ASD_K_COUNT = 8 };
 typedef struct {
     double ms[ASD_K_COUNT];       /* summed duration of the launches of each class */
     int32_t launches[ASD_K_COUNT];

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 OK, E_INVAL, E_STATE, E_NOMEM, E_IO, E_HIP = 0, -1, -2, -3, -4, -5
 DT_F32, DT_BF16 = 0, 1
 MAX_ROWS = 16
-KERNEL_CLASSES = ("embed", "qkv", "attn", "attn_merge", "oproj", "gateup", "down", "lmhead", "finish")
+KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "finish")
 
 
 class AsdError(RuntimeError):
@@ -49,7 +49,7 @@ class GenStats(ctypes.Structure):
 
 
 class KernelTimes(ctypes.Structure):
-    _fields_ = [("ms", ctypes.c_double * 9), ("launches", ctypes.c_int32 * 9), ("bytes", ctypes.c_double * 9),
+    _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int32 * 8), ("bytes", ctypes.c_double * 8),
                 ("ms_total", ctypes.c_double)]
 
 

@@ -7,7 +7,7 @@
 // ascending chunk order; the groups of a head spread over many compute units (one unit alone cannot
 // pull a head's K/V fast enough).  When the context spans several groups, each group's partial goes to
 // global memory and the groups are merged in ascending order by the group that arrives last (its four waves
-// share the rows), or by a separate row-parallel merge step (fuse_merge == 0).  Partials and the arrival counter are
+// share the rows).  Partials and the arrival counter are
 // exchanged with device-scope relaxed atomic stores / loads (served past the non-coherent per-XCD
 // L2), ordered by waiting for the stores to complete before the counter is bumped; no cache-wide fence.
 // A row at position p sees keys 0..p (causal among the rows of the call as well).
@@ -54,7 +54,6 @@ struct AttnArgs {
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
     unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
-    int32_t fuse_merge;       // the last group of a head to arrive merges the groups (else: attn_merge_kernel does)
     void* out;                // tiled activation [n_h*h]
 };
 
@@ -279,7 +278,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         }
         __syncthreads();
     }
-    if (n_groups == 1 || !a.fuse_merge) return;
+    if (n_groups == 1) return;
 
     // ---- arrival: the group that completes the head's last outstanding group merges the groups
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -304,14 +303,6 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
     __shared__ unsigned s_old;
     if ((int)blockIdx.x * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;       // no row of this call sees this group
     attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
-}
-
-// Row-parallel merge for passes with more rows: one wave per (head, group of ATT_RB rows); same arithmetic.
-template <class T, int H>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
-    const int pos0 = a.st->pos + a.pos_off;
-    if ((pos0 + a.M - 1) / ATT_GROUP == 0) return;      // a single group: attn_kernel already wrote the output
-    attn_merge_rows<T, H, false>(a, blockIdx.x, blockIdx.y * ATT_RB, pos0, threadIdx.x);
 }
 
 // ---------------------------------------------------------------- prompt blocks: causal attention, one wave per 16 query rows

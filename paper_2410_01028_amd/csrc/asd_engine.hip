@@ -340,19 +340,15 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
     return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
 }
 
-template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc) {
     const int H = e->c.head_dim;
-    const dim3 gp((nc + ATT_GW - 1) / ATT_GW, e->c.n_heads), gm(e->c.n_heads, (a.M + ATT_RB - 1) / ATT_RB);
-#define ATT(h)                                                                  \
-    if (H == h) {                                                               \
-        if (merge) attn_merge_kernel<T, h><<<gm, 64, 0, e->stream>>>(a);        \
-        else attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                    \
-    }
-    ATT(32) ATT(64) ATT(128)
-#undef ATT
+    const dim3 gp((nc + ATT_GW - 1) / ATT_GW, e->c.n_heads);
+    if (H == 32) attn_kernel<T, 32><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
+    if (H == 64) attn_kernel<T, 64><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
+    if (H == 128) attn_kernel<T, 128><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
 }
-void launch_attn(asd_engine* e, const AttnArgs& a, int nc, bool merge) {
-    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc, merge); else launch_attn_t<F32>(e, a, nc, merge);
+void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
+    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
 }
 
 // ------------------------------------------------------------------ algorithmic bytes
@@ -449,9 +445,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
             t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
-            t.fuse_merge = 1;                    // the last group of a head to arrive merges that head's groups
             push(OP_ATTN, ASD_K_ATTN, 0, cls_bytes[ASD_K_ATTN] / L).t = t;
-            if (!t.fuse_merge) push(OP_MERGE, ASD_K_ATTN_MERGE, 0, 0).t = t;
 
             GemmArgs o = base;
             o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16;
@@ -507,8 +501,7 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d
             case OP_DOWN: ok = launch_gemm<EPI_RES>(e, e->g_down, op.g); break;
             case OP_GU: ok = launch_gemm<EPI_GU>(e, e->g_gu, op.g); break;
             case OP_LM: ok = launch_gemm<EPI_LM>(e, e->g_lm, op.g); break;
-            case OP_ATTN: launch_attn(e, op.t, nc, false); break;
-            case OP_MERGE: launch_attn(e, op.t, nc, true); break;
+            case OP_ATTN: launch_attn(e, op.t, nc); break;
             case OP_FINISH:
                 finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg,
                                                            e->st, e->tokbuf, e->out_tokens);
@@ -1446,7 +1439,7 @@ int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* mask, asd_
 
 int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps, double* us_avg, double* bytes_per_launch) {
     if (!e) return ASD_E_INVAL;
-    if (!us_avg || reps < 1 || cls <= ASD_K_EMBED || cls >= ASD_K_FINISH || cls == ASD_K_ATTN_MERGE)
+    if (!us_avg || reps < 1 || cls <= ASD_K_EMBED || cls >= ASD_K_FINISH)
         return fail(e, ASD_E_INVAL, "us_avg is NULL, reps < 1 or the class is not a timed step class");
     int rc = bench_checks(e, n_rows);
     if (rc) return rc;

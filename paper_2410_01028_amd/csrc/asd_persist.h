@@ -12,7 +12,7 @@
 #include "asd_gemm.h"
 #include "asd_misc.h"
 
-enum { OP_EMBED = 0, OP_QKV = 1, OP_ATTN = 2, OP_MERGE = 3, OP_OPROJ = 4, OP_GU = 5, OP_DOWN = 6, OP_LM = 7, OP_FINISH = 8 };
+enum { OP_EMBED = 0, OP_QKV = 1, OP_ATTN = 2, OP_OPROJ = 3, OP_GU = 4, OP_DOWN = 5, OP_LM = 6, OP_FINISH = 7 };
 
 struct PassOp {
     int32_t type;
@@ -128,14 +128,6 @@ __global__ __launch_bounds__(PASS_THREADS, 4) void pass_kernel(const PassArgs P)
                     attn_group<T, H, true>(op.t, valid ? u % ng : 0, valid ? u / ng : 0, valid, hw, lane,
                                            att_so + (size_t)half * ATT_GW * ATT_RH * H, att_ml + half * ATT_GW * ASD_ROWS * 2, att_old + half);
                 }
-                break;
-            }
-            case OP_MERGE: {
-                const int pos0 = op.t.st->pos + op.t.pos_off;
-                if ((pos0 + op.t.M - 1) / ATT_GROUP == 0) break;     // a single group: the attention step wrote the output
-                const int groups = (op.t.M + ATT_RB - 1) / ATT_RB, units = groups * op.t.n_h;
-                for (int u = w * G + wg; u < units; u += G * NWV)
-                    attn_merge_rows<T, H, true>(op.t, u % op.t.n_h, (u / op.t.n_h) * ATT_RB, pos0, lane);
                 break;
             }
             case OP_FINISH:

@@ -317,3 +317,33 @@ def test_persistent_pass_kernel_matches_step_kernels_bitwise(monkeypatch):
         eng.close()
     for x, y in zip(*results):
         assert np.array_equal(np.asarray(x), np.asarray(y))
+
+
+def test_degenerate_sizes():
+    """One-token prompt, one new token, the longest draft the row limit allows, and a cache filled to its last slot."""
+    s = si.SHAPES["tiny"]
+    eng, orc = build_pair(s, seed=1, max_seq=64, page_tokens=64)
+    L2 = 2 * s.n_layers
+    # prompt of one token, one new token
+    out, st, _ = eng.generate([5], 1, 0)
+    assert out.tolist() == orc.generate_plain([5], 1).tolist() and st["emitted"] == 1
+    # prompt of one token, then speculative decoding with k = max_rows - 1 drafts per cycle
+    skip = np.zeros(L2, np.uint8); skip[2] = 1
+    plain, _, _ = eng.generate([5], 30, 0)
+    out, st, _ = eng.generate([5], 30, asd.MAX_ROWS - 1, fixed_mask=skip)
+    assert np.array_equal(out, plain) and np.array_equal(plain, orc.generate_plain([5], 30))
+    # the cache filled exactly: prompt + new tokens + draft head-room = capacity
+    cap = 64
+    prompt = si.prompt(2, 20, s.vocab)
+    k = 3
+    n_new = cap - len(prompt) - k
+    plain, _, _ = eng.generate(prompt, n_new, 0)
+    out, st, _ = eng.generate(prompt, n_new, k, fixed_mask=skip)
+    assert np.array_equal(out, plain) and eng.kv_len <= cap
+    with pytest.raises(asd.AsdError):
+        eng.generate(prompt, n_new + 1, k, fixed_mask=skip)
+    # a prompt that fills every slot of the cache
+    first, acs, _ = eng.prefill(si.prompt(3, cap, s.vocab))
+    assert eng.kv_len == cap
+    o = make_oracle(s, seed=1, max_seq=cap).forward(si.prompt(3, cap, s.vocab), 0)
+    assert np.abs(acs - o["cos"]).max() < COS_TOL

@@ -60,3 +60,21 @@ def test_short_prompts_take_the_decode_kernels():
     first, acs, lg = eng.prefill(toks, want_logits=True)
     first2, acs2, lg2 = eng.prefill(toks, want_logits=True, chunked=True)
     assert first == first2 and np.array_equal(acs, acs2) and np.array_equal(lg, lg2)
+
+
+@pytest.mark.parametrize("n", [16, 17, 512, 513, 1039], ids=lambda n: f"n{n}")
+def test_block_boundaries_agree_with_the_chunked_pass(n):
+    """Prompt lengths at the 16-row and 512-row boundaries (one row spilling into a new chunk / a new block)."""
+    import paper_2410_01028_amd as asd
+    shape = BF_GQA
+    W = list(si.all_tensors(shape, 12))
+    eng = asd.Engine(asd.make_config(shape, 1088)).load(W)
+    ref = asd.Engine(asd.make_config(shape, 1088)).load(W)
+    toks = si.prompt(n, n + 3, shape.vocab)
+    f1, acs1, lg1 = eng.prefill(toks[:n], want_logits=True)
+    f2, acs2, lg2 = ref.prefill(toks[:n], want_logits=True, chunked=True)
+    assert eng.kv_len == n and np.abs(acs1 - acs2).max() < COS_TOL
+    assert rel_err(lg1, lg2) < TOL[shape.dtype]
+    a = eng.forward(toks[n:n + 3], n)["logits"]
+    b = ref.forward(toks[n:n + 3], n)["logits"]
+    assert rel_err(a, b).max() < TOL[shape.dtype]
