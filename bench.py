@@ -98,6 +98,7 @@ def main():
 
     first, acs, _ = eng.prefill(prompt)          # untimed: first touch of every weight, lazy runtime set-up
     torch.cuda.synchronize()
+    pf_prof = eng.profile_prefill(prompt) if (P > 16 and not args.no_extras) else None     # resets the cache: before the timed passes
     t0 = time.time()
     for _ in range(3):
         first, acs, _ = eng.prefill(prompt)
@@ -141,6 +142,19 @@ def main():
                       "model_TFLOPs": round((w_flop + a_flop) / t_prefill / 1e12, 1),
                       "frac_of_bf16_mfma_peak": round((w_flop + a_flop) / t_prefill / 2.5e15, 4),
                       "matrix_core_planes": 2 if shape.dtype else 1}
+    if pf_prof:
+        # event pair around every launch of one prompt pass; flops of a class = its contractions, each multiply-add once
+        out["prefill"]["kernels"] = {n: {"avg_us": round(v["ms"] / v["launches"] * 1e3, 1), "launches": v["launches"],
+                                         "TFLOPs": round(v["flops"] / v["ms"] / 1e9, 1) if v["flops"] else None}
+                                     for n, v in pf_prof.items() if n != "ms_total" and v["launches"]}
+        gu = pf_prof["gateup"]
+        tf = gu["flops"] / gu["ms"] / 1e9
+        planes = 2 if shape.dtype else 1
+        out["prefill"]["roofline"] = {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0 if shape.dtype else 157.3, "unit": "TFLOP/s",
+                                      "frac": round(tf / (2500.0 if shape.dtype else 157.3), 4),
+                                      "kernel": "pf_gemm_kernel<PF_GU> (prompt-block gate/up projection + SiLU*mul)",
+                                      "flops_per_launch": gu["flops"] / gu["launches"], "avg_launch_us": round(gu["ms"] / gu["launches"] * 1e3, 2),
+                                      "matrix_core_issue_frac": round(tf * planes / (2500.0 if shape.dtype else 157.3), 4)}
 
     # ---- roofline of the dominant kernel (gate/up projection GEMM), HIP events on the engine's stream
     reps = 5

@@ -255,8 +255,19 @@ int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits,
 int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t n_new, const asd_gen_params* p,
                  int32_t* out_tokens, asd_gen_stats* stats, uint8_t* mask_used);
 
+/* Per-kernel-class GPU time of one profiled prompt pass in blocks (asd_prefill's path for prompts of more than
+ * max_rows tokens); flops = multiply-adds x 2 of the class's contractions, each counted once. */
+enum { ASD_PK_ROWS = 0, ASD_PK_QKV = 1, ASD_PK_ATTN = 2, ASD_PK_OPROJ = 3, ASD_PK_GATEUP = 4, ASD_PK_DOWN = 5,
+       ASD_PK_LMHEAD = 6, ASD_PK_COUNT = 7 };
+typedef struct {
+    double ms[ASD_PK_COUNT];
+    int32_t launches[ASD_PK_COUNT];
+    double flops[ASD_PK_COUNT];
+    double ms_total;
+} asd_prefill_times;
+
 /*
- * Measurement helpers (benchmark only; they leave kv_len unchanged).
+ * Measurement helpers (benchmark only; they leave kv_len unchanged, except asd_profile_prefill).
  * asd_time_pass: average milliseconds of one forward pass of n_rows rows at the
  * current kv_len with the given mask, over reps back-to-back repetitions bracketed
  * by HIP events on the engine's stream (as a captured graph when use_graph != 0);
@@ -267,6 +278,9 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
  * microseconds per launch (weights differ from launch to launch, so no launch finds its weights cached) and the
  * algorithmic bytes one launch must read.  The steps run out of their usual order: the pass's activations are
  * scratch afterwards.
+ * asd_profile_prefill: the prompt pass in blocks over n > max_rows tokens (host array), once untimed and once with
+ * an event pair around every launch; ASD_PK_ROWS collects the row-wise kernels (embedding, residual add + cosine
+ * tap), ASD_PK_LMHEAD the last row's hand-over, LM head and argmax.  Resets the cache (kv_len 0 afterwards).
  * asd_copy_bench: average milliseconds of a plain device copy kernel moving
  * nbytes (read nbytes + write nbytes) inside the arena's scratch region; used to
  * calibrate byte counters and to report the achievable HBM rate.
@@ -275,6 +289,7 @@ int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, int32
                   double* ms_avg, double* bytes);
 int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* skip_mask, asd_kernel_times* out);
 int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps, double* us_avg, double* bytes_per_launch);
+int asd_profile_prefill(asd_engine* e, const int32_t* tokens, int32_t n, asd_prefill_times* out);
 int asd_copy_bench(asd_engine* e, size_t nbytes, int32_t reps, double* ms_avg);
 
 #ifdef __cplusplus

@@ -48,6 +48,14 @@ class GenStats(ctypes.Structure):
                 ("gamma", ctypes.c_double), ("ar", ctypes.c_double)]
 
 
+PREFILL_CLASSES = ("rows", "qkv", "attn", "oproj", "gateup", "down", "lmhead")
+
+
+class PrefillTimes(ctypes.Structure):
+    _fields_ = [("ms", ctypes.c_double * 7), ("launches", ctypes.c_int32 * 7), ("flops", ctypes.c_double * 7),
+                ("ms_total", ctypes.c_double)]
+
+
 class KernelTimes(ctypes.Structure):
     _fields_ = [("ms", ctypes.c_double * 8), ("launches", ctypes.c_int32 * 8), ("bytes", ctypes.c_double * 8),
                 ("ms_total", ctypes.c_double)]
@@ -91,6 +99,7 @@ def lib():
         L.asd_time_pass.argtypes = [vp, i32, vp, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.asd_profile_forward.argtypes = [vp, i32, vp, ctypes.POINTER(KernelTimes)]
         L.asd_copy_bench.argtypes = [vp, sz, i32, ctypes.POINTER(ctypes.c_double)]
+        L.asd_profile_prefill.argtypes = [vp, vp, i32, ctypes.POINTER(PrefillTimes)]
         L.asd_time_step_class.argtypes = [vp, i32, i32, i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         _lib = L
     return _lib
@@ -291,6 +300,15 @@ class Engine:
         out = {name: {"ms": kt.ms[i], "launches": kt.launches[i], "bytes": kt.bytes[i]}
                for i, name in enumerate(KERNEL_CLASSES)}
         out["ms_total"] = kt.ms_total
+        return out
+
+    def profile_prefill(self, tokens) -> dict:
+        """Per-class GPU time of the prompt pass in blocks (event pair around every launch); resets the cache."""
+        tok = np.ascontiguousarray(tokens, dtype=np.int32)
+        pt = PrefillTimes()
+        self._ck(lib().asd_profile_prefill(self._h, tok.ctypes.data, tok.size, ctypes.byref(pt)))
+        out = {name: {"ms": pt.ms[i], "launches": pt.launches[i], "flops": pt.flops[i]} for i, name in enumerate(PREFILL_CLASSES)}
+        out["ms_total"] = pt.ms_total
         return out
 
     def time_step_class(self, name: str, n_rows: int = 1, reps: int = 10):

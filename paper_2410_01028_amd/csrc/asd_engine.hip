@@ -661,10 +661,11 @@ void launch_pf_rows(asd_engine* e, int what, int rows, int n_chunks, int ksplit,
 
 // The whole prompt, block by block and layer by layer; leaves the last row's logits / greedy token in row 0 of the
 // decode buffers and the cosine sums of all rows in cos_acc (the caller cleared it).  Enqueue only.
-int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
+int prefill_blocks(asd_engine* e, const int32_t* tokens, int n, Profiler* profiler = nullptr) {
     const asd_config& c = e->c;
     const int L = c.n_layers, KE = e->KE;
-    const int qd = c.n_heads * c.head_dim;
+    const double qd = (double)c.n_heads * c.head_dim, kvd = (double)c.n_kv_heads * c.head_dim;
+    Prof pr{profiler, e->stream};
     auto wl = [&](PfArgs& a, const GemmCfg& cfg, int total_tiles, int KB) {
         a.n_tiles = total_tiles; a.KB = KB; a.w_tile_stride = cfg.kmajor ? 1 : KB; a.w_kb_stride = cfg.kmajor ? total_tiles : 1;
     };
@@ -674,7 +675,11 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
         const int n_chunks = (rows + 15) / 16;
         CK(e, hipMemcpyAsync(e->pf_tok, tokens + r0, (size_t)rows * 4, hipMemcpyHostToDevice, e->stream));
         set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, r0, 0, 0, 0);
+        pr.begin(ASD_PK_ROWS, 0);
         launch_pf_rows(e, 0, rows, n_chunks, 1, e->layers[0].g_attn, nullptr, 0);
+        pr.end();
+        // flops of each contraction over this block's rows (every weight multiply-add counted once), causal attention
+        const double fl_row = 2.0 * rows, ctx_sum = (double)rows * r0 + 0.5 * rows * (rows + 1.0);
 
         PfArgs base{};
         base.rows = rows; base.rscale = e->pf_rscale; base.raw = e->pf_raw;
@@ -689,38 +694,53 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
             a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->pf_xb; a.x_plane = (int64_t)PF_CHUNKS * e->KBd * 64; a.x_chunk = (int64_t)e->KBd * 64;
             wl(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
+            pr.begin(ASD_PK_QKV, fl_row * c.d_model * (qd + 2 * kvd));
             ok = ok && launch_pf_gemm<PF_QKV>(e, e->pf_qkv, a, n_chunks);
+            pr.end();
 
             PfAttnArgs t{};
             t.q = e->pf_q; t.out = e->pf_attn_out; t.q_plane = base.q_plane; t.q_chunk = base.q_chunk; t.kv = a.kv;
             t.page_table = e->page_table; t.pos0 = r0; t.rows = rows;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
             t.scale = 1.f / sqrtf((float)c.head_dim);
+            pr.begin(ASD_PK_ATTN, 4.0 * qd * ctx_sum);
             if (c.dtype == ASD_DT_BF16) launch_pf_attn_t<BF16>(e, t, n_chunks); else launch_pf_attn_t<F32>(e, t, n_chunks);
+            pr.end();
 
             PfArgs o = base;
             o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->pf_attn_out; o.x_plane = (int64_t)PF_CHUNKS * e->KBq * 64; o.x_chunk = (int64_t)e->KBq * 64;
             wl(o, e->g_o, c.d_model / 16, e->KBq);
+            pr.begin(ASD_PK_OPROJ, fl_row * qd * c.d_model);
             ok = ok && launch_pf_gemm<PF_RAW>(e, e->pf_o, o, n_chunks);
+            pr.end();
+            pr.begin(ASD_PK_ROWS, 0);
             launch_pf_rows(e, 1, rows, n_chunks, e->pf_o.KS < e->KBq ? e->pf_o.KS : e->KBq, ly.g_mlp, e->pf_cos_rows + (size_t)(2 * l) * PF_ROWS, 0);
+            pr.end();
 
             PfArgs gu = base;
             gu.W = (const u32x4*)ly.wg; gu.W2 = (const u32x4*)ly.wu; gu.X = (const u32x4*)e->pf_xb; gu.x_plane = a.x_plane; gu.x_chunk = a.x_chunk;
             wl(gu, e->g_gu, c.d_ffn / 16, e->KBd);
+            pr.begin(ASD_PK_GATEUP, fl_row * 2.0 * c.d_model * c.d_ffn);
             ok = ok && launch_pf_gemm<PF_GU>(e, e->pf_gu, gu, n_chunks);
+            pr.end();
 
             PfArgs dn = base;
             dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->pf_hmid; dn.x_plane = (int64_t)PF_CHUNKS * e->KBf * 64; dn.x_chunk = (int64_t)e->KBf * 64;
             wl(dn, e->g_down, c.d_model / 16, e->KBf);
+            pr.begin(ASD_PK_DOWN, fl_row * (double)c.d_model * c.d_ffn);
             ok = ok && launch_pf_gemm<PF_RAW>(e, e->pf_down, dn, n_chunks);
+            pr.end();
+            pr.begin(ASD_PK_ROWS, 0);
             launch_pf_rows(e, 1, rows, n_chunks, e->pf_down.KS < e->KBf ? e->pf_down.KS : e->KBf, l + 1 < L ? e->layers[l + 1].g_attn : e->g_final,
                            e->pf_cos_rows + (size_t)(2 * l + 1) * PF_ROWS, 0);
+            pr.end();
             if (!ok) return fail(e, ASD_E_STATE, "no prompt GEMM instance for this launch shape");
         }
         pf_cos_sum_kernel<<<2 * L, 256, 0, e->stream>>>(e->pf_cos_rows, rows, e->cos_acc);
         e->kv_len = r0 + rows;
     }
     // the last prompt row through the final norm and the LM head, as row 0 of a one-row pass
+    pr.begin(ASD_PK_LMHEAD, 2.0 * c.d_model * c.vocab);
     launch_pf_rows(e, 2, rows, 0, 1, nullptr, nullptr, rows - 1);
     std::vector<PassOp> ops;
     build_pass(e, 1, 0, nullptr, n, ops);
@@ -730,9 +750,9 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n) {
         if (!launch_gemm<EPI_LM>(e, e->g_lm, op.g)) return fail(e, ASD_E_STATE, "no kernel instance for the LM head");
     }
     finish_kernel<<<1, 64, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, 1, e->argmax, FIN_NONE, 0, e->st, e->tokbuf, e->out_tokens);
+    pr.end();
     hipError_t r = hipGetLastError();
     if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
-    (void)qd;
     return ASD_OK;
 }
 
@@ -1434,6 +1454,41 @@ int asd_profile_forward(asd_engine* e, int32_t n_rows, const uint8_t* mask, asd_
     for (hipEvent_t ev : pf.ev) hipEventDestroy(ev);
     if (rc) return rc;
     if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "profiled pass: %s", hipGetErrorString(r2));
+    return ASD_OK;
+}
+
+int asd_profile_prefill(asd_engine* e, const int32_t* tokens, int32_t n, asd_prefill_times* out) {
+    if (!e) return ASD_E_INVAL;
+    if (!tokens || !out) return fail(e, ASD_E_INVAL, "tokens or out is NULL");
+    if (n <= e->c.max_rows || n > capacity(e)) return fail(e, ASD_E_INVAL, "prompt length %d outside (%d, %d]", n, e->c.max_rows, capacity(e));
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    int rc = check_tokens(e, tokens, n);
+    if (rc) return rc;
+    const int L2 = 2 * e->c.n_layers;
+    e->kv_len = 0; e->acs_valid = false;
+    CK(e, hipMemsetAsync(e->cos_acc, 0, (size_t)L2 * 8, e->stream));
+    rc = prefill_blocks(e, tokens, n);                 // warm-up
+    if (rc) return rc;
+    e->kv_len = 0;
+    CK(e, hipMemsetAsync(e->cos_acc, 0, (size_t)L2 * 8, e->stream));
+    Profiler pf;
+    rc = prefill_blocks(e, tokens, n, &pf);
+    hipError_t r2 = hipStreamSynchronize(e->stream);
+    memset(out, 0, sizeof *out);
+    if (!rc && r2 == hipSuccess) {
+        for (size_t i = 0; i < pf.cls.size(); ++i) {
+            float ms = 0.f;
+            hipEventElapsedTime(&ms, pf.ev[2 * i], pf.ev[2 * i + 1]);
+            out->ms[pf.cls[i]] += ms; out->launches[pf.cls[i]] += 1; out->flops[pf.cls[i]] += pf.bytes[i];
+        }
+        float tot = 0.f;
+        if (!pf.ev.empty()) hipEventElapsedTime(&tot, pf.ev.front(), pf.ev.back());
+        out->ms_total = tot;
+    }
+    for (hipEvent_t ev : pf.ev) hipEventDestroy(ev);
+    e->kv_len = 0;                                     // the cache content is the prompt's, but no ACS was kept: start over
+    if (rc) return rc;
+    if (r2 != hipSuccess) return fail(e, ASD_E_HIP, "profiled prompt pass: %s", hipGetErrorString(r2));
     return ASD_OK;
 }
 
