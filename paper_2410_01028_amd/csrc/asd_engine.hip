@@ -586,8 +586,6 @@ int check_tokens(asd_engine* e, const int32_t* t, int n) {
     return ASD_OK;
 }
 
-int check_mask(asd_engine*, const uint8_t*) { return ASD_OK; }
-
 void drop_graphs(asd_engine* e) {
     for (auto& kv : e->graphs) hipGraphExecDestroy(kv.second);
     e->graphs.clear();

@@ -265,7 +265,6 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     }
 
     if constexpr (EPI == EPI_GU) {
-        using E = typename T::elem;
         for (int e = tid; e < TN * 256; e += NT) {
             const int s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
             if (m >= a.M || !tval[s]) continue;
@@ -278,7 +277,6 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     }
 
     if constexpr (EPI == EPI_RES) {
-        using E = typename T::elem;
 #pragma unroll
         for (int q = 0; q < NE; ++q) {
             const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
@@ -316,7 +314,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
         }
         __syncthreads();
         if (tid < 16) {
-            AmaxPart best{-INFINITY, 0x7fffffff};
+            AmaxPart best{-INFINITY, 0x7fffffff, 0.f, 0.f};
             for (int s = 0; s < NA; ++s)
                 for (int nl = 0; nl < 16; ++nl) {
                     const float v = epi_a[s * 256 + tid * 16 + nl];

@@ -122,14 +122,19 @@ __global__ __launch_bounds__(NW * 64) void pf_gemm_kernel(const PfArgs a) {
                     if (w + NW * i < XF) xs[buf][w + NW * i][lane] = xg[p][i];
                 __syncthreads();
                 if (kb + PD < kb1) issue(p, kb + PD);
+                // all LDS reads of the k-block are requested before its first MFMA: one LDS latency per k-block, not one per pair
+                u32x4 b[NC][NP];
 #pragma unroll
                 for (int c = 0; c < NC; ++c)
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) {
-                        const u32x4 b = xs[buf][c * NP + pl][lane];
+                    for (int pl = 0; pl < NP; ++pl) b[c][pl] = xs[buf][c * NP + pl][lane];
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                        for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], ac[s], b);
-                    }
+                for (int c = 0; c < NC; ++c)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl)
+#pragma unroll
+                        for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], ac[s], b[c][pl]);
             }
         }
     }
