@@ -32,7 +32,7 @@ def cpu_baseline(shape, seed, n_prompt=2, n_decode=6):
     import asd_inputs as si
     import oracle
     t0 = time.time()
-    orc = oracle.Oracle(shape, n_prompt + n_decode + 1)
+    orc = oracle.Oracle(shape, n_prompt + n_decode + 1, kv_storage=True)
     for t, l, a in si.all_tensors(shape, seed):
         orc.set_weight(t, l, a)
     t_load = time.time() - t0

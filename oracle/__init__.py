@@ -26,7 +26,7 @@ def build(force: bool = False) -> str:
 class _Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab", "max_seq", "dtype")] + \
-               [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
+               [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double), ("kv_storage", ctypes.c_int32)]
 
 
 class _GenParams(ctypes.Structure):
@@ -176,13 +176,14 @@ def acs(cos_rows) -> np.ndarray:
 
 
 class Oracle:
-    """One model instance: weights in storage type, unrounded double KV cache."""
+    """One model instance: weights in storage type; the KV cache keeps K / V as computed (double), or, with
+    kv_storage=True, rounded to the model's storage type as the workloads define their caches."""
 
-    def __init__(self, shape, max_seq: int):
+    def __init__(self, shape, max_seq: int, kv_storage: bool = False):
         self.shape = shape
         self.max_seq = max_seq
         c = _Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
-                    shape.d_ffn, shape.vocab, max_seq, shape.dtype, shape.rms_eps, shape.rope_theta)
+                    shape.d_ffn, shape.vocab, max_seq, shape.dtype, shape.rms_eps, shape.rope_theta, int(kv_storage))
         self._h = _L().orc_create(ctypes.byref(c))
         if not self._h:
             raise ValueError("orc_create: invalid configuration")

@@ -16,8 +16,9 @@
  * tests, the smoke check and the benchmark's CPU-baseline leg may call it.
  * Weights are kept in their storage type (fp32, or bf16 bit patterns) and are
  * widened exactly to double on use; every reduction is a sequential double
- * sum, and nothing is rounded in between, so multi-row calls equal one-row
- * calls bit for bit.  OpenMP only distributes independent output elements.
+ * sum, and nothing is rounded in between (except, when the configuration says
+ * so, K and V on their way into the cache: the workloads keep the KV cache in
+ * the model's storage type), so multi-row calls equal one-row calls bit for bit.  OpenMP only distributes independent output elements.
  *
  * Parity status: decoder, cosine, ADMG and the speculative loop are pinned by
  * the CPU tests (independent Llama implementation, closed forms, invariants,
@@ -44,6 +45,10 @@ enum {
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab, max_seq, dtype;
     double rms_eps, rope_theta;
+    int32_t kv_storage;         /* 0: the cache keeps K and V as computed (double); 1: K and V are stored in the   */
+                                /* model's storage type, as the workloads define their KV cache (bf16 models keep  */
+                                /* a bf16 cache): each value is rounded to fp32, then for bf16 to nearest-even     */
+                                /* bf16, when it is written; everything else stays double                         */
 } orc_config;
 
 typedef struct {
@@ -84,6 +89,18 @@ static inline double wget(const void* w, int dtype, size_t i) {
         return (double)f;
     }
     return (double)((const float*)w)[i];
+}
+
+/* A value as the KV cache of a model of storage type dtype holds it (see orc_config.kv_storage). */
+static double to_storage(double v, int dtype) {
+    float f = (float)v;
+    if (dtype == ORC_BF16) {
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        u = (u + 0x7fffu + ((u >> 16) & 1u)) & 0xffff0000u;      /* round to nearest even on the upper 16 bits */
+        memcpy(&f, &u, 4);
+    }
+    return (double)f;
 }
 
 static void tensor_dims(const orc_config* c, int t, size_t* rows, size_t* cols) {
@@ -260,6 +277,8 @@ static void decoder_row(orc_model* M, int tok, int pos, const uint8_t* skip,
             matvec(L->wv, dt, kd, d, xn, vr);
             for (int a = 0; a < nh; ++a) rope(q + a * h, h, pos, c->rope_theta);
             for (int a = 0; a < nkv; ++a) rope(kr + a * h, h, pos, c->rope_theta);
+            if (c->kv_storage)
+                for (int i = 0; i < kd; ++i) { kr[i] = to_storage(kr[i], dt); vr[i] = to_storage(vr[i], dt); }
             double scale = 1.0 / sqrt((double)h);
             for (int a = 0; a < nh; ++a) {
                 int kvh = a / group;

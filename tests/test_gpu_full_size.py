@@ -22,7 +22,7 @@ def eng7b():
 def test_7b_shape_short_context_against_oracle(eng7b):
     """Teacher-forced logits and cosines of 6 prompt rows + 2 single rows, all 32 layers, oracle in fp64."""
     s, eng = eng7b
-    orc = oracle.Oracle(s, 16)
+    orc = oracle.Oracle(s, 16, kv_storage=True)
     for t, l, a in si.all_tensors(s, 0):
         orc.set_weight(t, l, a)
     toks = si.prompt(0, 8, s.vocab)
@@ -40,6 +40,33 @@ def test_7b_shape_short_context_against_oracle(eng7b):
     assert err.max() < 2e-2, err
     assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
     orc.close()
+
+
+def test_7b_shape_prompt_blocks_against_oracle(eng7b):
+    """The prompt pass in blocks (large-M kernels) at full width and depth: 40 prompt rows against the oracle, then the
+    full 512-row prompt against the decode-kernel path (both on the GPU)."""
+    s, eng = eng7b
+    orc = oracle.Oracle(s, 48, kv_storage=True)
+    for t, l, a in si.all_tensors(s, 0):
+        orc.set_weight(t, l, a)
+    toks = si.prompt(0, 44, s.vocab)
+    first, acs, lg = eng.prefill(toks[:40], want_logits=True)
+    o = orc.forward(toks[:40], 0)
+    assert np.abs(acs - o["cos"]).max() < 1e-3
+    assert np.abs(lg - o["logits"][-1]).max() / np.abs(o["logits"][-1]).max() < 2e-2
+    g = eng.forward(toks[40:44], 40)                      # reads the cache the block pass wrote
+    o2 = orc.forward(toks[40:44], 40)
+    err = np.abs(g["logits"] - o2["logits"]).max(-1) / np.abs(o2["logits"]).max(-1)
+    assert err.max() < 2e-2, err
+    orc.close()
+    prompt = si.prompt(0, s.prompt_len, s.vocab)
+    f1, a1, l1 = eng.prefill(prompt, want_logits=True)
+    n1 = eng.forward(prompt[:3], s.prompt_len, commit=False)["logits"]
+    f2, a2, l2 = eng.prefill(prompt, want_logits=True, chunked=True)
+    n2 = eng.forward(prompt[:3], s.prompt_len, commit=False)["logits"]
+    assert f1 == f2 and np.abs(a1 - a2).max() < 1e-3
+    assert np.abs(l1 - l2).max() / np.abs(l2).max() < 2e-2
+    assert (np.abs(n1 - n2).max(-1) / np.abs(n2).max(-1)).max() < 2e-2
 
 
 def test_7b_full_benchmark_sizes_properties(eng7b):
@@ -72,7 +99,7 @@ def test_other_shapes_run_and_keep_invariants(name):
     """13B and 70B-GQA shapes at full width, reduced depth (4 layers) to keep the test short."""
     s = si.SHAPES[name].with_(n_layers=4)
     eng = asd.Engine(asd.make_config(s, 512, page_tokens=256)).init_synthetic(0)
-    orc = oracle.Oracle(s, 16)
+    orc = oracle.Oracle(s, 16, kv_storage=True)
     for t, l, a in si.all_tensors(s, 0):
         orc.set_weight(t, l, a)
     toks = si.prompt(0, 200, s.vocab)

@@ -31,7 +31,7 @@ def rel_err(got, want):
 def build_pair(shape, seed=0, max_seq=256, gain_std=0.0, page_tokens=64):
     W = list(si.all_tensors(shape, seed, gain_std))
     eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens)).load(W)
-    orc = oracle.Oracle(shape, max_seq).load(W)
+    orc = oracle.Oracle(shape, max_seq, kv_storage=True).load(W)      # the engine's cache is in the storage type too
     return eng, orc
 
 
@@ -245,7 +245,7 @@ def test_long_context_merge_paths():
     eng = asd.Engine(asd.make_config(shape, 1536, page_tokens=128)).load(W)
     rng = np.random.default_rng(3)
     eng.set_page_table(rng.permutation(12))
-    orc = oracle.Oracle(shape, 1536).load(W)
+    orc = oracle.Oracle(shape, 1536, kv_storage=True).load(W)
     toks = si.prompt(5, 1500, shape.vocab)
     first, acs, _ = eng.prefill(toks[:1400])                 # 22 chunks
     o = orc.forward(toks[:1400], 0)
@@ -345,5 +345,5 @@ def test_degenerate_sizes():
     # a prompt that fills every slot of the cache
     first, acs, _ = eng.prefill(si.prompt(3, cap, s.vocab))
     assert eng.kv_len == cap
-    o = make_oracle(s, seed=1, max_seq=cap).forward(si.prompt(3, cap, s.vocab), 0)
+    o = make_oracle(s, seed=1, max_seq=cap, kv_storage=True).forward(si.prompt(3, cap, s.vocab), 0)
     assert np.abs(acs - o["cos"]).max() < COS_TOL

@@ -239,3 +239,64 @@ def test_rope_depends_on_relative_position_only():
     r = o.forward(np.full(8, 7, np.int32), 0, want_hidden=True)
     # identical tokens -> identical v at every position -> every row's hidden state equals row 0's
     assert np.abs(r["hidden"] - r["hidden"][0]).max() < 1e-13
+
+
+@pytest.mark.parametrize("dtype", [si.DT_BF16, si.DT_F32], ids=["bf16", "fp32"])
+def test_cache_in_storage_type_against_matrix_formulation(dtype):
+    """kv_storage: K (after the rotary embedding) and V are rounded to the model's storage type on their way into
+    the cache, nothing else.  One-layer whole-sequence numpy formulation with the rounding done by torch's own
+    float32 -> bfloat16 conversion (an independent implementation of round-to-nearest-even)."""
+    s = si.Shape("one", 1, 48, 3, 3, 16, 80, 50, dtype, 0, 0, 0)
+    w = {k: si.as_f64(a) for k, a in weights_dict(s, seed=9, gain_std=0.2).items()}
+    tok = si.prompt(4, 7, s.vocab)
+    S, h, nh = len(tok), s.head_dim, s.n_heads
+    rms = lambda x, g: x / np.sqrt((x * x).mean(-1, keepdims=True) + s.rms_eps) * g
+
+    def store(A):
+        t = torch.tensor(np.asarray(A, dtype=np.float64)).to(torch.float32)
+        if dtype == si.DT_BF16:
+            t = t.to(torch.bfloat16)
+        return t.to(torch.float64).numpy()
+
+    X = w[(si.T_EMBED, 0)][tok]
+    xn = rms(X, w[(si.T_ATTN_NORM, 0)])
+    Q, K, V = (xn @ w[(t, 0)].T for t in (si.T_WQ, si.T_WK, si.T_WV))
+    ang = np.arange(S)[:, None] * s.rope_theta ** (-2.0 * np.arange(h // 2) / h)[None, :]
+
+    def rot(A):
+        A = A.reshape(S, nh, h)
+        a, b = A[..., : h // 2], A[..., h // 2:]
+        c, sn = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+        return np.concatenate([a * c - b * sn, b * c + a * sn], -1)
+
+    Qr, Kr, Vh = rot(Q), store(rot(K)), store(V.reshape(S, nh, h))
+    sc = np.einsum("ind,jnd->nij", Qr, Kr) / np.sqrt(h)
+    sc = np.where(np.tril(np.ones((S, S), bool))[None], sc, -np.inf)
+    P = np.exp(sc - sc.max(-1, keepdims=True))
+    P /= P.sum(-1, keepdims=True)
+    O = np.einsum("nij,jnd->ind", P, Vh).reshape(S, nh * h)
+    Y = X + O @ w[(si.T_WO, 0)].T
+    yn = rms(Y, w[(si.T_MLP_NORM, 0)])
+    G, U = yn @ w[(si.T_WG, 0)].T, yn @ w[(si.T_WU, 0)].T
+    Z = Y + (G / (1 + np.exp(-G)) * U) @ w[(si.T_WD, 0)].T
+    logits = rms(Z, w[(si.T_FINAL_NORM, 0)]) @ w[(si.T_LM_HEAD, 0)].T
+
+    r = make_oracle(s, seed=9, max_seq=16, gain_std=0.2, kv_storage=True).forward(tok, 0, want_hidden=True)
+    assert np.abs(r["logits"] - logits).max() < 1e-12 and np.abs(r["hidden"] - Z).max() < 1e-13
+    # and it is a different function from the unrounded cache, by about the storage type's rounding
+    r0 = make_oracle(s, seed=9, max_seq=16, gain_std=0.2).forward(tok, 0)
+    gap = np.abs(r["logits"] - r0["logits"]).max() / np.abs(r0["logits"]).max()
+    assert (1e-7 < gap < 2e-2) if dtype == si.DT_BF16 else (1e-12 < gap < 1e-6)      # (this sublayer's output scale is small)
+
+
+def test_cache_in_storage_type_keeps_the_loop_invariants():
+    s = SMALL_GQA.with_(dtype=si.DT_BF16)
+    o = make_oracle(s, seed=3, kv_storage=True)
+    tok = si.prompt(5, 12, s.vocab)
+    a = o.forward(tok, 0)
+    o.reset()
+    rows = [o.forward(tok[i:i + 1], i) for i in range(12)]
+    assert all(np.array_equal(rows[i]["logits"][0], a["logits"][i]) for i in range(12))      # rows equal single calls
+    plain = o.generate_plain(tok, 14)
+    spec, st, _, _ = o.generate_spec(tok, 14, 3, 0.9, 2, 1)
+    assert np.array_equal(spec, plain)
