@@ -1,5 +1,9 @@
 """Parity at the benchmark's full width and depth (7B shape, bf16) on a short context, plus properties
-that hold at the full benchmark sizes (prompt 512, 256 tokens) in the launch configuration bench.py times."""
+that hold at the full benchmark sizes (prompt 512, 256 tokens) in the launch configuration bench.py times.
+
+Stated tolerances: logits 2e-2 of the row's largest |logit|, cosines 1e-3.  Measured at the 7B depth against the
+oracle with its cache in the storage type: 1e-3 and 3e-5 (32 layers of random weights amplify every rounding), so the
+assertions use 5e-3 and 1e-4 as working bounds."""
 import numpy as np
 import pytest
 
@@ -8,6 +12,8 @@ import oracle
 import paper_2410_01028_amd as asd
 
 pytestmark = pytest.mark.gpu
+
+TOL, COS_TOL = 5e-3, 1e-4
 
 
 @pytest.fixture(scope="module")
@@ -31,14 +37,14 @@ def test_7b_shape_short_context_against_oracle(eng7b):
         g = eng.forward(toks[lo:hi], lo)
         o = orc.forward(toks[lo:hi], lo)
         err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
-        assert err.max() < 2e-2, err
-        assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+        assert err.max() < TOL, err
+        assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < COS_TOL
     mask = si.fixed_keep_mask(s.n_layers, 2)
     g = eng.forward(toks[:3], 8, mask, commit=False)
     o = orc.forward(toks[:3], 8, mask, commit=False)
     err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
-    assert err.max() < 2e-2, err
-    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+    assert err.max() < TOL, err
+    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < COS_TOL
     orc.close()
 
 
@@ -52,21 +58,21 @@ def test_7b_shape_prompt_blocks_against_oracle(eng7b):
     toks = si.prompt(0, 44, s.vocab)
     first, acs, lg = eng.prefill(toks[:40], want_logits=True)
     o = orc.forward(toks[:40], 0)
-    assert np.abs(acs - o["cos"]).max() < 1e-3
-    assert np.abs(lg - o["logits"][-1]).max() / np.abs(o["logits"][-1]).max() < 2e-2
+    assert np.abs(acs - o["cos"]).max() < COS_TOL
+    assert np.abs(lg - o["logits"][-1]).max() / np.abs(o["logits"][-1]).max() < TOL
     g = eng.forward(toks[40:44], 40)                      # reads the cache the block pass wrote
     o2 = orc.forward(toks[40:44], 40)
     err = np.abs(g["logits"] - o2["logits"]).max(-1) / np.abs(o2["logits"]).max(-1)
-    assert err.max() < 2e-2, err
+    assert err.max() < TOL, err
     orc.close()
     prompt = si.prompt(0, s.prompt_len, s.vocab)
     f1, a1, l1 = eng.prefill(prompt, want_logits=True)
     n1 = eng.forward(prompt[:3], s.prompt_len, commit=False)["logits"]
     f2, a2, l2 = eng.prefill(prompt, want_logits=True, chunked=True)
     n2 = eng.forward(prompt[:3], s.prompt_len, commit=False)["logits"]
-    assert f1 == f2 and np.abs(a1 - a2).max() < 1e-3
-    assert np.abs(l1 - l2).max() / np.abs(l2).max() < 2e-2
-    assert (np.abs(n1 - n2).max(-1) / np.abs(n2).max(-1)).max() < 2e-2
+    assert f1 == f2 and np.abs(a1 - a2).max() < COS_TOL
+    assert np.abs(l1 - l2).max() / np.abs(l2).max() < TOL
+    assert (np.abs(n1 - n2).max(-1) / np.abs(n2).max(-1)).max() < TOL
 
 
 def test_7b_full_benchmark_sizes_properties(eng7b):
@@ -106,8 +112,8 @@ def test_other_shapes_run_and_keep_invariants(name):
     g = eng.forward(toks[:5], 0)
     o = orc.forward(toks[:5], 0)
     err = np.abs(g["logits"] - o["logits"]).max(-1) / np.abs(o["logits"]).max(-1)
-    assert err.max() < 2e-2, err
-    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < 1e-3
+    assert err.max() < TOL, err
+    assert np.abs(g["cos_rows"] - o["cos_rows"]).max() < COS_TOL
     orc.close()
     plain, _, _ = eng.generate(toks, 24, 0)
     out, st, _ = eng.generate(toks, 24, 6, fixed_mask=np.array([0, 0, 1, 0, 0, 1, 0, 0], np.uint8))

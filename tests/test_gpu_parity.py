@@ -1,8 +1,10 @@
 """GPU parity: the HIP engine (through the C ABI) against the CPU oracle, element by element.
 
-Tolerances (stated by the benchmark spec): logits within 2e-2 (bf16) / 1e-4 (fp32) of the row's largest
-|logit| (inf-norm relative, teacher-forced on the same tokens); cosine similarities within 1e-3
-absolute; token sequences bit-exact against the GPU's own plain greedy decode.
+Stated tolerances: logits within 2e-2 (bf16) / 1e-4 (fp32) of the row's largest |logit| (inf-norm relative,
+teacher-forced on the same tokens); cosine similarities within 1e-3 absolute; token sequences bit-exact against the
+GPU's own plain greedy decode.  Against the oracle with its cache in the model's storage type (as the engine's is)
+the engine is far inside those bars on these shapes (measured 8e-6 bf16, 6e-7 fp32, cosines 1e-6), so the
+assertions use tighter working bounds (TOL, COS_TOL below), which catch regressions the stated bars would hide.
 """
 import numpy as np
 import pytest
@@ -14,8 +16,9 @@ from helpers import SMALL_GQA, make_oracle
 
 pytestmark = pytest.mark.gpu
 
-TOL = {si.DT_F32: 1e-4, si.DT_BF16: 2e-2}
-COS_TOL = 1e-3
+STATED_TOL = {si.DT_F32: 1e-4, si.DT_BF16: 2e-2}
+TOL = {si.DT_F32: 1e-5, si.DT_BF16: 2e-4}
+COS_TOL = 2e-5
 
 # bf16 shape with several tiles per matrix, GQA, head_dim 32, ragged K (d_ffn 208 is not a multiple of 32)
 BF_GQA = SMALL_GQA.with_(name="bf-gqa", dtype=si.DT_BF16)
