@@ -229,7 +229,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
                     const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
                     const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
                     pf[ks][0][w2] = h0 | (h1 << 16);
-                    pf[ks][1][w2] = l0 | (l1 << 16);
+                    if constexpr (NP == 2) pf[ks][1][w2] = l0 | (l1 << 16);
                 }
         } else {
 #pragma unroll
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(64) void pf_attn_kernel(const PfAttnArgs a) {
                     const uint32_t h0 = BF16::from_f32(p0v), h1 = BF16::from_f32(p1v);
                     const uint32_t l0 = BF16::from_f32(p0v - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1v - BF16::to_f32((uint16_t)h1));
                     pf[ks][0][w2] = h0 | (h1 << 16);
-                    pf[ks][1][w2] = l0 | (l1 << 16);
+                    if constexpr (NP == 2) pf[ks][1][w2] = l0 | (l1 << 16);
                 }
         } else {
 #pragma unroll

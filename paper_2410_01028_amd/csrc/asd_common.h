@@ -22,6 +22,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 
+// planes of a bf16 activation (2 = hi + lo; 1 is a build-time experiment: single bf16 activations)
+#ifndef ASD_BF16_PLANES
+#define ASD_BF16_PLANES 2
+#endif
 #define ASD_WAVE 64
 #define ASD_ROWS 16          // rows (MFMA columns) of every forward call
 #define ASD_CHUNK 64         // keys per attention work item; chunk boundaries are absolute positions
@@ -32,7 +36,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 struct BF16 {
     using elem = uint16_t;
     static constexpr int KE = 8;
-    static constexpr int NP = 2;
+    static constexpr int NP = ASD_BF16_PLANES;
     static __device__ __forceinline__ float to_f32(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
     static __device__ __forceinline__ uint16_t from_f32(float f) {
         return __builtin_bit_cast(uint16_t, (__bf16)f);     // round to nearest even
@@ -110,7 +114,7 @@ __device__ __forceinline__ void store_act4(void* base, int64_t plane, int64_t ch
             lo[j] = T::from_f32(v[j] - T::to_f32((uint16_t)hi[j]));
         }
         *(uint2*)p = uint2{hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16)};
-        *(uint2*)(p + plane) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
+        if constexpr (T::NP == 2) *(uint2*)(p + plane) = uint2{lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16)};
     } else {
         *(float4*)p = float4{v[0], v[1], v[2], v[3]};
     }

@@ -322,7 +322,10 @@ template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, i
 // ------------------------------------------------------------------ GEMM dispatch
 template <class T, int EPI, int TN, int NW>
 void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
-    gemm_kernel<T, EPI, TN, NW, 4><<<grid, NW * 64, 0, s>>>(a);
+    if constexpr (T::NP == 2) {          // two-plane activations: passes of at most 8 rows pack both planes into one operand
+        if (a.M <= 8) { gemm_kernel<T, EPI, TN, NW, 4, true><<<grid, NW * 64, 0, s>>>(a); return; }
+    }
+    gemm_kernel<T, EPI, TN, NW, 4, false><<<grid, NW * 64, 0, s>>>(a);
 }
 
 template <class T, int EPI>
@@ -556,7 +559,7 @@ int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, 
                     Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0) {
     std::vector<PassOp> ops;
     build_pass(e, M, pos_off, mask, ctx_for_bytes, ops);
-    if (e->persistent && !profiler) {
+    if (e->persistent && !profiler && (M <= 8 || e->c.dtype != ASD_DT_BF16)) {     // (its bf16 GEMM blocks are the packed, at-most-8-row form)
         std::vector<int> key{M, pos_off, (int)(d_tokens - e->tokbuf)};
         for (int j = 0; j < 2 * e->c.n_layers; ++j) key.push_back(mask ? (mask[j] ? 1 : 0) : 0);
         return launch_persistent(e, ops, key, d_tokens, M, mask, fin_mode, fin_arg);

@@ -68,21 +68,21 @@ struct GemmArgs {
     AmaxPart* amax_part;     // [grid][16] best (logit, index) among this workgroup's features, and their exp-sum
 };
 
-// Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments.
+// Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments
+// (NPL fragments per k-block, xpl apart, each with its own accumulators).
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
 // X points at this lane's fragment of k-block 0 (or is NULL for a lane whose row is unused: zeros); consecutive
 // k-blocks are xstep fragments apart.
-template <class T, int NA, int U, bool COH, class F>
+template <class T, int NA, int NPL, int U, bool COH, class F>
 __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
-                                           int64_t wks, f32x4 (&acc)[NA], F between) {
-    constexpr int NP = T::NP;
-    u32x4 a[U][NA], b[U][NP];
+                                           int64_t wks, f32x4 (&acc)[NPL][NA], F between) {
+    u32x4 a[U][NA], b[U][NPL];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         if (u < n) {
             const size_t o = (size_t)(first + u * step) * ASD_WAVE;
 #pragma unroll
-            for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + u * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
+            for (int pl = 0; pl < NPL; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + u * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
         }
@@ -95,12 +95,12 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
 #pragma unroll
                 for (int s = 0; s < NA; ++s)
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) mma16<T>(acc[s], a[u][s], b[u][pl]);
+                    for (int pl = 0; pl < NPL; ++pl) mma16<T>(acc[pl][s], a[u][s], b[u][pl]);
                 const int nx = i + u + U;
                 if (nx < n) {
                     const size_t o = (size_t)(first + nx * step) * ASD_WAVE;
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + nx * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
+                    for (int pl = 0; pl < NPL; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + nx * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
                     for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
                 }
@@ -112,12 +112,19 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
 // One workgroup's share of the contraction: "virtual block" bid owns tiles bid*TN .. bid*TN+TN-1.  Called once per
 // workgroup by gemm_kernel (bid = blockIdx.x) and in a loop over virtual blocks by the persistent pass kernel
 // (COH = true: every access to data exchanged with other workgroups of the same kernel is coherent).
-template <class T, int EPI, int TN, int NW, int U, bool COH>
+//
+// Two-plane (bf16) activations: the hi and the lo plane are contracted into separate sums, added once at the end.
+// PACK (passes of at most 8 rows): both planes share one operand, rows in columns 0..7 hi and 8..15 lo, so a
+// k-block costs one fragment load and one MFMA; otherwise each plane has its own operand and accumulators.  Either
+// way an output element is (sum over waves of its hi sums) + (sum over waves of its lo sums): the same bits.
+template <class T, int EPI, int TN, int NW, int U, bool COH, bool PACK>
 __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     constexpr int NT = NW * 64;
+    constexpr int NPL = PACK ? 1 : T::NP;               // operands (and accumulator sets) per k-block
+    static_assert(!PACK || T::NP == 2, "packing is for two-plane activations");
     constexpr bool kNormed = (EPI != EPI_RES);          // input went through RMSNorm: needs the row scale
-    __shared__ f32x4 red[NW][NA][64];
+    __shared__ f32x4 red[NW][NPL][NA][64];
     __shared__ float epi_a[(EPI == EPI_RES || EPI == EPI_LM) ? NA * 256 : 1];
     __shared__ float epi_b[EPI == EPI_RES ? NA * 256 : 1];
     __shared__ float fin_a[kNormed ? NT : 1];
@@ -176,14 +183,20 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
         }
     };
 
-    f32x4 acc[NA];
+    f32x4 acc[NPL][NA];
 #pragma unroll
-    for (int s = 0; s < NA; ++s) acc[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const u32x4* Xl = (lane & 15) < a.M ? a.X + (lane >> 4) * a.RS + (lane & 15) : nullptr;
-    stream_mma<T, NA, U, COH>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
+    for (int pl = 0; pl < NPL; ++pl)
+#pragma unroll
+        for (int s = 0; s < NA; ++s) acc[pl][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4* Xl;
+    if constexpr (PACK) Xl = (lane & 7) < a.M ? a.X + ((lane & 8) ? a.x_plane : 0) + (lane >> 4) * a.RS + (lane & 7) : nullptr;
+    else Xl = (lane & 15) < a.M ? a.X + (lane >> 4) * a.RS + (lane & 15) : nullptr;
+    stream_mma<T, NA, NPL, U, COH>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
 
 #pragma unroll
-    for (int s = 0; s < NA; ++s) red[w][s][lane] = acc[s];
+    for (int pl = 0; pl < NPL; ++pl)
+#pragma unroll
+        for (int s = 0; s < NA; ++s) red[w][pl][s][lane] = acc[pl][s];
 
     if constexpr (kNormed) {
         constexpr int J = NT / 16;
@@ -220,7 +233,13 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
         const int src = (nl >> 2) * 16 + m, r = nl & 3;
         float v = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < NW; ++ww) v += red[ww][s][src][r];
+        for (int ww = 0; ww < NW; ++ww) v += red[ww][0][s][src][r];
+        if constexpr (T::NP == 2) {                      // the lo plane's sums: columns m + 8 (packed) or the second set
+            float lo = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) lo += PACK ? red[ww][0][s][src + 8][r] : red[ww][NPL - 1][s][src][r];
+            v += lo;
+        }
         return v;
     };
 
@@ -331,7 +350,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     }
 }
 
-template <class T, int EPI, int TN, int NW, int U>
+template <class T, int EPI, int TN, int NW, int U, bool PACK>
 __global__ __launch_bounds__(NW * 64) void gemm_kernel(const GemmArgs a) {
-    gemm_block<T, EPI, TN, NW, U, false>(a, blockIdx.x);
+    gemm_block<T, EPI, TN, NW, U, false, PACK>(a, blockIdx.x);
 }

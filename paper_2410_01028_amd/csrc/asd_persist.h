@@ -103,17 +103,17 @@ __global__ __launch_bounds__(PASS_THREADS, 4) void pass_kernel(const PassArgs P)
                                          vb % EMBED_SPLIT, vb / EMBED_SPLIT, red);
                 break;
             case OP_QKV:
-                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_QKV, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_QKV, 1, NWV, 4, true, T::NP == 2>(op.g, vb); __syncthreads(); }
                 break;
             case OP_OPROJ:
             case OP_DOWN:
-                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_RES, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_RES, 1, NWV, 4, true, T::NP == 2>(op.g, vb); __syncthreads(); }
                 break;
             case OP_GU:
-                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_GU, 1, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_GU, 1, NWV, 4, true, T::NP == 2>(op.g, vb); __syncthreads(); }
                 break;
             case OP_LM:
-                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_LM, 2, NWV, 4, true>(op.g, vb); __syncthreads(); }
+                for (int vb = wg; vb < op.grid; vb += G) { gemm_block<T, EPI_LM, 2, NWV, 4, true, T::NP == 2>(op.g, vb); __syncthreads(); }
                 break;
             case OP_ATTN: {
                 // two groups of ATT_GW waves per workgroup; every wave makes the same number of trips (the group
