@@ -154,7 +154,7 @@ GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     g.kint = g.kmajor;
     g.NW = 8;     // every class: the persistent pass kernel runs 8-wave workgroups and must reduce in the same order
     (void)KB;
-    static const char* names[] = {"", "qkv", "", "", "o", "gu", "down", "lm"};
+    static const char* names[ASD_K_COUNT] = {"", "qkv", "", "o", "gu", "down", "lm", ""};       // indexed by kernel class
     if (const char* env = getenv("ASD_TUNE")) {
         std::string e(env), key = std::string(names[cls]) + "=";
         size_t pos = (";" + e).find(";" + key);
