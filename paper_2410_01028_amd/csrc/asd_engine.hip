@@ -320,12 +320,15 @@ template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, i
 }
 
 // ------------------------------------------------------------------ GEMM dispatch
+#ifndef ASD_GEMM_U
+#define ASD_GEMM_U 4          // weight fragments in flight per wave and tile
+#endif
 template <class T, int EPI, int TN, int NW>
 void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
     if constexpr (T::NP == 2) {          // two-plane activations: passes of at most 8 rows pack both planes into one operand
-        if (a.M <= 8) { gemm_kernel<T, EPI, TN, NW, 4, true><<<grid, NW * 64, 0, s>>>(a); return; }
+        if (a.M <= 8) { gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, true><<<grid, NW * 64, 0, s>>>(a); return; }
     }
-    gemm_kernel<T, EPI, TN, NW, 4, false><<<grid, NW * 64, 0, s>>>(a);
+    gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, false><<<grid, NW * 64, 0, s>>>(a);
 }
 
 template <class T, int EPI>
