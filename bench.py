@@ -76,6 +76,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras")
     ap.add_argument("--n-new", type=int, default=None, help="override the workload's number of new tokens (profiling runs)")
     ap.add_argument("--copy-only-extra", action="store_true", help="with --no-extras: still run the plain copy kernel (counter calibration)")
+    ap.add_argument("--only-verify-passes", type=int, default=0, metavar="N",
+                    help="counter runs: after the prompt pass launch N eager (draft_len+1)-row verification passes and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -98,6 +100,10 @@ def main():
 
     first, acs, _ = eng.prefill(prompt)          # untimed: first touch of every weight, lazy runtime set-up
     torch.cuda.synchronize()
+    if args.only_verify_passes:
+        ms, by = eng.time_pass(k + 1, None, args.only_verify_passes, False)
+        print(json.dumps({"verify_rows": k + 1, "ms_per_pass": round(ms, 4), "GBps": round(by / ms / 1e6, 1)}), flush=True)
+        return
     pf_prof = eng.profile_prefill(prompt) if (P > 16 and not args.no_extras) else None     # resets the cache: before the timed passes
     t0 = time.time()
     for _ in range(3):
