@@ -146,10 +146,11 @@ bool config_ok(const asd_config* c, std::string* why) {
 // (development aid) overrides, e.g. ASD_TUNE="qkv=1,8,1,1;o=1,16,0,0" (TN, NW, k-major, interleave).
 GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     GemmCfg g{};
-    g.TN = 1;
-    if (epi == EPI_LM) g.TN = 2;
-    if (epi == EPI_GU && tiles > 2048) g.TN = 2;
-    if (epi == EPI_RES && tiles > 1024) g.TN = 2;
+    // One tile per workgroup unless two tiles per workgroup leave the busiest compute unit with no more tiles than
+    // before (256 units; e.g. 320 tiles: 2 either way, and the two-tile workgroups stream better: 13B O / down).
+    const int units = 256;
+    const int max1 = (tiles + units - 1) / units, max2 = ((tiles + 1) / 2 + units - 1) / units * 2;
+    g.TN = (epi == EPI_LM || max2 <= max1) ? 2 : 1;      // (the LM head: two tiles per workgroup at every vocabulary size)
     g.kmajor = (cls == ASD_K_QKV || cls == ASD_K_DOWN || cls == ASD_K_LMHEAD) ? 1 : 0;
     g.kint = g.kmajor;
     g.NW = 8;     // every class: the persistent pass kernel runs 8-wave workgroups and must reduce in the same order
