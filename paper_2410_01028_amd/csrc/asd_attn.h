@@ -305,6 +305,18 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
     attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
 }
 
+// The same kernel with the register allocation held to four waves per SIMD (128 registers instead of ~220): a wave
+// then no longer keeps all of a chunk's K and V^T fragments in flight at once, but every group of a long context is
+// resident at once (one round of workgroups instead of two).  Same arithmetic, same bits; chosen by the grid size.
+template <class T, int H>
+__global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(const AttnArgs a) {
+    __shared__ float so[ATT_GW * ATT_RH * H];
+    __shared__ float sml[ATT_GW * ASD_ROWS * 2];
+    __shared__ unsigned s_old;
+    if ((int)blockIdx.x * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
+    attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
+}
+
 // ---------------------------------------------------------------- prompt blocks: causal attention, one wave per 16 query rows
 // Rows 16c .. 16c+15 of a prompt block (cache positions pos0 + 16c ..) of one query head against all keys up to
 // their own positions: the wave walks the 64-key chunks in ascending order with a running maximum and sum per row

@@ -96,6 +96,7 @@ struct asd_engine {
     unsigned long long bar_count;
     int32_t* bar_err;
     std::vector<uint8_t> graph_mask;
+    bool force_att_w4;                  // ASD_ATT_W4 (development / test aid): always launch the four-waves-per-SIMD attention variant
     float graph_T;
     uint64_t graph_seed;
     std::string err;
@@ -350,9 +351,15 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
 template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc) {
     const int H = e->c.head_dim;
     const dim3 gp((nc + ATT_GW - 1) / ATT_GW, e->c.n_heads);
-    if (H == 32) attn_kernel<T, 32><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
-    if (H == 64) attn_kernel<T, 64><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
-    if (H == 128) attn_kernel<T, 128><<<gp, ATT_GW * 64, 0, e->stream>>>(a);
+    // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
+    const bool many = (long)gp.x * gp.y > 512 || e->force_att_w4;
+#define ATT(h)                                                                          \
+    if (H == h) {                                                                       \
+        if (many) attn_kernel_w4<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);           \
+        else attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                   \
+    }
+    ATT(32) ATT(64) ATT(128)
+#undef ATT
 }
 void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
     if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
@@ -815,7 +822,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
-    e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
+    e->force_att_w4 = getenv("ASD_ATT_W4") != nullptr; e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
     // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
     e->persistent = false; e->pass_grid = 0;
     {

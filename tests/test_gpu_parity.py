@@ -350,3 +350,24 @@ def test_degenerate_sizes():
     assert eng.kv_len == cap
     o = make_oracle(s, seed=1, max_seq=cap, kv_storage=True).forward(si.prompt(3, cap, s.vocab), 0)
     assert np.abs(acs - o["cos"]).max() < COS_TOL
+
+
+def test_attention_register_variants_give_the_same_bits(monkeypatch):
+    """Long contexts launch the attention kernel compiled for four waves per SIMD; short ones the one that keeps a
+    whole chunk in flight per wave.  Same arithmetic: forcing the former everywhere must not change a bit."""
+    shape = MID16
+    toks = si.prompt(4, 700, shape.vocab)
+    outs = []
+    for force in (False, True):
+        if force:
+            monkeypatch.setenv("ASD_ATT_W4", "1")
+        else:
+            monkeypatch.delenv("ASD_ATT_W4", raising=False)
+        eng = asd.Engine(asd.make_config(shape, 768)).init_synthetic(2)
+        eng.prefill(toks[:690])
+        a = eng.forward(toks[690:695], 690)
+        b = eng.forward(toks[695:696], 695)
+        outs.append((a["logits"], a["cos_rows"], b["logits"]))
+        eng.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
