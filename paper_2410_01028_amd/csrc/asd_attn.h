@@ -50,6 +50,7 @@ struct AttnArgs {
     int32_t pos_off, M, RS;   // rows in use, row stride of the activation buffers
     int32_t n_h, n_kv, h, page_tokens;
     int32_t nc_stride;        // groups per head in the partial buffers
+    int32_t grid_groups;      // groups per head the launch covers (per-step kernels: see attn_unit)
     float scale;              // 1/sqrt(h)
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
@@ -296,13 +297,30 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     __syncthreads();
 }
 
+// Workgroup -> (group, head) of the per-step kernels.  Workgroups are handed to the 8 XCDs round robin by index, and
+// each XCD has its own L2: the query heads that share a KV head (grouped-query attention) read the same K/V, so the
+// workgroups of one (KV head, group) pair get consecutive slots of ONE XCD and its K/V crosses the fabric once instead
+// of once per query head; successive pairs go to successive XCDs.  With one query head per KV head this is the plain
+// order (group fastest).  Returns false for the padding workgroups of the last round.
+__device__ __forceinline__ bool attn_unit(const AttnArgs& a, int* grp, int* head) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, G = a.n_h / a.n_kv;
+    const int pair = (slot / G) * 8 + xcd;
+    if (pair >= a.n_kv * a.grid_groups) return false;
+    *grp = pair % a.grid_groups;
+    *head = (pair / a.grid_groups) * G + slot % G;
+    return true;
+}
+__host__ __device__ inline int attn_grid(int n_h, int n_kv, int groups) { return (n_kv * groups + 7) / 8 * 8 * (n_h / n_kv); }
+
 template <class T, int H>
 __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
-    if ((int)blockIdx.x * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;       // no row of this call sees this group
-    attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
+    int grp, head;
+    if (!attn_unit(a, &grp, &head)) return;
+    if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;       // no row of this call sees this group
+    attn_group<T, H, false>(a, grp, head, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
 }
 
 // The same kernel with the register allocation held to four waves per SIMD (128 registers instead of ~220): a wave
@@ -313,8 +331,10 @@ __global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(const AttnArgs 
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
-    if ((int)blockIdx.x * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
-    attn_group<T, H, false>(a, blockIdx.x, blockIdx.y, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
+    int grp, head;
+    if (!attn_unit(a, &grp, &head)) return;
+    if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
+    attn_group<T, H, false>(a, grp, head, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
 }
 
 // ---------------------------------------------------------------- prompt blocks: causal attention, one wave per 16 query rows

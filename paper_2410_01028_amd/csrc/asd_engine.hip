@@ -348,15 +348,17 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
     return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
 }
 
-template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a, int nc) {
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc) {
     const int H = e->c.head_dim;
-    const dim3 gp((nc + ATT_GW - 1) / ATT_GW, e->c.n_heads);
+    AttnArgs a = a0;
+    a.grid_groups = (nc + ATT_GW - 1) / ATT_GW;
+    const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups);
     // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
-    const bool many = (long)gp.x * gp.y > 512 || e->force_att_w4;
+    const bool many = (long)a.grid_groups * e->c.n_heads > 512 || e->force_att_w4;
 #define ATT(h)                                                                          \
     if (H == h) {                                                                       \
-        if (many) attn_kernel_w4<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);           \
-        else attn_kernel<T, h><<<gp, ATT_GW * 64, 0, e->stream>>>(a);                   \
+        if (many) attn_kernel_w4<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);         \
+        else attn_kernel<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);                 \
     }
     ATT(32) ATT(64) ATT(128)
 #undef ATT
