@@ -51,6 +51,7 @@ struct AttnArgs {
     int32_t n_h, n_kv, h, page_tokens;
     int32_t nc_stride;        // groups per head in the partial buffers
     int32_t grid_groups;      // groups per head the launch covers (per-step kernels: see attn_unit)
+    int32_t gh;               // query heads of one KV head a workgroup handles at once (a power of two, gh * RS <= 16)
     float scale;              // 1/sqrt(h)
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
@@ -65,19 +66,22 @@ template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
 }
 template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 
-// Merge the group partials of rows m0 .. m0+ATT_RB-1 (those below a.M) of one head, in ascending chunk order, and
-// write the normalised output: chunk statistics with one chunk per lane, outputs with two head dims per lane; all
+// Merge the group partials of ATT_RB (head, row) pairs, in ascending chunk order, and write the normalised output.
+// Pair p of the n_pairs pairs of a workgroup's heads is head head0 + p / M, row p % M; this call takes pairs
+// p0 .. p0 + ATT_RB - 1.  Chunk statistics with one chunk per lane, outputs with two head dims per lane; all
 // loads of a round are requested before any is used.  One wave.
 template <class T, int H, bool COH>
-__device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int m0, int pos0, int lane) {
+__device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, int p0, int n_pairs, int pos0, int lane) {
     const bool mine = 2 * lane < H;
     {
         float2 st[ATT_RB][ATT_NCL], v[ATT_RB][ATT_CB];
-        int nc[ATT_RB];
+        int nc[ATT_RB], hd[ATT_RB], row[ATT_RB];
 #pragma unroll
         for (int rb = 0; rb < ATT_RB; ++rb) {
-            const int mm = m0 + rb;
-            nc[rb] = mm < a.M ? (pos0 + mm) / ATT_GROUP + 1 : 0;
+            const int pp = p0 + rb < n_pairs ? p0 + rb : p0;        // an inactive slot aliases the first pair and loads nothing
+            hd[rb] = head0 + pp / a.M; row[rb] = pp % a.M;
+            const int head = hd[rb], mm = row[rb];
+            nc[rb] = p0 + rb < n_pairs ? (pos0 + mm) / ATT_GROUP + 1 : 0;
             const float* ml = a.ml_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * 2;
             const float* opm = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * H + 2 * lane;
 #pragma unroll
@@ -91,8 +95,8 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int
         }
 #pragma unroll
         for (int rb = 0; rb < ATT_RB; ++rb) {
-            const int mm = m0 + rb;
-            if (mm >= a.M) break;
+            if (p0 + rb >= n_pairs) break;
+            const int head = hd[rb], mm = row[rb];
             float gmax = -INFINITY;
 #pragma unroll
             for (int q = 0; q < ATT_NCL; ++q) gmax = fmaxf(gmax, st[rb][q].x);
@@ -135,7 +139,10 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head, int
     }
 }
 
-// One group (ATT_GW waves) of one query head.  Every thread of the calling workgroup must call this the same
+// One group (ATT_GW waves) of a.gh consecutive query heads that share a KV head, first head `head`: the 16 columns of
+// the matrix-core products are (head, row) pairs, column j * RS + row for the j-th head (a.gh = 1: the rows of one
+// head).  A column's arithmetic does not depend on what the other columns hold, so the result is the same bits for
+// every gh.  Every thread of the calling workgroup must call this the same
 // number of times (it synchronises the workgroup); `valid` = false makes the group a no-op, hw is the wave's
 // index inside its group.  so: [ATT_GW][ATT_RH][H] floats, sml: [ATT_GW][16][2] floats, s_old: 1 word, per group.
 template <class T, int H, bool COH>
@@ -148,6 +155,9 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     constexpr int KST = 64 / (4 * KE);          // fragment steps over the 64 keys (2 bf16, 4 fp32)
     constexpr int NP = T::NP;
     const int g = lane >> 4, m = lane & 15, r = lane & 15;
+    const int cj = m / a.RS, cm = m % a.RS;                 // this lane's column: head head + cj, row cm
+    const bool col_ok = cj < a.gh && cm < a.M;
+    const int n_cols = (a.gh - 1) * a.RS + a.M;             // columns in use: 0 .. n_cols-1 (those with cm >= M are holes)
     const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
     const int n_groups = last / ATT_GROUP + 1;
     const int c = grp * ATT_GW + hw;
@@ -163,7 +173,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
         const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
         const E* Vp = Kp + (size_t)PT * H;
-        const E* qp = (const E*)a.q + (size_t)head * H * a.RS;
+        const E* qp = (const E*)a.q + (size_t)(head + (col_ok ? cj : 0)) * H * a.RS;
 
         // ---- scores: 4 tiles of 16 keys
         u32x4 qf[HS][NP];
@@ -171,8 +181,8 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
-                qf[hs][pl] = m < a.M ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + m) * KE))
-                                     : u32x4{0u, 0u, 0u, 0u};
+                qf[hs][pl] = col_ok ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + cm) * KE))
+                                    : u32x4{0u, 0u, 0u, 0u};
         f32x4 s[4];
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) {
@@ -195,7 +205,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
                     (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
 
         // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
-        const int row_pos = pos0 + m;
+        const int row_pos = pos0 + cm;
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
@@ -247,32 +257,32 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     }
     if (g == 0) { sml[(hw * ASD_ROWS + m) * 2] = mx; sml[(hw * ASD_ROWS + m) * 2 + 1] = l; }
 
-    // ---- merge the group's chunks through LDS, ATT_RH rows per pass, ascending chunk order
-    for (int m0 = 0; m0 < a.M; m0 += ATT_RH) {
+    // ---- merge the group's chunks through LDS, ATT_RH columns per pass, ascending chunk order
+    for (int m0 = 0; m0 < n_cols; m0 += ATT_RH) {
         if (m >= m0 && m < m0 + ATT_RH) {
 #pragma unroll
             for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[((size_t)hw * ATT_RH + (m - m0)) * H + ht * 16 + 4 * g] = o[ht];
         }
         __syncthreads();
         for (int idx = hw * 64 + lane; idx < ATT_RH * H; idx += ATT_GW * 64) {
-            const int rr = idx / H, hd = idx % H, mm = m0 + rr;
-            if (!valid || mm >= a.M) continue;
+            const int rr = idx / H, hd = idx % H, col = m0 + rr, mm = col % a.RS, hh = head + col / a.RS;
+            if (!valid || col >= n_cols || mm >= a.M) continue;
             float gmax = -INFINITY;
 #pragma unroll
-            for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + mm) * 2]);
+            for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + col) * 2]);
             float L = 0.f, acc = 0.f;
             if (gmax != -INFINITY) {
 #pragma unroll
                 for (int ww = 0; ww < ATT_GW; ++ww) {          // a chunk the row does not see has max -inf: weight 0
-                    const float wgt = __expf(sml[(ww * ASD_ROWS + mm) * 2] - gmax);
-                    L += sml[(ww * ASD_ROWS + mm) * 2 + 1] * wgt;
+                    const float wgt = __expf(sml[(ww * ASD_ROWS + col) * 2] - gmax);
+                    L += sml[(ww * ASD_ROWS + col) * 2 + 1] * wgt;
                     acc += so[((size_t)ww * ATT_RH + rr) * H + hd] * wgt;
                 }
             }
             if (n_groups == 1) {
-                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + hd, mm, acc / L);
+                store_act<T, COH>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
             } else {
-                const size_t row = ((size_t)head * a.nc_stride + grp) * ASD_ROWS + mm;
+                const size_t row = ((size_t)hh * a.nc_stride + grp) * ASD_ROWS + mm;
                 coherent_store(a.o_part + row * H + hd, acc);
                 if (hd == 0) { coherent_store(a.ml_part + row * 2, gmax); coherent_store(a.ml_part + row * 2 + 1, L); }
             }
@@ -289,28 +299,29 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         *s_old = valid ? __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xffffffffu;
     }
     __syncthreads();
-    if ((int)*s_old == n_groups - 1) {                // the group's waves share the rows, ATT_RB rows per wave and trip
+    if ((int)*s_old == n_groups - 1) {                // the group's waves share the (head, row) pairs, ATT_RB per wave and trip
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         if (hw == 0 && lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        for (int m0 = hw * ATT_RB; m0 < a.M; m0 += ATT_GW * ATT_RB) attn_merge_rows<T, H, COH>(a, head, m0, pos0, lane);
+        const int n_pairs = a.gh * a.M;
+        for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H, COH>(a, head, p0, n_pairs, pos0, lane);
     }
     __syncthreads();
 }
 
-// Workgroup -> (group, head) of the per-step kernels.  Workgroups are handed to the 8 XCDs round robin by index, and
+// Workgroup -> (group, first head) of the per-step kernels.  Workgroups are handed to the 8 XCDs round robin by index, and
 // each XCD has its own L2: the query heads that share a KV head (grouped-query attention) read the same K/V, so the
 // workgroups of one (KV head, group) pair get consecutive slots of ONE XCD and its K/V crosses the fabric once instead
 // of once per query head; successive pairs go to successive XCDs.  With one query head per KV head this is the plain
 // order (group fastest).  Returns false for the padding workgroups of the last round.
 __device__ __forceinline__ bool attn_unit(const AttnArgs& a, int* grp, int* head) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, G = a.n_h / a.n_kv;
-    const int pair = (slot / G) * 8 + xcd;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, G = a.n_h / a.n_kv, U = G / a.gh;   // U workgroups per pair
+    const int pair = (slot / U) * 8 + xcd;
     if (pair >= a.n_kv * a.grid_groups) return false;
     *grp = pair % a.grid_groups;
-    *head = (pair / a.grid_groups) * G + slot % G;
+    *head = (pair / a.grid_groups) * G + (slot % U) * a.gh;
     return true;
 }
-__host__ __device__ inline int attn_grid(int n_h, int n_kv, int groups) { return (n_kv * groups + 7) / 8 * 8 * (n_h / n_kv); }
+__host__ __device__ inline int attn_grid(int n_h, int n_kv, int groups, int gh) { return (n_kv * groups + 7) / 8 * 8 * (n_h / n_kv / gh); }
 
 template <class T, int H>
 __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {

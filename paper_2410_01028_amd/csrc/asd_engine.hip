@@ -96,6 +96,7 @@ struct asd_engine {
     unsigned long long bar_count;
     int32_t* bar_err;
     std::vector<uint8_t> graph_mask;
+    bool att_gh1;                       // ASD_ATT_GH1 (test aid): one query head per attention workgroup also for grouped-query models
     bool force_att_w4;                  // ASD_ATT_W4 (development / test aid): always launch the four-waves-per-SIMD attention variant
     float graph_T;
     uint64_t graph_seed;
@@ -352,9 +353,12 @@ template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc)
     const int H = e->c.head_dim;
     AttnArgs a = a0;
     a.grid_groups = (nc + ATT_GW - 1) / ATT_GW;
-    const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups);
+    // grouped-query models: as many query heads of a KV head per workgroup as the 16 columns hold beside the rows
+    a.gh = 1;
+    if (!e->att_gh1) while (a.gh * 2 * a.RS <= ASD_ROWS && a.gh * 2 <= e->c.n_heads / e->c.n_kv_heads && (e->c.n_heads / e->c.n_kv_heads) % (a.gh * 2) == 0) a.gh *= 2;
+    const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups, a.gh);
     // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
-    const bool many = (long)a.grid_groups * e->c.n_heads > 512 || e->force_att_w4;
+    const bool many = (long)a.grid_groups * (e->c.n_heads / a.gh) > 512 || e->force_att_w4;
 #define ATT(h)                                                                          \
     if (H == h) {                                                                       \
         if (many) attn_kernel_w4<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);         \
@@ -459,7 +463,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
             t.q = e->q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
             t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
-            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
+            t.nc_stride = e->nc_stride; t.gh = 1; t.scale = 1.f / sqrtf((float)c.head_dim);
             t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
             push(OP_ATTN, ASD_K_ATTN, 0, cls_bytes[ASD_K_ATTN] / L).t = t;
 
@@ -824,6 +828,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
+    e->att_gh1 = getenv("ASD_ATT_GH1") != nullptr;
     e->force_att_w4 = getenv("ASD_ATT_W4") != nullptr; e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
     // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
     e->persistent = false; e->pass_grid = 0;

@@ -371,3 +371,40 @@ def test_attention_register_variants_give_the_same_bits(monkeypatch):
         eng.close()
     for x, y in zip(*outs):
         assert np.array_equal(x, y)
+
+
+GQA8 = si.Shape("gqa8", 2, 256, 16, 2, 64, 688, 1024, si.DT_BF16, 40, 12, 4)
+
+
+@pytest.mark.parametrize("shape", [BF_GQA, MID16, GQA8, SMALL_GQA], ids=lambda s: s.name)
+def test_query_heads_per_attention_workgroup_give_the_same_bits(shape, monkeypatch):
+    """Grouped-query models: a decode-attention workgroup takes as many query heads of a KV head as fit the 16
+    matrix-core columns beside the rows of the pass (8 heads for 1-2 rows ... 1 head for 9-16 rows).  Columns are
+    independent, so one head per workgroup must give the same bits, for short contexts (one 256-key group) and
+    contexts of several groups alike."""
+    toks = si.prompt(6, 700, shape.vocab)
+    outs = []
+    for single in (False, True):
+        if single:
+            monkeypatch.setenv("ASD_ATT_GH1", "1")
+        else:
+            monkeypatch.delenv("ASD_ATT_GH1", raising=False)
+        eng = asd.Engine(asd.make_config(shape, 768)).init_synthetic(5)
+        got = []
+        pos = 0
+        for M in (1, 2, 3, 4, 5, 8, 9, 16, 1):                 # one group per head
+            r = eng.forward(toks[pos:pos + M], pos)
+            got += [r["logits"], r["cos_rows"]]
+            pos += M
+        eng.prefill(toks[:600])                                # three groups per head
+        pos = 600
+        for M in (1, 2, 4, 7, 16, 1):
+            r = eng.forward(toks[pos:pos + M], pos)
+            got += [r["logits"], r["cos_rows"]]
+            pos += M
+        out, st, mask = eng.decode(int(toks[pos]), 24, 4, alpha=0.9, m=2, n=1)
+        got.append(out)
+        outs.append(got)
+        eng.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
