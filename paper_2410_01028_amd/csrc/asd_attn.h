@@ -139,6 +139,95 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, in
     }
 }
 
+// ---- pieces of one chunk's work, shared by the kernels below
+// causal mask, chunk max, exponentials, chunk sum of one column (lane group g holds keys 4g..4g+3 of each score tile)
+template <class T>
+__device__ __forceinline__ void att_softmax(f32x4 (&s)[4], int c, int row_pos, float scale, int g, float& mx, float& l) {
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
+            const float v = (key <= row_pos) ? s[kt][j] * scale : -INFINITY;
+            s[kt][j] = v;
+            mx = fmaxf(mx, v);
+        }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
+            s[kt][j] = p;
+            l += p;
+        }
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+}
+// the probabilities as B fragments of the output product (hi + lo planes for bf16)
+template <class T>
+__device__ __forceinline__ void att_pfrags(const f32x4 (&s)[4], u32x4 (&pf)[64 / (4 * T::KE)][T::NP]) {
+    constexpr int KE = T::KE, KST = 64 / (4 * KE), NP = T::NP;
+    if constexpr (KE == 8) {
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) {
+                const f32x4& t = s[2 * ks + (w2 >> 1)];
+                const float p0 = t[(w2 & 1) * 2], p1 = t[(w2 & 1) * 2 + 1];
+                const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
+                const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
+                pf[ks][0][w2] = h0 | (h1 << 16);
+                if constexpr (NP == 2) pf[ks][1][w2] = l0 | (l1 << 16);
+            }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
+    }
+}
+// Merge a group's chunks through LDS, ATT_RH columns per pass, ascending chunk order; the result goes to the output
+// (a context of one group) or to the group's partial.  Synchronises the workgroup; the chunk statistics are in sml.
+template <class T, int H, bool COH>
+__device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int head, bool valid, int n_groups, int n_cols, int hw, int lane,
+                                                const f32x4 (&o)[H / 16], float* so, const float* sml) {
+    constexpr int HT = H / 16;
+    const int g = lane >> 4, m = lane & 15;
+    for (int m0 = 0; m0 < n_cols; m0 += ATT_RH) {
+        if (m >= m0 && m < m0 + ATT_RH) {
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[((size_t)hw * ATT_RH + (m - m0)) * H + ht * 16 + 4 * g] = o[ht];
+        }
+        __syncthreads();
+        for (int idx = hw * 64 + lane; idx < ATT_RH * H; idx += ATT_GW * 64) {
+            const int rr = idx / H, hd = idx % H, col = m0 + rr, mm = col % a.RS, hh = head + col / a.RS;
+            if (!valid || col >= n_cols || mm >= a.M) continue;
+            float gmax = -INFINITY;
+#pragma unroll
+            for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + col) * 2]);
+            float L = 0.f, acc = 0.f;
+            if (gmax != -INFINITY) {
+#pragma unroll
+                for (int ww = 0; ww < ATT_GW; ++ww) {          // a chunk the row does not see has max -inf: weight 0
+                    const float wgt = __expf(sml[(ww * ASD_ROWS + col) * 2] - gmax);
+                    L += sml[(ww * ASD_ROWS + col) * 2 + 1] * wgt;
+                    acc += so[((size_t)ww * ATT_RH + rr) * H + hd] * wgt;
+                }
+            }
+            if (n_groups == 1) {
+                store_act<T, COH>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
+            } else {
+                const size_t row = ((size_t)hh * a.nc_stride + grp) * ASD_ROWS + mm;
+                coherent_store(a.o_part + row * H + hd, acc);
+                if (hd == 0) { coherent_store(a.ml_part + row * 2, gmax); coherent_store(a.ml_part + row * 2 + 1, L); }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // One group (ATT_GW waves) of a.gh consecutive query heads that share a KV head, first head `head`: the 16 columns of
 // the matrix-core products are (head, row) pairs, column j * RS + row for the j-th head (a.gh = 1: the rows of one
 // head).  A column's arithmetic does not depend on what the other columns hold, so the result is the same bits for
@@ -204,50 +293,12 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
                 vf[ht][ks] = __builtin_nontemporal_load(
                     (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
 
-        // ---- causal mask, chunk max, exponentials, chunk sum (per row = per column m)
-        const int row_pos = pos0 + cm;
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = c * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
-                const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
-                s[kt][j] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mx);
-                s[kt][j] = p;
-                l += p;
-            }
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        // ---- causal mask, chunk max, exponentials, chunk sum (per column)
+        att_softmax<T>(s, c, pos0 + cm, a.scale, g, mx, l);
 
         // ---- output: O[dim][row] += V^T[dim][keys] * P[keys][row]; P goes in as hi + lo planes for bf16
         u32x4 pf[KST][NP];
-        if constexpr (KE == 8) {
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-                for (int w2 = 0; w2 < 4; ++w2) {
-                    const f32x4& t = s[2 * ks + (w2 >> 1)];
-                    const float p0 = t[(w2 & 1) * 2], p1 = t[(w2 & 1) * 2 + 1];
-                    const uint32_t h0 = BF16::from_f32(p0), h1 = BF16::from_f32(p1);
-                    const uint32_t l0 = BF16::from_f32(p0 - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1 - BF16::to_f32((uint16_t)h1));
-                    pf[ks][0][w2] = h0 | (h1 << 16);
-                    if constexpr (NP == 2) pf[ks][1][w2] = l0 | (l1 << 16);
-                }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
-        }
+        att_pfrags<T>(s, pf);
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
@@ -257,38 +308,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     }
     if (g == 0) { sml[(hw * ASD_ROWS + m) * 2] = mx; sml[(hw * ASD_ROWS + m) * 2 + 1] = l; }
 
-    // ---- merge the group's chunks through LDS, ATT_RH columns per pass, ascending chunk order
-    for (int m0 = 0; m0 < n_cols; m0 += ATT_RH) {
-        if (m >= m0 && m < m0 + ATT_RH) {
-#pragma unroll
-            for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[((size_t)hw * ATT_RH + (m - m0)) * H + ht * 16 + 4 * g] = o[ht];
-        }
-        __syncthreads();
-        for (int idx = hw * 64 + lane; idx < ATT_RH * H; idx += ATT_GW * 64) {
-            const int rr = idx / H, hd = idx % H, col = m0 + rr, mm = col % a.RS, hh = head + col / a.RS;
-            if (!valid || col >= n_cols || mm >= a.M) continue;
-            float gmax = -INFINITY;
-#pragma unroll
-            for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + col) * 2]);
-            float L = 0.f, acc = 0.f;
-            if (gmax != -INFINITY) {
-#pragma unroll
-                for (int ww = 0; ww < ATT_GW; ++ww) {          // a chunk the row does not see has max -inf: weight 0
-                    const float wgt = __expf(sml[(ww * ASD_ROWS + col) * 2] - gmax);
-                    L += sml[(ww * ASD_ROWS + col) * 2 + 1] * wgt;
-                    acc += so[((size_t)ww * ATT_RH + rr) * H + hd] * wgt;
-                }
-            }
-            if (n_groups == 1) {
-                store_act<T, COH>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
-            } else {
-                const size_t row = ((size_t)hh * a.nc_stride + grp) * ASD_ROWS + mm;
-                coherent_store(a.o_part + row * H + hd, acc);
-                if (hd == 0) { coherent_store(a.ml_part + row * 2, gmax); coherent_store(a.ml_part + row * 2 + 1, L); }
-            }
-        }
-        __syncthreads();
-    }
+    att_group_merge<T, H, COH>(a, grp, head, valid, n_groups, n_cols, hw, lane, o, so, sml);
     if (n_groups == 1) return;
 
     // ---- arrival: the group that completes the head's last outstanding group merges the groups

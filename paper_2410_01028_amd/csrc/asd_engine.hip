@@ -356,9 +356,10 @@ template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc)
     // grouped-query models: as many query heads of a KV head per workgroup as the 16 columns hold beside the rows
     a.gh = 1;
     if (!e->att_gh1) while (a.gh * 2 * a.RS <= ASD_ROWS && a.gh * 2 <= e->c.n_heads / e->c.n_kv_heads && (e->c.n_heads / e->c.n_kv_heads) % (a.gh * 2) == 0) a.gh *= 2;
+    const int units = e->c.n_heads / a.gh;                    // workgroups per group index
     const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups, a.gh);
     // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
-    const bool many = (long)a.grid_groups * (e->c.n_heads / a.gh) > 512 || e->force_att_w4;
+    const bool many = (long)a.grid_groups * units > 512 || e->force_att_w4;
 #define ATT(h)                                                                          \
     if (H == h) {                                                                       \
         if (many) attn_kernel_w4<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);         \
