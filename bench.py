@@ -65,6 +65,11 @@ def read_traffic(path):
     return None
 
 
+def progress(msg):
+    """One line on stderr per finished phase: long workloads stay visibly alive; stdout carries only the JSON line."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -98,8 +103,10 @@ def main():
     prompt = si.prompt(seed, P, shape.vocab)
     L2 = 2 * shape.n_layers
 
+    progress(f"{shape.name}: weights ready")
     first, acs, _ = eng.prefill(prompt)          # untimed: first touch of every weight, lazy runtime set-up
     torch.cuda.synchronize()
+    progress("first prompt pass done")
     if args.only_verify_passes:
         ms, by = eng.time_pass(k + 1, None, args.only_verify_passes, False)
         print(json.dumps({"verify_rows": k + 1, "ms_per_pass": round(ms, 4), "GBps": round(by / ms / 1e6, 1)}), flush=True)
@@ -115,12 +122,15 @@ def main():
         eng.truncate(P)
         return eng.decode(first, N - 1, draft_len, **kw)
 
+    progress(f"prompt pass timed: {t_prefill * 1e3:.1f} ms")
     for _ in range(args.warmup):
         decode_step(0)
+        progress("warm-up decode done")
     torch.cuda.synchronize()
     t0 = time.time()
-    for _ in range(args.steps):
+    for i in range(args.steps):
         plain, st_plain, _ = decode_step(0)
+        progress(f"timed decode {i + 1}/{args.steps} done")
     torch.cuda.synchronize()
     total = time.time() - t0
     ms_per_step = total / args.steps * 1e3
@@ -203,6 +213,7 @@ def main():
         }
         cp = eng.copy_bench(192 << 20, 10)
         out["copy_kernel_GBps"] = round(2 * (192 << 20) / cp / 1e6, 1)
+        progress("per-pass timings done")
         spec = {}
         # Table 2's setting for Llama-2-7B; a cosine-only setting (no periodic rule) with the threshold moved to where
         # this random-init model's ACS values lie; and the all-keep bracket (every draft accepted, no layer skipped)
@@ -218,6 +229,7 @@ def main():
             kk = kw.pop("kmax", k)
             decode_step(kk, **kw)
             torch.cuda.synchronize()
+            progress(f"speculative {name}: warm-up done")
             t0 = time.time()
             toks, st, used = decode_step(kk, **kw)
             dt = time.time() - t0
@@ -225,6 +237,7 @@ def main():
                           "cycles": st["cycles"], "drafted": st["drafted"], "accepted": st["accepted"],
                           "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()), "mask_changes": st["mask_changes"],
                           "tokens_equal_plain": bool(np.array_equal(toks, plain))}
+            progress(f"speculative {name}: {spec[name]['tokens_per_s']} tokens/s")
         out["speculative"] = spec
         # sampled decoding at the paper's higher temperature: plain sampling of the full model against speculative sampling
         samp = {}
@@ -238,6 +251,7 @@ def main():
             dt = time.time() - t0
             samp[name] = {"tokens_per_s": round((N - 1) / dt, 2), "cycles": st["cycles"], "drafted": st["drafted"],
                           "accepted": st["accepted"], "removed_attn": int(used[0::2].sum())}
+            progress(f"sampled {name}: {samp[name]['tokens_per_s']} tokens/s")
         samp["speedup"] = round(samp["admg_a0.9999_m0_n0_T0.6"]["tokens_per_s"] / samp["plain_T0.6"]["tokens_per_s"], 3)
         out["sampled"] = samp
 
@@ -246,6 +260,7 @@ def main():
     torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
+        progress("GPU part done; timing the CPU oracle")
         if shape.name == "tiny":
             out["cpu_baseline"] = cpu_baseline(shape, seed, 8, 24)
         else:
