@@ -21,6 +21,7 @@
 //   registers are exactly the B fragment whose keys match a contiguous V^T load.
 #pragma once
 #include "asd_common.h"
+#include <type_traits>
 
 #define ATT_GW 4                           // waves (chunks) per group
 #define ATT_GROUP (ATT_GW * ASD_CHUNK)     // keys per group
@@ -368,13 +369,10 @@ __global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(const AttnArgs 
     attn_group<T, H, false>(a, grp, head, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
 }
 
-// ---------------------------------------------------------------- prompt blocks: causal attention, one wave per 16 query rows
-// Rows 16c .. 16c+15 of a prompt block (cache positions pos0 + 16c ..) of one query head against all keys up to
-// their own positions: the wave walks the 64-key chunks in ascending order with a running maximum and sum per row
-// (the output accumulator is rescaled when the maximum grows), so nothing is exchanged between waves and the
-// result has one fixed order.  Same fragments and key order as the decode kernel above; the next chunk's K and
-// V^T fragments are requested before the current chunk's softmax and output product.  Workgroups are numbered
-// longest row block first.
+// ---------------------------------------------------------------- prompt blocks: causal attention
+// 16 * PF_ATT_NT query rows of a prompt block (cache positions pos0 + ...) of one query head against all keys up to
+// their own positions.  Same fragments and key order as the decode kernel above.  Workgroups are numbered longest
+// row block first.
 struct PfAttnArgs {
     const void* q;            // [chunk][n_h*h/KE][16][KE], planes q_plane elements apart, chunks q_chunk apart
     void* out;                // same layout
@@ -386,130 +384,179 @@ struct PfAttnArgs {
     float scale;
 };
 
+#ifndef PF_ATT_NT
+#define PF_ATT_NT 2            // 16-row chunks of query rows per workgroup of pf_attn_kernel
+#endif
+// A workgroup takes 32 query rows (two 16-row chunks) and splits the keys over its four waves: wave w walks the
+// 64-key chunks w, w + 4, ... with a running maximum and sum per row (the output accumulator is rescaled when the
+// maximum grows), and the four partial results are merged through LDS in wave order at the end, so the result has
+// one fixed order.  A chunk's K and V^T fragments are loaded once per 32 query rows and feed two column tiles of
+// matrix-core work (with one tile per load the loads, not the products, fill the time: 1.8x slower at 8K context);
+// the next chunk's K fragments are requested as soon as the score products have consumed the current ones, the
+// next V^T fragments right after the output products, into the same registers (the scheduler is fenced at those
+// points: without the fences, or with three column tiles, the kernel is slower).  Needs a SIMD's whole register
+// file per wave.
 template <class T, int H>
-__global__ __launch_bounds__(64) void pf_attn_kernel(const PfAttnArgs a) {
+__global__ __launch_bounds__(256, 1) void pf_attn_kernel(const PfAttnArgs a) {
     using E = typename T::elem;
-    constexpr int KE = T::KE, HS = H / (4 * KE), HT = H / 16, KST = 64 / (4 * KE), NP = T::NP;
-    const int lane = threadIdx.x, g = lane >> 4, m = lane & 15, r = lane & 15;
-    const int n_chunks = (a.rows + 15) / 16;
-    const int c = n_chunks - 1 - (int)blockIdx.x, head = blockIdx.y;
-    const int M = min(16, a.rows - 16 * c);
-    const int p0 = a.pos0 + 16 * c, last = p0 + M - 1, row_pos = p0 + m;
+    constexpr int KE = T::KE, HS = H / (4 * KE), HT = H / 16, KST = 64 / (4 * KE), NP = T::NP, NT = PF_ATT_NT, NWV = 4;
+    __shared__ float so[NWV][16][H];
+    __shared__ float sml[NWV][NT][16][2];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, m = lane & 15, r = lane & 15;
+    const int n_units = (a.rows + 16 * NT - 1) / (16 * NT);
+    const int u = n_units - 1 - (int)blockIdx.x, head = blockIdx.y;
+    const int rows_u = min(16 * NT, a.rows - 16 * NT * u);
+    const int p0 = a.pos0 + 16 * NT * u, last = p0 + rows_u - 1;
     const int kvh = head / (a.n_h / a.n_kv), PT = a.page_tokens;
-    const E* qp = (const E*)a.q + (size_t)c * a.q_chunk + (size_t)head * H * 16;
+    int M[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) M[t] = min(16, max(0, rows_u - 16 * t));
 
-    u32x4 qf[HS][NP];
+    u32x4 qf[NT][HS][NP];
 #pragma unroll
-    for (int hs = 0; hs < HS; ++hs)
+    for (int t = 0; t < NT; ++t) {
+        const E* qp = (const E*)a.q + (size_t)(NT * u + t) * a.q_chunk + (size_t)head * H * 16;
 #pragma unroll
-        for (int pl = 0; pl < NP; ++pl)
-            qf[hs][pl] = m < M ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * 16 + m) * KE) : u32x4{0u, 0u, 0u, 0u};
-
-    f32x4 o[HT];
+        for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
-    for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float mx = -INFINITY, l = 0.f;
+            for (int pl = 0; pl < NP; ++pl)
+                qf[t][hs][pl] = m < M[t] ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * 16 + m) * KE) : u32x4{0u, 0u, 0u, 0u};
+    }
+    f32x4 o[NT][HT];
+    float mx[NT], l[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        mx[t] = -INFINITY; l[t] = 0.f;
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) o[t][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     u32x4 kf[4][HS], vf[HT][KST];
-    auto load = [&](int kc) {
-        const int page = a.page_table[(kc * ASD_CHUNK) / PT], slot0 = (kc * ASD_CHUNK) % PT;
-        const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
-        const E* Vp = Kp + (size_t)PT * H;
+    auto chunk_base = [&](int kcv) {        // K rows of chunk kc; V^T follows PT * H elements after the page's K
+        // the chunk index is the same in every lane: as a scalar read through the constant address space (nothing
+        // writes the page table while a pass runs) the page lookup is a scalar load, outside the vector loads' queue
+        typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+        const int kc = __builtin_amdgcn_readfirstlane(kcv);
+        const int page = ((const_i32_ptr)(uintptr_t)a.page_table)[(kc * ASD_CHUNK) / PT], slot0 = (kc * ASD_CHUNK) % PT;
+        return (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H + (size_t)slot0 * H;
+    };
+    auto issue_k = [&](const E* Kc) {
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int hs = 0; hs < HS; ++hs)
-                kf[kt][hs] = *(const u32x4*)(Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE + hs * 4 * KE);
+                kf[kt][hs] = *(const u32x4*)(Kc + (size_t)score_key<T>(kt, r) * H + g * KE + hs * 4 * KE);
+    };
+    auto issue_v = [&](const E* Kc, int kc) {
+        const int slot0 = (kc * ASD_CHUNK) % PT;
+        const E* Vc = Kc - (size_t)slot0 * H + (size_t)PT * H + slot0;
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
-                vf[ht][ks] = *(const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE);
+                vf[ht][ks] = *(const u32x4*)(Vc + (size_t)(ht * 16 + r) * PT + ks * 4 * KE + g * KE);
+    };
+    auto one_chunk = [&](const int kc, auto has_next) {
+        constexpr bool more = decltype(has_next)::value;
+        const E* Kn = nullptr;
+        if constexpr (more) Kn = chunk_base(kc + NWV);
+        f32x4 s[NT][4];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt) {
+                s[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl) mma16<T>(s[t][kt], kf[kt][hs], qf[t][hs][pl]);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (more) issue_k(Kn);                 // the K registers are free again
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            // causal mask, running maximum and sum per row (= per column m); a chunk none of whose keys a row sees
+            // leaves that row's state as it is
+            const int row_pos = p0 + 16 * t + m;
+            float cm = -INFINITY;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int key = kc * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
+                    const float v = (key <= row_pos) ? s[t][kt][j] * a.scale : -INFINITY;
+                    s[t][kt][j] = v;
+                    cm = fmaxf(cm, v);
+                }
+            cm = fmaxf(cm, __shfl_xor(cm, 16));
+            cm = fmaxf(cm, __shfl_xor(cm, 32));
+            const float mn = fmaxf(mx[t], cm);
+            const float alpha = (mx[t] == -INFINITY) ? 0.f : __expf(mx[t] - mn);
+            float cs = 0.f;
+#pragma unroll
+            for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float p = (s[t][kt][j] == -INFINITY) ? 0.f : __expf(s[t][kt][j] - mn);
+                    s[t][kt][j] = p;
+                    cs += p;
+                }
+            cs += __shfl_xor(cs, 16);
+            cs += __shfl_xor(cs, 32);
+            l[t] = l[t] * alpha + cs;
+            mx[t] = mn;
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht) { o[t][ht][0] *= alpha; o[t][ht][1] *= alpha; o[t][ht][2] *= alpha; o[t][ht][3] *= alpha; }
+            u32x4 pf[KST][NP];
+            att_pfrags<T>(s[t], pf);
+#pragma unroll
+            for (int ht = 0; ht < HT; ++ht)
+#pragma unroll
+                for (int ks = 0; ks < KST; ++ks)
+#pragma unroll
+                    for (int pl = 0; pl < NP; ++pl) mma16<T>(o[t][ht], vf[ht][ks], pf[ks][pl]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (more) issue_v(Kn, kc + NWV);       // and so are the V^T registers
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     const int n_kc = last / ASD_CHUNK + 1;
-    load(0);
-    for (int kc = 0; kc < n_kc; ++kc) {
-        f32x4 s[4];
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int hs = 0; hs < HS; ++hs)
-#pragma unroll
-                for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf[kt][hs], qf[hs][pl]);
-        }
-        u32x4 vc[HT][KST];
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks) vc[ht][ks] = vf[ht][ks];
-        if (kc + 1 < n_kc) load(kc + 1);
-
-        // causal mask, running maximum and sum per row (= per column m)
-        float cm = -INFINITY;
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = kc * ASD_CHUNK + score_key<T>(kt, 4 * g + j);
-                const float v = (key <= row_pos) ? s[kt][j] * a.scale : -INFINITY;
-                s[kt][j] = v;
-                cm = fmaxf(cm, v);
-            }
-        cm = fmaxf(cm, __shfl_xor(cm, 16));
-        cm = fmaxf(cm, __shfl_xor(cm, 32));
-        const float mn = fmaxf(mx, cm);                         // finite from the first chunk on: key 0 is visible to every row
-        const float alpha = (mx == -INFINITY) ? 0.f : __expf(mx - mn);
-        float cs = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float p = (s[kt][j] == -INFINITY) ? 0.f : __expf(s[kt][j] - mn);
-                s[kt][j] = p;
-                cs += p;
-            }
-        cs += __shfl_xor(cs, 16);
-        cs += __shfl_xor(cs, 32);
-        l = l * alpha + cs;
-        mx = mn;
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht) { o[ht][0] *= alpha; o[ht][1] *= alpha; o[ht][2] *= alpha; o[ht][3] *= alpha; }
-
-        u32x4 pf[KST][NP];
-        if constexpr (KE == 8) {
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-                for (int w2 = 0; w2 < 4; ++w2) {
-                    const f32x4& t = s[2 * ks + (w2 >> 1)];
-                    const float p0v = t[(w2 & 1) * 2], p1v = t[(w2 & 1) * 2 + 1];
-                    const uint32_t h0 = BF16::from_f32(p0v), h1 = BF16::from_f32(p1v);
-                    const uint32_t l0 = BF16::from_f32(p0v - BF16::to_f32((uint16_t)h0)), l1 = BF16::from_f32(p1v - BF16::to_f32((uint16_t)h1));
-                    pf[ks][0][w2] = h0 | (h1 << 16);
-                    if constexpr (NP == 2) pf[ks][1][w2] = l0 | (l1 << 16);
-                }
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) pf[ks][0][j] = __float_as_uint(s[ks][j]);
-        }
-#pragma unroll
-        for (int ht = 0; ht < HT; ++ht)
-#pragma unroll
-            for (int ks = 0; ks < KST; ++ks)
-#pragma unroll
-                for (int pl = 0; pl < NP; ++pl) mma16<T>(o[ht], vc[ht][ks], pf[ks][pl]);
+    if (w < n_kc) {
+        const E* Kc = chunk_base(w);
+        issue_k(Kc);
+        issue_v(Kc, w);
+        int kc = w;
+        for (; kc + NWV < n_kc; kc += NWV) one_chunk(kc, std::true_type{});
+        one_chunk(kc, std::false_type{});
     }
 
-    if (m < M) {
-        const float inv = 1.f / l;
+    // ---- merge the four waves' partial results, wave order, one 16-row chunk at a time
 #pragma unroll
-        for (int ht = 0; ht < HT; ++ht) {
-            const float v[4] = {o[ht][0] * inv, o[ht][1] * inv, o[ht][2] * inv, o[ht][3] * inv};
-            store_act4<T>(a.out, a.q_plane, (int64_t)c * a.q_chunk, head * H + ht * 16 + 4 * g, m, v);
+    for (int t = 0; t < NT; ++t) {
+        if (g == 0) { sml[w][t][m][0] = mx[t]; sml[w][t][m][1] = l[t]; }
+#pragma unroll
+        for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[w][m][ht * 16 + 4 * g] = o[t][ht];
+        __syncthreads();
+        const int row = tid & 15;
+        float gmax = -INFINITY;                          // finite: wave 0 holds chunk 0, whose key 0 every row sees
+#pragma unroll
+        for (int ww = 0; ww < NWV; ++ww) gmax = fmaxf(gmax, sml[ww][t][row][0]);
+        float wgt[NWV], L = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NWV; ++ww) { wgt[ww] = __expf(sml[ww][t][row][0] - gmax); L += sml[ww][t][row][1] * wgt[ww]; }
+        const float inv = 1.f / L;
+        for (int d = (tid >> 4) * 4; d < H; d += 64) {
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ww = 0; ww < NWV; ++ww) {
+                const f32x4 x = *(const f32x4*)&so[ww][row][d];
+                v[0] += x[0] * wgt[ww]; v[1] += x[1] * wgt[ww]; v[2] += x[2] * wgt[ww]; v[3] += x[3] * wgt[ww];
+            }
+            v[0] *= inv; v[1] *= inv; v[2] *= inv; v[3] *= inv;
+            if (row < M[t]) store_act4<T>(a.out, a.q_plane, (int64_t)(NT * u + t) * a.q_chunk, head * H + d, row, v);
         }
+        __syncthreads();
     }
 }

@@ -652,10 +652,10 @@ template <int EPI> bool launch_pf_gemm(asd_engine* e, const PfCfg& g, const PfAr
 
 template <class T> void launch_pf_attn_t(asd_engine* e, const PfAttnArgs& a, int n_chunks) {
     const int H = e->c.head_dim;
-    const dim3 grid(n_chunks, e->c.n_heads);
-    if (H == 32) pf_attn_kernel<T, 32><<<grid, 64, 0, e->stream>>>(a);
-    if (H == 64) pf_attn_kernel<T, 64><<<grid, 64, 0, e->stream>>>(a);
-    if (H == 128) pf_attn_kernel<T, 128><<<grid, 64, 0, e->stream>>>(a);
+    const dim3 grid((n_chunks + PF_ATT_NT - 1) / PF_ATT_NT, e->c.n_heads);
+    if (H == 32) pf_attn_kernel<T, 32><<<grid, 256, 0, e->stream>>>(a);
+    if (H == 64) pf_attn_kernel<T, 64><<<grid, 256, 0, e->stream>>>(a);
+    if (H == 128) pf_attn_kernel<T, 128><<<grid, 256, 0, e->stream>>>(a);
 }
 
 template <class T> void launch_pf_rows_t(asd_engine* e, int what, int rows, int n_chunks, int ksplit, const float* gain, float* cos_row, int tail_row) {
