@@ -618,14 +618,14 @@ int capacity(const asd_engine* e) { return e->n_pages * e->c.page_tokens; }
 // Launch shape of a prompt GEMM class: NC 16-row chunks per workgroup and K slices (slices only for the two
 // residual-add GEMMs).  ASD_PF_TUNE (development aid) overrides, e.g. "qkv=8,1;o=8,2;gu=4,1;down=8,4".
 PfCfg pf_pick(const char* name, int nc, int ks) {
-    PfCfg g{nc, ks, 1};
+    PfCfg g{nc, ks, 2};
     if (const char* env = getenv("ASD_PF_TUNE")) {
         std::string e(env), key = std::string(name) + "=";
         size_t pos = (";" + e).find(";" + key);
         if (pos != std::string::npos) {
             int a, b, d = 1;
             if (sscanf(e.c_str() + pos + key.size(), "%d,%d,%d", &a, &b, &d) >= 2 && (a == 2 || a == 4 || a == 8) && b >= 1 && b <= PF_MAX_KSPLIT &&
-                (d == 1 || d == 2)) { g.NC = a; g.KS = b; g.PD = d; }
+                d >= 1 && d <= 4) { g.NC = a; g.KS = b; g.PD = d; }
         }
     }
     return g;
@@ -642,7 +642,7 @@ template <class T, int EPI> bool launch_pf_gemm_t(hipStream_t s, const PfCfg& g,
     if (a.ksplit > a.KB) a.ksplit = a.KB;
     const unsigned grid = (unsigned)((a.n_fb + 7) / 8 * 8 * a.n_rb * a.ksplit);
 #define PFK(nc, pd) if (g.NC == nc && g.PD == pd) { pf_gemm_kernel<T, EPI, NA, nc, PF_NW, pd><<<grid, PF_NW * 64, 0, s>>>(a); return true; }
-    PFK(2, 1) PFK(4, 1) PFK(8, 1) PFK(2, 2) PFK(4, 2) PFK(8, 2)
+    PFK(2, 1) PFK(4, 1) PFK(8, 1) PFK(2, 2) PFK(4, 2) PFK(8, 2) PFK(2, 3) PFK(4, 3) PFK(2, 4) PFK(4, 4)
 #undef PFK
     return false;
 }

@@ -18,6 +18,7 @@
 //           the residual stream in slice order, writes the normed copy for the next sublayer and finishes the
 //           cosine tap of every row.
 #pragma once
+#include <type_traits>
 #include "asd_gemm.h"
 
 #define PF_ROWS 512                    // rows per prompt block
@@ -56,7 +57,7 @@ template <class T> __device__ __forceinline__ void store_elem4(typename T::elem*
 }
 
 template <class T, int EPI, int NA, int NC, int NW, int PD>
-__global__ __launch_bounds__(NW * 64) void pf_gemm_kernel(const PfArgs a) {
+__global__ __launch_bounds__(NW * 64, PD >= 2 ? 2 : 1) void pf_gemm_kernel(const PfArgs a) {
     using E = typename T::elem;
     constexpr int NP = T::NP;
     constexpr int NAT = (EPI == PF_GU) ? 2 * NA : NA;
@@ -96,48 +97,53 @@ __global__ __launch_bounds__(NW * 64) void pf_gemm_kernel(const PfArgs a) {
 #pragma unroll
         for (int c = 0; c < NC; ++c) acc[s][c] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // weight and activation fragments are requested PD k-blocks ahead of their use (register ring)
+    // Weight and activation fragments are requested PD k-blocks ahead of their use (register ring).  Every trip of
+    // the main loop issues the same loads whatever the k-block (past the end of the range the last k-block is asked
+    // for again and never used): the wait counts the compiler derives are exact only when no path skips a load, and
+    // one conditional request is enough to turn every wait into a full drain, which undoes the prefetch.
     u32x4 an[PD][NAT], xg[PD][XW];
     auto issue = [&](int slot, int kb) {
 #pragma unroll
         for (int i = 0; i < XW; ++i)
-            if (w + NW * i < XF) xg[slot][i] = Xp[i][(size_t)kb * ASD_WAVE];
+            if (XF % NW == 0 || w + NW * i < XF) xg[slot][i] = Xp[i][(size_t)kb * ASD_WAVE];
 #pragma unroll
         for (int s = 0; s < NAT; ++s) an[slot][s] = A[s][(size_t)kb * a.w_kb_stride * ASD_WAVE];
     };
+    // One k-block from ring slot p.  The slot's next request goes out only after its products (straight into the
+    // same registers): asked for any earlier, the old values would have to be copied aside and the new ones copied
+    // back at the loop's end, which the compiler can only do after waiting for them, every trip.
+    auto k_block = [&](const int p, const int kb, auto prefetch) {
+        const int buf = (kb - kb0) & 1;
 #pragma unroll
-    for (int p = 0; p < PD; ++p)
-        if (kb0 + p < kb1) issue(p, kb0 + p);
-    for (int kbb = kb0; kbb < kb1; kbb += PD) {
+        for (int i = 0; i < XW; ++i)
+            if (XF % NW == 0 || w + NW * i < XF) xs[buf][w + NW * i][lane] = xg[p][i];
+        __syncthreads();
+        // all LDS reads of the k-block are requested before its first MFMA: one LDS latency per k-block, not one per pair
+        u32x4 b[NC][NP];
 #pragma unroll
-        for (int p = 0; p < PD; ++p) {
-            const int kb = kbb + p;
-            if (kb < kb1) {
-                const int buf = (kb - kb0) & 1;
-                u32x4 ac[NAT];
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int s = 0; s < NAT; ++s) ac[s] = an[p][s];
+            for (int pl = 0; pl < NP; ++pl) b[c][pl] = xs[buf][c * NP + pl][lane];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < XW; ++i)
-                    if (w + NW * i < XF) xs[buf][w + NW * i][lane] = xg[p][i];
-                __syncthreads();
-                if (kb + PD < kb1) issue(p, kb + PD);
-                // all LDS reads of the k-block are requested before its first MFMA: one LDS latency per k-block, not one per pair
-                u32x4 b[NC][NP];
+        for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int c = 0; c < NC; ++c)
+            for (int pl = 0; pl < NP; ++pl)
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl) b[c][pl] = xs[buf][c * NP + pl][lane];
-                __builtin_amdgcn_sched_barrier(0);
+                for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], an[p][s], b[c][pl]);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(prefetch)::value) issue(p, kb + PD < kb1 ? kb + PD : kb1 - 1);
+    };
 #pragma unroll
-                for (int c = 0; c < NC; ++c)
+    for (int p = 0; p < PD; ++p) issue(p, kb0 + p < kb1 ? kb0 + p : kb1 - 1);
+    const int n_full = (kb1 - kb0) / PD * PD;
+    for (int kbb = kb0; kbb < kb0 + n_full; kbb += PD) {
 #pragma unroll
-                    for (int pl = 0; pl < NP; ++pl)
-#pragma unroll
-                        for (int s = 0; s < NAT; ++s) mma16<T>(acc[s][c], ac[s], b[c][pl]);
-            }
-        }
+        for (int p = 0; p < PD; ++p) k_block(p, kbb + p, std::true_type{});
     }
+#pragma unroll
+    for (int p = 0; p + 1 < PD; ++p)                    // the last, partial round: nothing further to request
+        if (kb0 + n_full + p < kb1) k_block(p, kb0 + n_full + p, std::false_type{});
 
     // ---- epilogues, straight from the accumulators: lane 16g + m holds features 4g..4g+3 of each tile for row m
     int row[NC];
