@@ -71,41 +71,55 @@ struct GemmArgs {
 // Stream n k-blocks kb = first, first + step, ... of NA weight tiles and the matching activation fragments
 // (NPL fragments per k-block, xpl apart, each with its own accumulators).
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
-// X points at this lane's fragment of k-block 0 (or is NULL for a lane whose row is unused: zeros); consecutive
-// k-blocks are xstep fragments apart.
+// X points at this lane's fragment of k-block 0 (always a valid address); consecutive k-blocks are xstep fragments
+// apart.
 template <class T, int NA, int NPL, int U, bool COH, class F>
 __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
                                            int64_t wks, f32x4 (&acc)[NPL][NA], F between) {
+    // A ring of U slots.  The steady-state loop has no conditional request in it, and X is a valid address in every
+    // lane (a lane whose row is not in use reads another row's fragment: its column of the products is never read,
+    // and zeroing it would be a use that waits for the load).  The wait counts the compiler derives are exact only
+    // when every path issues the same loads; a single request under a condition made it wait for ALL outstanding
+    // loads at the top of every trip, which turns the ring into load-everything-then-drain.
     u32x4 a[U][NA], b[U][NPL];
+    auto fill = [&](const int u, const int kb) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        if (u < n) {
-            const size_t o = (size_t)(first + u * step) * ASD_WAVE;
+        for (int pl = 0; pl < NPL; ++pl) b[u][pl] = ld_frag<COH>(X + (size_t)(first + kb * step) * xstep + pl * xpl);
 #pragma unroll
-            for (int pl = 0; pl < NPL; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + u * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
+        for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + (size_t)(first + kb * step) * ASD_WAVE * wks);
+    };
+    auto use = [&](const int u) {
 #pragma unroll
-            for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
+        for (int s = 0; s < NA; ++s)
+#pragma unroll
+            for (int pl = 0; pl < NPL; ++pl) mma16<T>(acc[pl][s], a[u][s], b[u][pl]);
+    };
+    if (n >= U) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) fill(u, u);
+        between();
+        int i = 0;
+        for (; i + 2 * U <= n; i += U) {               // every refill of such a trip is a k-block of the range
+#pragma unroll
+            for (int u = 0; u < U; ++u) { use(u); fill(u, i + u + U); }
         }
-    }
-    between();
-    for (int i = 0; i < n; i += U) {
+        const int extra = n - i - U;                   // 0 .. U-1 k-blocks still to request; the slots hold i .. i+U-1
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            if (i + u < n) {
-#pragma unroll
-                for (int s = 0; s < NA; ++s)
-#pragma unroll
-                    for (int pl = 0; pl < NPL; ++pl) mma16<T>(acc[pl][s], a[u][s], b[u][pl]);
-                const int nx = i + u + U;
-                if (nx < n) {
-                    const size_t o = (size_t)(first + nx * step) * ASD_WAVE;
-#pragma unroll
-                    for (int pl = 0; pl < NPL; ++pl) b[u][pl] = X ? ld_frag<COH>(X + (size_t)(first + nx * step) * xstep + pl * xpl) : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-                    for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + o * wks);
-                }
-            }
+            use(u);
+            if (u < extra) fill(u, i + u + U);
         }
+#pragma unroll
+        for (int u = 0; u + 1 < U; ++u)
+            if (u < extra) use(u);
+    } else {                                           // a K range shorter than the ring
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < n) fill(u, u);
+        between();
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < n) use(u);
     }
 }
 
@@ -131,7 +145,11 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     __shared__ float fin_b[kNormed ? NT : 1];
     __shared__ float rscale[16];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    // The wave index as a scalar: everything derived from it (this wave's K range, the trip counts of the stream) is
+    // then scalar too and the stream's control flow is real branches.  As a vector value the conditions become lane
+    // masks, and a short conditional block is then executed with an empty mask instead of being branched around;
+    // the matrix-core instructions do not honour the mask.
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     int tile[NA];
     bool tval[NA];
@@ -158,16 +176,22 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     // residual epilogue this thread's residual inputs.
     float syy = 0.f, sxy = 0.f;
     constexpr int NE = (EPI == EPI_RES) ? (NA * 256 + NT - 1) / NT : 1;
-    float xpre[NE], gpre[NE];
+    constexpr int PRE_P = 8;                          // partials per thread requested ahead (the rest, if any, after the stream)
+    float xpre[NE], gpre[NE], py[kNormed ? PRE_P : 1], px[kNormed ? PRE_P : 1];
+    // Only requests here, no use: the loads queue in order, and waiting for one of these would wait for every
+    // weight fragment requested before it, i.e. empty the ring once at the start of every kernel.
     auto early = [&]() {
         if constexpr (kNormed) {
             constexpr int J = NT / 16;
             const int m = tid & 15, j = tid >> 4;
-            if (m < a.M) {
-                for (int p = j; p < a.P_in; p += J) {
-                    syy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2 + 1]);
-                    if (bid == 0) sxy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2]);
-                }
+#pragma unroll
+            for (int q = 0; q < PRE_P; ++q) {
+                const int p = j + q * J;
+                const bool on = m < a.M && p < a.P_in;
+                const float* src = &a.part_in[((size_t)(on ? p : 0) * 16 + (on ? m : 0)) * 2];
+                const float y = ld_f32<COH>(src + 1), x = ld_f32<COH>(src);
+                py[q] = on ? y : 0.f;
+                px[q] = on ? x : 0.f;
             }
         }
         if constexpr (EPI == EPI_RES) {
@@ -182,16 +206,35 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
             }
         }
     };
+    // ||y||^2 (and x.y in workgroup 0) per row from the partials, in the same order in every workgroup
+    auto sum_partials = [&]() {
+        if constexpr (kNormed) {
+            constexpr int J = NT / 16;
+            const int m = tid & 15, j = tid >> 4;
+            if (m < a.M) {
+#pragma unroll
+                for (int q = 0; q < PRE_P; ++q)
+                    if (j + q * J < a.P_in) { syy += py[q]; if (bid == 0) sxy += px[q]; }
+                for (int p = j + PRE_P * J; p < a.P_in; p += J) {
+                    syy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2 + 1]);
+                    if (bid == 0) sxy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2]);
+                }
+            }
+        }
+    };
 
     f32x4 acc[NPL][NA];
 #pragma unroll
     for (int pl = 0; pl < NPL; ++pl)
 #pragma unroll
         for (int s = 0; s < NA; ++s) acc[pl][s] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // this lane's activation fragments; a lane whose row is not in use reads row 0's (the epilogues never look at
+    // the columns of unused rows)
     const u32x4* Xl;
-    if constexpr (PACK) Xl = (lane & 7) < a.M ? a.X + ((lane & 8) ? a.x_plane : 0) + (lane >> 4) * a.RS + (lane & 7) : nullptr;
-    else Xl = (lane & 15) < a.M ? a.X + (lane >> 4) * a.RS + (lane & 15) : nullptr;
+    if constexpr (PACK) Xl = a.X + ((lane & 8) ? a.x_plane : 0) + (lane >> 4) * a.RS + ((lane & 7) < a.M ? (lane & 7) : 0);
+    else Xl = a.X + (lane >> 4) * a.RS + ((lane & 15) < a.M ? (lane & 15) : 0);
     stream_mma<T, NA, NPL, U, COH>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
+    sum_partials();
 
 #pragma unroll
     for (int pl = 0; pl < NPL; ++pl)
