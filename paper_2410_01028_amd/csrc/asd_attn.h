@@ -53,6 +53,7 @@ struct AttnArgs {
     int32_t nc_stride;        // groups per head in the partial buffers
     int32_t grid_groups;      // groups per head the launch covers (per-step kernels: see attn_unit)
     int32_t gh;               // query heads of one KV head a workgroup handles at once (a power of two, gh * RS <= 16)
+    int32_t cap_chunks;       // 64-key chunks the cache has room for (the page table covers them all)
     float scale;              // 1/sqrt(h)
     float* o_part;            // [n_h][nc_stride][16][h] unnormalised group outputs
     float* ml_part;           // [n_h][nc_stride][16][2] (group max, group sum)
@@ -235,7 +236,7 @@ __device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int 
 // every gh.  Every thread of the calling workgroup must call this the same
 // number of times (it synchronises the workgroup); `valid` = false makes the group a no-op, hw is the wave's
 // index inside its group.  so: [ATT_GW][ATT_RH][H] floats, sml: [ATT_GW][16][2] floats, s_old: 1 word, per group.
-template <class T, int H, bool COH>
+template <class T, int H, bool COH, bool EARLY = false>
 __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, const int head, const bool valid, const int hw,
                                            const int lane, float* so, float* sml, unsigned* s_old) {
     using E = typename T::elem;
@@ -248,51 +249,58 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     const int cj = m / a.RS, cm = m % a.RS;                 // this lane's column: head head + cj, row cm
     const bool col_ok = cj < a.gh && cm < a.M;
     const int n_cols = (a.gh - 1) * a.RS + a.M;             // columns in use: 0 .. n_cols-1 (those with cm >= M are holes)
-    const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
-    const int n_groups = last / ATT_GROUP + 1;
     const int c = grp * ATT_GW + hw;
-    const bool active = valid && c * ASD_CHUNK <= last;
-
-    f32x4 o[HT];
-#pragma unroll
-    for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float mx = -INFINITY, l = 0.f;
-    if (active) {
-        const int kvh = head / (a.n_h / a.n_kv);
-        const int PT = a.page_tokens;
+    const int kvh = head / (a.n_h / a.n_kv);
+    const int PT = a.page_tokens;
+    u32x4 qf[HS][NP], kf[4][HS], vf[HT][KST];
+    auto request = [&]() {                  // this chunk's K and V^T fragments and the query fragments
         const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
         const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
         const E* Vp = Kp + (size_t)PT * H;
         const E* qp = (const E*)a.q + (size_t)(head + (col_ok ? cj : 0)) * H * a.RS;
-
-        // ---- scores: 4 tiles of 16 keys
-        u32x4 qf[HS][NP];
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
                 qf[hs][pl] = col_ok ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + cm) * KE))
                                     : u32x4{0u, 0u, 0u, 0u};
-        f32x4 s[4];
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt) {
-            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const E* krow = Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE;
+        for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-            for (int hs = 0; hs < HS; ++hs) {
-                const u32x4 kf = __builtin_nontemporal_load((const u32x4*)(krow + hs * 4 * KE));
-#pragma unroll
-                for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf, qf[hs][pl]);
-            }
-        }
-        // ---- V^T fragments (independent of the scores: issued early)
-        u32x4 vf[HT][KST];
+            for (int hs = 0; hs < HS; ++hs)
+                kf[kt][hs] = __builtin_nontemporal_load((const u32x4*)(Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE + hs * 4 * KE));
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
                 vf[ht][ks] = __builtin_nontemporal_load(
                     (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
+    };
+    // EARLY: the requests go out before the pass's position is known (the chunk exists in the cache whatever the
+    // position; a chunk beyond the position is then dropped unused), which takes the position's load and the
+    // comparison out of the chain position -> page -> fragments.
+    if constexpr (EARLY) { if (valid && c < a.cap_chunks) request(); }
+    const int pos0 = a.st->pos + a.pos_off, last = pos0 + a.M - 1;
+    const int n_groups = last / ATT_GROUP + 1;
+    const bool live = valid && grp * ATT_GROUP <= last;     // a group no row of the call sees is a no-op
+    const bool active = live && c * ASD_CHUNK <= last;
+
+    f32x4 o[HT];
+#pragma unroll
+    for (int ht = 0; ht < HT; ++ht) o[ht] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mx = -INFINITY, l = 0.f;
+    if (active) {
+        if constexpr (!EARLY) request();
+        // ---- scores: 4 tiles of 16 keys
+        f32x4 s[4];
+#pragma unroll
+        for (int kt = 0; kt < 4; ++kt) {
+            s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int hs = 0; hs < HS; ++hs)
+#pragma unroll
+                for (int pl = 0; pl < NP; ++pl) mma16<T>(s[kt], kf[kt][hs], qf[hs][pl]);
+        }
 
         // ---- causal mask, chunk max, exponentials, chunk sum (per column)
         att_softmax<T>(s, c, pos0 + cm, a.scale, g, mx, l);
@@ -309,7 +317,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     }
     if (g == 0) { sml[(hw * ASD_ROWS + m) * 2] = mx; sml[(hw * ASD_ROWS + m) * 2 + 1] = l; }
 
-    att_group_merge<T, H, COH>(a, grp, head, valid, n_groups, n_cols, hw, lane, o, so, sml);
+    att_group_merge<T, H, COH>(a, grp, head, live, n_groups, n_cols, hw, lane, o, so, sml);
     if (n_groups == 1) return;
 
     // ---- arrival: the group that completes the head's last outstanding group merges the groups
@@ -317,7 +325,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     __builtin_amdgcn_s_waitcnt(0);                   // this wave's partial stores have completed
     __syncthreads();
     if (hw == 0 && lane == 0) {
-        *s_old = valid ? __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xffffffffu;
+        *s_old = live ? __hip_atomic_fetch_add(a.arrivals + head, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xffffffffu;
     }
     __syncthreads();
     if ((int)*s_old == n_groups - 1) {                // the group's waves share the (head, row) pairs, ATT_RB per wave and trip
@@ -351,8 +359,9 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
     __shared__ unsigned s_old;
     int grp, head;
     if (!attn_unit(a, &grp, &head)) return;
-    if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;       // no row of this call sees this group
-    attn_group<T, H, false>(a, grp, head, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
+    // (a group no row of this call sees does nothing: every wave of it is inactive, and a context of one group
+    // returns before the arrival)
+    attn_group<T, H, false, true>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
 }
 
 // The same kernel with the register allocation held to four waves per SIMD (128 registers instead of ~220): a wave
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(const AttnArgs 
     int grp, head;
     if (!attn_unit(a, &grp, &head)) return;
     if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
-    attn_group<T, H, false>(a, grp, head, true, threadIdx.x >> 6, threadIdx.x & 63, so, sml, &s_old);
+    attn_group<T, H, false>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
 }
 
 // ---------------------------------------------------------------- prompt blocks: causal attention

@@ -349,10 +349,13 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
     return e->c.dtype == ASD_DT_BF16 ? launch_gemm_t<BF16, EPI>(e->stream, g, a) : launch_gemm_t<F32, EPI>(e->stream, g, a);
 }
 
+int capacity(const asd_engine* e);
+
 template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc) {
     const int H = e->c.head_dim;
     AttnArgs a = a0;
     a.grid_groups = (nc + ATT_GW - 1) / ATT_GW;
+    a.cap_chunks = capacity(e) / ASD_CHUNK;
     // grouped-query models: as many query heads of a KV head per workgroup as the 16 columns hold beside the rows
     a.gh = 1;
     if (!e->att_gh1) while (a.gh * 2 * a.RS <= ASD_ROWS && a.gh * 2 <= e->c.n_heads / e->c.n_kv_heads && (e->c.n_heads / e->c.n_kv_heads) % (a.gh * 2) == 0) a.gh *= 2;
