@@ -408,3 +408,24 @@ def test_query_heads_per_attention_workgroup_give_the_same_bits(shape, monkeypat
         eng.close()
     for x, y in zip(*outs):
         assert np.array_equal(x, y)
+
+
+# K sizes that put a wave's share of the weight stream (K / 32 k-blocks over 8 waves, ring of 4 slots) into every
+# phase of the ring: shorter than the ring (1, 3), exactly one ring (4), a partial last round without a steady-state
+# trip (5, 7), steady-state trips with and without a remainder (8, 9, 12, 13), and uneven shares (the 43 and 86
+# k-blocks of the down projection's 1376 and 2752 inputs)
+RING_SHAPES = [si.Shape(f"ring-{dm}-{ff}", 1, dm, 2, 2, 64, ff, 512, dt, 12, 8, 3)
+               for dm, ff, dt in ((256, 768, si.DT_BF16), (1024, 1280, si.DT_BF16), (1792, 2048, si.DT_BF16),
+                                  (2304, 3072, si.DT_BF16), (3328, 1376, si.DT_BF16), (512, 2752, si.DT_BF16),
+                                  (640, 1168, si.DT_F32))]
+
+
+@pytest.mark.parametrize("shape", RING_SHAPES, ids=lambda s: s.name)
+def test_weight_stream_ring_phases_against_oracle(shape):
+    eng, orc = build_pair(shape, seed=6, max_seq=64, gain_std=0.1)
+    tol = TOL[shape.dtype]
+    toks = si.prompt(2, 40, shape.vocab)
+    pos = 0
+    for n in (1, 5, 8, 9, 16, 1):                      # packed (<= 8 rows) and two-operand passes
+        check_forward(eng, orc, toks[pos:pos + n], pos, None, tol)
+        pos += n
