@@ -65,7 +65,7 @@ __global__ __launch_bounds__(NW * 64, PD >= 2 ? 2 : 1) void pf_gemm_kernel(const
     constexpr int XW = (XF + NW - 1) / NW;            // ... staged by each wave
     __shared__ u32x4 xs[2][XF][64];
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, g = lane >> 4, m = lane & 15;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 4, m = lane & 15;
     // workgroup -> (feature block, row block, K slice): consecutive workgroup ids go to the 8 XCDs in turn, so the
     // XCD is the low 3 bits; on one XCD the row blocks and K slices of a feature block follow each other.
     const int L = blockIdx.x, inner = a.n_rb * a.ksplit;
