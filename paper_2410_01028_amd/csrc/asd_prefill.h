@@ -279,20 +279,39 @@ __global__ __launch_bounds__(256) void pf_resid_kernel(const float* raw, int ksp
     __shared__ float red[256];
     const int r = blockIdx.x, tid = threadIdx.x;
     float sxy = 0.f, syy = 0.f;
-    for (int n0 = tid * 4; n0 < d; n0 += 1024) {
-        const float4 x4 = *(const float4*)&xres[(size_t)r * d + n0];
-        float4 s4 = *(const float4*)&raw[(size_t)r * d + n0];
-        for (int k = 1; k < ksplit; ++k) {
-            const float4 t = *(const float4*)&raw[((size_t)k * PF_ROWS + r) * d + n0];
-            s4.x += t.x; s4.y += t.y; s4.z += t.z; s4.w += t.w;
-        }
-        const float4 gn = *(const float4*)&g_next[n0];
-        const float x[4] = {x4.x, x4.y, x4.z, x4.w}, s[4] = {s4.x, s4.y, s4.z, s4.w}, gg[4] = {gn.x, gn.y, gn.z, gn.w};
-        float y[4], v[4];
+    // four 4-element pieces per thread and trip, every load of a trip requested before the first use: with two
+    // workgroups per compute unit there is little else to hide the latency of a piece-by-piece walk
+    constexpr int PB = 4;
+    for (int base = tid * 4; base < d; base += PB * 1024) {
+        float4 x4[PB], s4[PB], gn[PB], t4[PB][PF_MAX_KSPLIT - 1];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { y[j] = x[j] + s[j]; v[j] = y[j] * gg[j]; sxy += x[j] * y[j]; syy += y[j] * y[j]; }
-        *(float4*)&xres[(size_t)r * d + n0] = float4{y[0], y[1], y[2], y[3]};
-        store_act4<T>(xb, xb_plane, (int64_t)(r / 16) * xb_chunk, n0, r % 16, v);
+        for (int q = 0; q < PB; ++q) {
+            const int n0 = base + q * 1024;
+            if (n0 < d) {
+                x4[q] = *(const float4*)&xres[(size_t)r * d + n0];
+                s4[q] = *(const float4*)&raw[(size_t)r * d + n0];
+                gn[q] = *(const float4*)&g_next[n0];
+#pragma unroll
+                for (int k = 1; k < PF_MAX_KSPLIT; ++k)
+                    if (k < ksplit) t4[q][k - 1] = *(const float4*)&raw[((size_t)k * PF_ROWS + r) * d + n0];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int n0 = base + q * 1024;
+            if (n0 < d) {
+#pragma unroll
+                for (int k = 1; k < PF_MAX_KSPLIT; ++k)
+                    if (k < ksplit) { s4[q].x += t4[q][k - 1].x; s4[q].y += t4[q][k - 1].y; s4[q].z += t4[q][k - 1].z; s4[q].w += t4[q][k - 1].w; }
+                const float x[4] = {x4[q].x, x4[q].y, x4[q].z, x4[q].w}, sv[4] = {s4[q].x, s4[q].y, s4[q].z, s4[q].w};
+                const float gg[4] = {gn[q].x, gn[q].y, gn[q].z, gn[q].w};
+                float y[4], v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { y[j] = x[j] + sv[j]; v[j] = y[j] * gg[j]; sxy += x[j] * y[j]; syy += y[j] * y[j]; }
+                *(float4*)&xres[(size_t)r * d + n0] = float4{y[0], y[1], y[2], y[3]};
+                store_act4<T>(xb, xb_plane, (int64_t)(r / 16) * xb_chunk, n0, r % 16, v);
+            }
+        }
     }
     const float xy = pf_block_sum(sxy, red);
     const float yy = pf_block_sum(syy, red);
