@@ -96,6 +96,7 @@ struct asd_engine {
     unsigned long long bar_count;
     int32_t* bar_err;
     std::vector<uint8_t> graph_mask;
+    bool sample_mem;                    // ASD_SAMPLE_MEM (test aid): sampling kernels that re-read memory instead of holding their segments
     bool att_gh1;                       // ASD_ATT_GH1 (test aid): one query head per attention workgroup also for grouped-query models
     bool force_att_w4;                  // ASD_ATT_W4 (development / test aid): always launch the four-waves-per-SIMD attention variant
     float graph_T;
@@ -224,7 +225,7 @@ Plan make_plan(const asd_config& c) {
     p.part = take((size_t)pmax * ASD_ROWS * 2 * 4);
     p.cos_rows = take((size_t)2 * c.n_layers * ASD_ROWS * 4);
     p.logits = take((size_t)ASD_ROWS * c.vocab * 4);
-    p.qlogits = take((size_t)ASD_ROWS * c.vocab * 4);
+    p.qlogits = take((size_t)ASD_ROWS * c.vocab * 4 + ASD_ROWS * 16);      // + per row: (maximum, Z) of the draft softmax as doubles
     p.o_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * c.head_dim * 4);
     p.rope = take((size_t)p.n_pages * c.page_tokens * (c.head_dim / 2) * 2 * 4);
     p.ml_part = take((size_t)c.n_heads * p.nc_stride * ASD_ROWS * 8);
@@ -833,6 +834,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
     e->att_gh1 = getenv("ASD_ATT_GH1") != nullptr;
+    e->sample_mem = getenv("ASD_SAMPLE_MEM") != nullptr;
     e->force_att_w4 = getenv("ASD_ATT_W4") != nullptr; e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
     // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
     e->persistent = false; e->pass_grid = 0;
@@ -1161,9 +1163,28 @@ static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int
 static SampleArgs sample_args(asd_engine* e, float temperature, uint64_t seed) {
     SampleArgs a{};
     a.logits = e->logits; a.qlogits = e->qlogits; a.V = e->c.vocab; a.inv_T = 1.f / temperature;
+    a.qstat = (double*)(e->qlogits + (size_t)ASD_ROWS * e->c.vocab);
     a.stream = h_stream(seed, 102u, 0u);
     a.st = e->st; a.tokbuf = e->tokbuf; a.out = e->out_tokens;
     return a;
+}
+
+// The sampling kernels hold a thread's share of a logit row in registers when the vocabulary allows it
+// (ASD_SAMPLE_MEM, a test aid, forces the variant that re-reads memory: same arithmetic, same draws).
+static bool sample_in_registers(const asd_engine* e) {
+    return !e->sample_mem && e->c.vocab <= SAMPLE_SEG * SAMPLE_THREADS;
+}
+static void launch_sample_draft(asd_engine* e, const SampleArgs& sa, int j) {
+    if (sample_in_registers(e)) sample_draft_kernel<SAMPLE_SEG><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+    else sample_draft_kernel<0><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+}
+static void launch_sample_accept(asd_engine* e, const SampleArgs& sa, int kk) {
+    if (sample_in_registers(e)) sample_accept_kernel<SAMPLE_SEG><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+    else sample_accept_kernel<0><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+}
+static void launch_sample_plain(asd_engine* e, const SampleArgs& sa, int row, int64_t index) {
+    if (sample_in_registers(e)) sample_plain_kernel<SAMPLE_SEG><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, row, index);
+    else sample_plain_kernel<0><<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, row, index);
 }
 
 // one sampled draft / verify / accept cycle, enqueue only
@@ -1171,11 +1192,11 @@ static int enqueue_sampled_cycle(asd_engine* e, int kk, const uint8_t* mask, int
     for (int j = 0; j < kk; ++j) {
         int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_NONE, 0);
         if (rc) return rc;
-        sample_draft_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+        launch_sample_draft(e, sa, j);
     }
     int rc = enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_NONE, 0);
     if (rc) return rc;
-    sample_accept_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+    launch_sample_accept(e, sa, kk);
     return ASD_OK;
 }
 
@@ -1192,10 +1213,10 @@ int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits,
     set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, kk + 1, 1, (int)index0);
     for (int j = 0; j < kk; ++j) {                 // each draft row takes the place a draft step's logits would have
         CK(e, hipMemcpyAsync(e->logits, q_logits + (size_t)j * V, V * 4, hipMemcpyHostToDevice, e->stream));
-        sample_draft_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, j);
+        launch_sample_draft(e, sa, j);
     }
     CK(e, hipMemcpyAsync(e->logits, p_logits, (size_t)(kk + 1) * V * 4, hipMemcpyHostToDevice, e->stream));
-    sample_accept_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, kk);
+    launch_sample_accept(e, sa, kk);
     int32_t tb[ASD_ROWS + 1];
     CK(e, hipMemcpyAsync(tb, e->tokbuf, sizeof tb, hipMemcpyDeviceToHost, e->stream));
     CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
@@ -1366,7 +1387,7 @@ int asd_generate(asd_engine* e, const int32_t* prompt, int32_t n_prompt, int32_t
     asd_gen_params pp = *p;
     if (p->temperature > 0.f) {           // the prompt pass's token is a plain draw with U(0, 2); decoding continues at index 1
         const SampleArgs sa = sample_args(e, p->temperature, p->seed);
-        sample_plain_kernel<<<1, SAMPLE_THREADS, 0, e->stream>>>(sa, e->last_logits_row, 0);
+        launch_sample_plain(e, sa, e->last_logits_row, 0);
         CK(e, hipMemcpyAsync(&t1, e->tokbuf, 4, hipMemcpyDeviceToHost, e->stream));
         CK(e, hipStreamSynchronize(e->stream));
         pp.sample_index0 = 1;

@@ -121,3 +121,34 @@ def test_sampled_loop_against_oracle():
             assert all(gst[x] == wst[x] for x in ("cycles", "drafted", "accepted", "emitted"))
             compared += 1
     assert compared >= 8
+
+
+def test_register_and_memory_variants_of_the_sampling_kernels_draw_the_same(monkeypatch):
+    """The sampling kernels hold a thread's share of a logit row in registers when the vocabulary allows it, and read
+    it from memory at every use otherwise: the same arithmetic in the same order, so the same draws, bit for bit
+    (drafts, accepted counts, replacements, and a whole sampled decode)."""
+    shape = si.SHAPES["tiny"].with_(vocab=4096)
+    rng = np.random.default_rng(11)
+    outs = []
+    for mem in (False, True):
+        if mem:
+            monkeypatch.setenv("ASD_SAMPLE_MEM", "1")
+        else:
+            monkeypatch.delenv("ASD_SAMPLE_MEM", raising=False)
+        eng = asd.Engine(asd.make_config(shape, 128)).init_synthetic(3)
+        got = []
+        r = np.random.default_rng(5)
+        for case in range(12):
+            kk = int(r.integers(0, 5))
+            q = r.normal(0, 2.5, (kk, shape.vocab)).astype(np.float32)
+            p = (q[:kk] + r.normal(0, 1.0, (kk, shape.vocab))).astype(np.float32) if kk else np.zeros((0, shape.vocab), np.float32)
+            p = np.concatenate([p, r.normal(0, 2.5, (1, shape.vocab)).astype(np.float32)])
+            drafts, a, nxt = eng.spec_sample(q, p, 0.7, seed=case, index0=3 * case)
+            got += [np.asarray(drafts), a, nxt]
+        prompt = si.prompt(1, 20, shape.vocab)
+        toks, st, _ = eng.generate(prompt, 40, 3, alpha=0.9, m=2, n=1, temperature=0.8, seed=9)
+        got += [toks, st["accepted"], st["drafted"]]
+        outs.append(got)
+        eng.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
