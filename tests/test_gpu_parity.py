@@ -417,7 +417,10 @@ def test_query_heads_per_attention_workgroup_give_the_same_bits(shape, monkeypat
 RING_SHAPES = [si.Shape(f"ring-{dm}-{ff}", 1, dm, 2, 2, 64, ff, 512, dt, 12, 8, 3)
                for dm, ff, dt in ((256, 768, si.DT_BF16), (1024, 1280, si.DT_BF16), (1792, 2048, si.DT_BF16),
                                   (2304, 3072, si.DT_BF16), (3328, 1376, si.DT_BF16), (512, 2752, si.DT_BF16),
-                                  (640, 1168, si.DT_F32))]
+                                  (640, 1168, si.DT_F32),
+                                  # 514 output tiles: more partial sums per row (one per producing workgroup) than a
+                                  # thread of the consuming kernel requests ahead of its weight stream
+                                  (8224, 256, si.DT_BF16))]
 
 
 @pytest.mark.parametrize("shape", RING_SHAPES, ids=lambda s: s.name)
