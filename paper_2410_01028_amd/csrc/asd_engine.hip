@@ -352,6 +352,14 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
 
 int capacity(const asd_engine* e);
 
+// Row stride of the tiled activation buffers of an M-row pass (rows per k-group).  The activation bytes a GEMM
+// workgroup reads grow with it, so it is the row count itself, not the next power of two (a 5-row verification
+// pass read 8 rows' worth).
+static int row_stride(int M) {
+    if (const char* env = getenv("ASD_RS_POW2")) { (void)env; int rs = 1; while (rs < M) rs *= 2; return rs; }
+    return M;
+}
+
 template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc) {
     const int H = e->c.head_dim;
     AttnArgs a = a0;
@@ -424,8 +432,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
     double cls_bytes[ASD_K_COUNT];
     pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // full-model totals; per-sublayer figures divide by L
     const double L = c.n_layers;
-    int RS = 1;
-    while (RS < M) RS *= 2;
+    const int RS = row_stride(M);
     ops.clear();
     auto push = [&](int type, int cls, int grid, double bytes) -> PassOp& {
         PassOp op{};
@@ -507,8 +514,7 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d
                  Profiler* profiler, int fin_mode, int fin_arg) {
     const asd_config& c = e->c;
     Prof pr{profiler, e->stream};
-    int RS = 1;
-    while (RS < M) RS *= 2;
+    const int RS = row_stride(M);
     for (const PassOp& op : ops) {
         pr.begin(op.cls, op.bytes);
         bool ok = true;
@@ -562,8 +568,7 @@ int launch_persistent(asd_engine* e, const std::vector<PassOp>& ops, const std::
         it = e->op_cache.emplace(key, std::make_pair((const PassOp*)dst, (int)ops.size())).first;
         e->ops_used += align_up(bytes);
     }
-    int RS = 1;
-    while (RS < M) RS *= 2;
+    const int RS = row_stride(M);
     PassArgs P{};
     P.ops = it->second.first; P.n_ops = it->second.second; P.M = M; P.RS = RS; P.d = c.d_model;
     P.E = e->embed; P.tokens = d_tokens; P.g_first = next_gain(e, mask, -1); P.xres = e->xres; P.xb = e->xb;

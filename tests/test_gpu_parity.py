@@ -432,3 +432,30 @@ def test_weight_stream_ring_phases_against_oracle(shape):
     for n in (1, 5, 8, 9, 16, 1):                      # packed (<= 8 rows) and two-operand passes
         check_forward(eng, orc, toks[pos:pos + n], pos, None, tol)
         pos += n
+
+
+def test_row_stride_of_the_activation_buffers_does_not_change_a_bit(monkeypatch):
+    """The tiled activation buffers of an M-row pass have a row stride of M (the bytes every GEMM workgroup reads grow
+    with it); a stride of the next power of two is only a different layout: same operands, same order, same bits."""
+    shape = MID16
+    toks = si.prompt(8, 400, shape.vocab)
+    outs = []
+    for pow2 in (False, True):
+        if pow2:
+            monkeypatch.setenv("ASD_RS_POW2", "1")
+        else:
+            monkeypatch.delenv("ASD_RS_POW2", raising=False)
+        eng = asd.Engine(asd.make_config(shape, 512)).init_synthetic(4)
+        got = []
+        eng.prefill(toks[:300])
+        pos = 300
+        for M in (3, 5, 6, 7, 9, 11, 13, 16, 1):
+            r = eng.forward(toks[pos:pos + M], pos)
+            got += [r["logits"], r["cos_rows"]]
+            pos += M
+        out, st, mask = eng.decode(int(toks[pos]), 24, 4, alpha=0.9, m=2, n=1)
+        got.append(out)
+        outs.append(got)
+        eng.close()
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
