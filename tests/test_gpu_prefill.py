@@ -78,3 +78,26 @@ def test_block_boundaries_agree_with_the_chunked_pass(n):
     a = eng.forward(toks[n:n + 3], n)["logits"]
     b = ref.forward(toks[n:n + 3], n)["logits"]
     assert rel_err(a, b).max() < TOL[shape.dtype]
+
+
+@pytest.mark.parametrize("force_w4", [False, True], ids=["default-attention", "four-waves-per-simd-attention"])
+def test_long_context_against_oracle(force_w4, monkeypatch):
+    """A context of ten 256-key groups per head on a small grouped-query model: the blocked prompt pass (five 512-row
+    blocks), then multi-row and single-row passes on top of it, against the oracle; once with the decode attention
+    variant that long contexts on large models select."""
+    if force_w4:
+        monkeypatch.setenv("ASD_ATT_W4", "1")
+    else:
+        monkeypatch.delenv("ASD_ATT_W4", raising=False)
+    shape = BF_GQA
+    n = 2500
+    eng, orc = build_pair(shape, seed=7, max_seq=n + 40)
+    toks = si.prompt(3, n + 20, shape.vocab)
+    first, acs, lg = eng.prefill(toks[:n], want_logits=True)
+    o = orc.forward(toks[:n], 0)
+    assert np.abs(acs - o["cos"]).max() < COS_TOL
+    assert rel_err(lg, o["logits"][-1]) < TOL[shape.dtype]
+    pos = n
+    for m in (7, 1, 2, 1):
+        check_forward(eng, orc, toks[pos:pos + m], pos, None, TOL[shape.dtype])
+        pos += m
