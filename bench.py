@@ -264,7 +264,10 @@ def main():
         if shape.name == "tiny":
             out["cpu_baseline"] = cpu_baseline(shape, seed, 8, 24)
         else:
-            out["cpu_baseline"] = cpu_baseline(shape, seed, 2, 6)
+            # about ten seconds of decoding on the box's 16 host threads: 40 tokens at the 7B size, fewer for larger models
+            per_tok = shape.n_layers * (shape.d_model * (shape.q_dim + 2 * shape.kv_dim) + shape.q_dim * shape.d_model
+                                        + 3 * shape.d_model * shape.d_ffn) + shape.vocab * shape.d_model
+            out["cpu_baseline"] = cpu_baseline(shape, seed, 2, max(4, int(40 * 6.6e9 / per_tok)))
     print(json.dumps(out), flush=True)
 
 
