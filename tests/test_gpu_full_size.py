@@ -100,6 +100,40 @@ def test_7b_full_benchmark_sizes_properties(eng7b):
         assert np.array_equal(one["logits"][0], a["logits"][i])
 
 
+def test_7b_long_context_benchmark_sizes_properties():
+    """The long-context workload at its full sizes (prompt 8192, 32 layers, cache sized as bench.py sizes it): output
+    equal to plain greedy decoding under the fixed masks the workload names and under the all-keep mask, the cache
+    bookkeeping, rows of a 7-row verification pass equal to single-row passes bit for bit at a context of 32 groups
+    per head, and the block prompt path against the chunked one."""
+    s = si.SHAPES["7b-long"]
+    eng = asd.Engine(asd.make_config(s, s.prompt_len + s.n_new + 16, page_tokens=256)).init_synthetic(0)
+    prompt = si.prompt(0, s.prompt_len, s.vocab)
+    N, k, L2 = 24, s.draft_len, 2 * s.n_layers
+    plain, st, _ = eng.generate(prompt, N, 0)
+    for kw in (dict(fixed_mask=si.fixed_keep_mask(s.n_layers, 2)), dict(fixed_mask=si.fixed_keep_mask(s.n_layers, 4)),
+               dict(fixed_mask=np.zeros(L2, np.uint8))):
+        out, st, mask = eng.generate(prompt, N, k, **kw)
+        assert np.array_equal(out, plain)
+        assert st["emitted"] == N == st["accepted"] + st["cycles"] + 1
+        assert eng.kv_len == s.prompt_len + N - 1
+    assert st["cycles"] == -(-(N - 1) // (k + 1)) and st["accepted"] == st["drafted"]     # all-keep: every draft accepted
+    first, acs, lg = eng.prefill(prompt, want_logits=True)
+    assert (acs <= 1.0).all() and (acs >= -1.0).all() and first == plain[0] and eng.kv_len == s.prompt_len
+    rows = np.concatenate([plain[:1], prompt[:k]]).astype(np.int32)
+    a = eng.forward(rows, s.prompt_len, commit=False)
+    b = eng.forward(rows, s.prompt_len, commit=False)
+    assert np.array_equal(a["logits"], b["logits"]) and np.array_equal(a["cos_rows"], b["cos_rows"])
+    for i in range(k + 1):
+        one = eng.forward(rows[i:i + 1], s.prompt_len + i)
+        assert np.array_equal(one["logits"][0], a["logits"][i])
+    assert int(np.argmax(a["logits"][0])) == plain[1]
+    # the two prompt paths differ in summation order only
+    first_c, acs_c, lg_c = eng.prefill(prompt[:2048], want_logits=True, chunked=True)
+    first_b, acs_b, lg_b = eng.prefill(prompt[:2048], want_logits=True)
+    assert np.abs(lg_c - lg_b).max() / np.abs(lg_b).max() < TOL and np.abs(acs_c - acs_b).max() < COS_TOL
+    eng.close()
+
+
 @pytest.mark.parametrize("name", ["13b", "70b"])
 def test_other_shapes_run_and_keep_invariants(name):
     """13B and 70B-GQA shapes at full width, reduced depth (4 layers) to keep the test short."""
