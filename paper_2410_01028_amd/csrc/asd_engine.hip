@@ -1156,6 +1156,8 @@ int asd_prefill_chunked(asd_engine* e, const int32_t* tokens, int32_t n, int32_t
 }
 
 // one draft/verify/accept cycle, enqueue only: kk draft steps with the masked model, then a (kk+1)-row verify
+#define DECODE_BURST 16      // draft-free decode cycles enqueued between two looks at the device state
+
 static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx) {
     for (int j = 0; j < kk; ++j) {
         int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_DRAFT, j);
@@ -1313,9 +1315,21 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
     double gamma = p->gamma0, ar = p->ar0;
     long mask_changes = 0;
     int emitted = 0, accepted = 0;
+    // Without drafts (and without a mask refresh) the host has nothing to decide between cycles: each one emits one
+    // token and advances the cache by one, so cycles are enqueued DECODE_BURST at a time behind one another and the
+    // host looks at the device state once per burst instead of once per token.
+    const bool lockstep = k == 0 && !refresh;
     while (emitted < n_more) {
+        const int burst = lockstep ? (n_more - emitted < DECODE_BURST ? n_more - emitted : DECODE_BURST) : 1;
+        for (int b = 0; b + 1 < burst; ++b) {
+            const int nc = chunks_for(e->kv_len + b), ctx = e->kv_len + b + 1;
+            rc = sampled ? run_captured(e, graphs, {3, 0, nc}, [&] { return enqueue_sampled_cycle(e, 0, mask.data(), nc, ctx, sa); })
+                         : run_captured(e, graphs, {0, 0, nc}, [&] { return enqueue_cycle(e, 0, mask.data(), nc, ctx); });
+            if (rc) return rc;
+        }
+        const int ahead = burst - 1;                 // cycles already enqueued in this trip
         const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
-        const int nc = chunks_for(e->kv_len + kk), ctx = e->kv_len + kk + 1;
+        const int nc = chunks_for(e->kv_len + ahead + kk), ctx = e->kv_len + ahead + kk + 1;
         int d = kk;
         if (sampled) {
             rc = run_captured(e, graphs, {3, kk, nc}, [&] { return enqueue_sampled_cycle(e, kk, mask.data(), nc, ctx, sa); });
@@ -1342,7 +1356,8 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
         CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
         if (refresh) CK(e, hipMemcpyAsync(cr.data(), e->cos_rows, cr.size() * 4, hipMemcpyDeviceToHost, e->stream));
         CK(e, hipStreamSynchronize(e->stream));
-        if (e->h_st->emitted <= emitted) return fail(e, ASD_E_STATE, "decode cycle made no progress");
+        if (e->h_st->emitted <= emitted || (lockstep && e->h_st->emitted != emitted + burst))
+            return fail(e, ASD_E_STATE, "decode cycle made no progress");
         const int a = e->h_st->accepted - accepted;
         accepted = e->h_st->accepted;
         emitted = e->h_st->emitted;
