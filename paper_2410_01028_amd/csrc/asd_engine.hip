@@ -145,7 +145,7 @@ bool config_ok(const asd_config* c, std::string* why) {
 
 // Launch shape and weight layout per GEMM class.  Tile-major keeps a tile's K range contiguous; k-major
 // keeps the fragments of all tiles for one k-block contiguous (with interleaved k-blocks per wave the
-// whole grid then sweeps one contiguous window).  Chosen by measurement on the 7B shape; ASD_TUNE
+// whole grid then sweeps one contiguous window).  Chosen by measurement on the 7B, 13B and 70B shapes; ASD_TUNE
 // (development aid) overrides, e.g. ASD_TUNE="qkv=1,8,1,1;o=1,16,0,0" (TN, NW, k-major, interleave).
 GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     GemmCfg g{};
@@ -155,9 +155,13 @@ GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     const int max1 = (tiles + units - 1) / units, max2 = ((tiles + 1) / 2 + units - 1) / units * 2;
     g.TN = (epi == EPI_LM || max2 <= max1) ? 2 : 1;      // (the LM head: two tiles per workgroup at every vocabulary size)
     g.kmajor = (cls == ASD_K_QKV || cls == ASD_K_DOWN || cls == ASD_K_LMHEAD) ? 1 : 0;
+    // Long K ranges (KB = KiB of weights per tile), measured on the 70B shape: the output projection (256 KiB per
+    // tile, 512 tiles) streams better k-major with one tile per workgroup (24.7 us against 28.7 us), the down
+    // projection (896 KiB per tile) better tile-major (73.3 us against 78.1 us); 7B and 13B sit below both limits.
+    if (cls == ASD_K_OPROJ && KB >= 256) { g.kmajor = 1; g.TN = 1; }
+    if (cls == ASD_K_DOWN && KB >= 512) g.kmajor = 0;
     g.kint = g.kmajor;
     g.NW = 8;     // every class: the persistent pass kernel runs 8-wave workgroups and must reduce in the same order
-    (void)KB;
     static const char* names[ASD_K_COUNT] = {"", "qkv", "", "o", "gu", "down", "lm", ""};       // indexed by kernel class
     if (const char* env = getenv("ASD_TUNE")) {
         std::string e(env), key = std::string(names[cls]) + "=";
