@@ -12,8 +12,8 @@
 // L2), ordered by waiting for the stores to complete before the counter is bumped; no cache-wide fence.
 // A row at position p sees keys 0..p (causal among the rows of the call as well).
 //
-// Cache page layout per (page, kv head): K[page_tokens][h] then V transposed [h][page_tokens],
-// which makes the fragments of both products contiguous 16-byte loads:
+// Cache block per (page, kv head): per 64-key chunk the K fragments, then the V^T fragments, each fragment the
+// contiguous 1 KiB register image of one load instruction (offsets: kv_k_frag_off / kv_v_frag_off):
 //   scores: A = K rows (keys x head-dim block), B = q (tiled [h/KE][16][KE]);
 //   output: A = V^T rows (head dims x key block), B = P taken straight from the score
 //   registers: a lane of group g holds, for its row, keys 4g..4g+3 of each 16-key score
@@ -60,13 +60,6 @@ struct AttnArgs {
     unsigned* arrivals;       // [n_h] groups finished per head (returns to 0)
     void* out;                // tiled activation [n_h*h]
 };
-
-// key (0..63, relative to the chunk) held by score tile kt, tile row r
-template <class T> __device__ __forceinline__ int score_key(int kt, int r);
-template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
-    return 32 * (kt >> 1) + 8 * (r >> 2) + 4 * (kt & 1) + (r & 3);    // two tiles interleave into one 32-key block
-}
-template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 
 // Merge the group partials of ATT_RB (head, row) pairs, in ascending chunk order, and write the normalised output.
 // Pair p of the n_pairs pairs of a workgroup's heads is head head0 + p / M, row p % M; this call takes pairs
@@ -255,8 +248,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     u32x4 qf[HS][NP], kf[4][HS], vf[HT][KST];
     auto request = [&]() {                  // this chunk's K and V^T fragments and the query fragments
         const int page = a.page_table[(c * ASD_CHUNK) / PT], slot0 = (c * ASD_CHUNK) % PT;
-        const E* Kp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H;
-        const E* Vp = Kp + (size_t)PT * H;
+        const E* Cp = (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H + kv_chunk_off<T>(slot0 / ASD_CHUNK, H) + lane * KE;
         const E* qp = (const E*)a.q + (size_t)(head + (col_ok ? cj : 0)) * H * a.RS;
 #pragma unroll
         for (int hs = 0; hs < HS; ++hs)
@@ -268,13 +260,12 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int hs = 0; hs < HS; ++hs)
-                kf[kt][hs] = __builtin_nontemporal_load((const u32x4*)(Kp + (size_t)(slot0 + score_key<T>(kt, r)) * H + g * KE + hs * 4 * KE));
+                kf[kt][hs] = __builtin_nontemporal_load((const u32x4*)(Cp + kv_k_frag_off<T>(kt, hs, H)));
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
-                vf[ht][ks] = __builtin_nontemporal_load(
-                    (const u32x4*)(Vp + (size_t)(ht * 16 + r) * PT + slot0 + ks * 4 * KE + g * KE));
+                vf[ht][ks] = __builtin_nontemporal_load((const u32x4*)(Cp + kv_v_frag_off<T>(ht, ks, H)));
     };
     // EARLY: the requests go out before the pass's position is known (the chunk exists in the cache whatever the
     // position; a chunk beyond the position is then dropped unused), which takes the position's load and the
@@ -441,29 +432,27 @@ __global__ __launch_bounds__(256, 1) void pf_attn_kernel(const PfAttnArgs a) {
     }
 
     u32x4 kf[4][HS], vf[HT][KST];
-    auto chunk_base = [&](int kcv) {        // K rows of chunk kc; V^T follows PT * H elements after the page's K
+    auto chunk_base = [&](int kcv) {        // this lane's pointer into chunk kc of the cache block (K fragments, then V^T fragments)
         // the chunk index is the same in every lane: as a scalar read through the constant address space (nothing
         // writes the page table while a pass runs) the page lookup is a scalar load, outside the vector loads' queue
         typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
         const int kc = __builtin_amdgcn_readfirstlane(kcv);
         const int page = ((const_i32_ptr)(uintptr_t)a.page_table)[(kc * ASD_CHUNK) / PT], slot0 = (kc * ASD_CHUNK) % PT;
-        return (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H + (size_t)slot0 * H;
+        return (const E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * H + kv_chunk_off<T>(slot0 / ASD_CHUNK, H) + lane * KE;
     };
     auto issue_k = [&](const E* Kc) {
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
             for (int hs = 0; hs < HS; ++hs)
-                kf[kt][hs] = *(const u32x4*)(Kc + (size_t)score_key<T>(kt, r) * H + g * KE + hs * 4 * KE);
+                kf[kt][hs] = *(const u32x4*)(Kc + kv_k_frag_off<T>(kt, hs, H));
     };
-    auto issue_v = [&](const E* Kc, int kc) {
-        const int slot0 = (kc * ASD_CHUNK) % PT;
-        const E* Vc = Kc - (size_t)slot0 * H + (size_t)PT * H + slot0;
+    auto issue_v = [&](const E* Kc, int) {
 #pragma unroll
         for (int ht = 0; ht < HT; ++ht)
 #pragma unroll
             for (int ks = 0; ks < KST; ++ks)
-                vf[ht][ks] = *(const u32x4*)(Vc + (size_t)(ht * 16 + r) * PT + ks * 4 * KE + g * KE);
+                vf[ht][ks] = *(const u32x4*)(Kc + kv_v_frag_off<T>(ht, ks, H));
     };
     auto one_chunk = [&](const int kc, auto has_next) {
         constexpr bool more = decltype(has_next)::value;

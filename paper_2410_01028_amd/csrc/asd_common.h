@@ -7,10 +7,12 @@
 //      lane = 16*g + r holds row 16*tile + r, k = kb*4*KE + g*KE .. +KE   (K padded with 0 to KB*4*KE)
 //    so that one wave reads one contiguous KiB per step and a tile's K range is
 //    one contiguous stream in HBM;
-//  * tiled activation X[rows][K] -> [K/KE][RS][KE] with RS = the pass's row stride (the power of two
-//    >= its row count): the fragment of k-block kb for lane 16*g + m is the 16 bytes at
-//    ((kb*4 + g)*RS + m)*KE; lanes of unused rows supply zeros instead of loading, so a one-row pass
-//    reads 64 bytes of activations per KiB of weights.
+//  * tiled activation X[rows][K] -> [K/KE][RS][KE] with RS = the pass's row stride (its row count): the
+//    fragment of k-block kb for lane 16*g + m is the 16 bytes at ((kb*4 + g)*RS + m)*KE; lanes of unused
+//    rows read row 0 (their columns of the products are never looked at), so a one-row pass reads 64 bytes
+//    of activations per KiB of weights;
+//  * KV cache: per (page, KV head) and 64-key chunk the K fragments, then the V^T fragments, each the
+//    contiguous 1 KiB register image of one attention load (see kv_k_off / kv_v_off below).
 //
 // MFMA operand use: A = weights (16 output features x k-block), B = activations
 // (k-block x 16 rows), D[n][m]: lane 16*g + m holds n = 4*g + j in register j.
@@ -49,6 +51,45 @@ struct F32 {
     static __device__ __forceinline__ float to_f32(float v) { return v; }
     static __device__ __forceinline__ float from_f32(float f) { return f; }
 };
+
+// ---- KV cache block of one (page, KV head): page_tokens / 64 chunks of 64 keys; a chunk holds its K fragments, then
+// its V^T fragments, and a fragment is the 1 KiB register image of one load instruction (lane 16g + r holds KE
+// consecutive elements), so that every attention load reads one contiguous KiB (whole cache lines: a compute unit's
+// load path is bound by the number of lines an instruction touches, and 64-byte row segments cost twice as many):
+//   K fragment (kt, hs):   lane (g, r) = key score_key(kt, r) of the chunk, head dims hs * 4KE + g * KE ...
+//   V^T fragment (ht, ks): lane (g, r) = head dim ht * 16 + r, keys ks * 4KE + g * KE ... of the chunk
+// key (0..63, relative to the chunk) held by score tile kt, tile row r: chosen per storage type so that the score
+// registers of a lane are exactly the keys of one V^T fragment's lane
+template <class T> __device__ __forceinline__ int score_key(int kt, int r);
+template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
+    return 32 * (kt >> 1) + 8 * (r >> 2) + 4 * (kt & 1) + (r & 3);    // two tiles interleave into one 32-key block
+}
+template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
+// the inverse: score tile and tile row of a chunk's key
+template <class T> __device__ __forceinline__ void score_tile_of(int key, int* kt, int* r);
+template <> __device__ __forceinline__ void score_tile_of<BF16>(int key, int* kt, int* r) {
+    *kt = 2 * (key >> 5) + ((key >> 2) & 1); *r = 4 * ((key >> 3) & 3) + (key & 3);
+}
+template <> __device__ __forceinline__ void score_tile_of<F32>(int key, int* kt, int* r) { *kt = key >> 4; *r = key & 15; }
+// element offsets inside a block (h = head dim, slot = token slot in the page)
+template <class T> __device__ __forceinline__ size_t kv_chunk_off(int chunk_in_page, int h) { return (size_t)chunk_in_page * 2 * ASD_CHUNK * h; }
+template <class T> __device__ __forceinline__ size_t kv_k_frag_off(int kt, int hs, int h) {      // + lane * KE
+    return (size_t)(kt * (h / (4 * T::KE)) + hs) * 64 * T::KE;
+}
+template <class T> __device__ __forceinline__ size_t kv_v_frag_off(int ht, int ks, int h) {      // + lane * KE
+    return (size_t)ASD_CHUNK * h + (size_t)(ht * (ASD_CHUNK / (4 * T::KE)) + ks) * 64 * T::KE;
+}
+template <class T> __device__ __forceinline__ size_t kv_k_off(int slot, int dim, int h) {
+    constexpr int KE = T::KE;
+    int kt, r;
+    score_tile_of<T>(slot % ASD_CHUNK, &kt, &r);
+    return kv_chunk_off<T>(slot / ASD_CHUNK, h) + kv_k_frag_off<T>(kt, dim / (4 * KE), h) + (size_t)(((dim / KE) & 3) * 16 + r) * KE + dim % KE;
+}
+template <class T> __device__ __forceinline__ size_t kv_v_off(int slot, int dim, int h) {
+    constexpr int KE = T::KE;
+    const int key = slot % ASD_CHUNK;
+    return kv_chunk_off<T>(slot / ASD_CHUNK, h) + kv_v_frag_off<T>(dim >> 4, key / (4 * KE), h) + (size_t)(((key / KE) & 3) * 16 + (dim & 15)) * KE + key % KE;
+}
 
 // acc[n][m] += sum over the k-block of A[n][k] * B[k][m]; both fragments use the same lane -> k map.
 template <class T> __device__ __forceinline__ void mma16(f32x4& acc, const u32x4& a, const u32x4& b);

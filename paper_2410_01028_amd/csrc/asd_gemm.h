@@ -313,13 +313,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
                 const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
                 const int PT = a.page_tokens, page = a.page_table[pos / PT], slot = pos % PT;
                 E* base = (E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * a.h;
-                if (isk) {                       // K[slot][h]
-                    st_elem<T, COH>(base + (size_t)slot * a.h + i, T::from_f32(v0));
-                    st_elem<T, COH>(base + (size_t)slot * a.h + i + hh, T::from_f32(v1));
-                } else {                         // V transposed: [h][slot]
-                    base += (size_t)PT * a.h;
-                    st_elem<T, COH>(base + (size_t)i * PT + slot, T::from_f32(v0));
-                    st_elem<T, COH>(base + (size_t)(i + hh) * PT + slot, T::from_f32(v1));
+                if (isk) {                       // into the chunk's K fragments
+                    st_elem<T, COH>(base + kv_k_off<T>(slot, i, a.h), T::from_f32(v0));
+                    st_elem<T, COH>(base + kv_k_off<T>(slot, i + hh, a.h), T::from_f32(v1));
+                } else {                         // into the chunk's V^T fragments
+                    st_elem<T, COH>(base + kv_v_off<T>(slot, i, a.h), T::from_f32(v0));
+                    st_elem<T, COH>(base + kv_v_off<T>(slot, i + hh, a.h), T::from_f32(v1));
                 }
             }
         }

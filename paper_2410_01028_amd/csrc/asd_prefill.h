@@ -217,12 +217,11 @@ __global__ __launch_bounds__(NW * 64, PD >= 2 ? 2 : 1) void pf_gemm_kernel(const
                     const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
                     const int PT = a.page_tokens, page = a.page_table[pos / PT], slot = pos % PT;
                     E* base = (E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * a.h;
-                    if (isk) {
-                        store_elem4<T>(base + (size_t)slot * a.h + dim, v);
+                    if (isk) {                   // dim is a multiple of 4: the four values stay inside one lane's KE elements
+                        store_elem4<T>(base + kv_k_off<T>(slot, dim, a.h), v);
                     } else {
-                        base += (size_t)PT * a.h;
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) base[(size_t)(dim + j) * PT + slot] = T::from_f32(v[j]);
+                        for (int j = 0; j < 4; ++j) base[kv_v_off<T>(slot, dim + j, a.h)] = T::from_f32(v[j]);
                     }
                 }
             }
