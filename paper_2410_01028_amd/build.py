@@ -14,6 +14,8 @@ FLAGS = [
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-result", "-Wno-unused-value",
+    # leading scalar kernel arguments arrive in SGPRs with the wave instead of through a load from the argument segment
+    "-mllvm", "-amdgpu-kernarg-preload-count=16",
 ]
 
 

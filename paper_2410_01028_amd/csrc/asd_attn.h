@@ -343,8 +343,19 @@ __device__ __forceinline__ bool attn_unit(const AttnArgs& a, int* grp, int* head
 }
 __host__ __device__ inline int attn_grid(int n_h, int n_kv, int groups, int gh) { return (n_kv * groups + 7) / 8 * 8 * (n_h / n_kv / gh); }
 
+// The leading scalar parameters of the two kernels repeat what a wave needs before its first requests: built with
+// kernel-argument preloading they arrive in SGPRs with the wave, while the argument structure comes from memory.
+// heads = n_h | n_kv << 16, rows = M | RS << 8 | gh << 16.
+#define ATT_HOT_PARAMS const void* q, const void* kv, const int32_t* page_table, int64_t q_plane, int32_t heads, int32_t rows, \
+                       int32_t grid_groups, int32_t cap_chunks, int32_t page_tokens, int32_t
+#define ATT_HOT_ARGS(a0)                                                                                                   \
+    AttnArgs a = a0;                                                                                                       \
+    a.q = q; a.kv = kv; a.page_table = page_table; a.q_plane = q_plane; a.n_h = heads & 0xffff; a.n_kv = heads >> 16;      \
+    a.M = rows & 255; a.RS = (rows >> 8) & 255; a.gh = rows >> 16; a.grid_groups = grid_groups; a.cap_chunks = cap_chunks; \
+    a.page_tokens = page_tokens;
 template <class T, int H>
-__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(ATT_HOT_PARAMS, const AttnArgs a0) {
+    ATT_HOT_ARGS(a0)
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
@@ -359,7 +370,8 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(const AttnArgs a) {
 // then no longer keeps all of a chunk's K and V^T fragments in flight at once, but every group of a long context is
 // resident at once (one round of workgroups instead of two).  Same arithmetic, same bits; chosen by the grid size.
 template <class T, int H>
-__global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(const AttnArgs a) {
+__global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(ATT_HOT_PARAMS, const AttnArgs a0) {
+    ATT_HOT_ARGS(a0)
     __shared__ float so[ATT_GW * ATT_RH * H];
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;

@@ -333,10 +333,16 @@ template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, i
 #endif
 template <class T, int EPI, int TN, int NW>
 void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
+    // (the leading arguments: what the first requests need, preloaded into SGPRs; see gemm_kernel)
+    const int32_t packed = a.k_interleave | (a.M << 8) | (a.RS << 16);
+    const int32_t wts = (int32_t)a.w_tile_stride, wks = (int32_t)a.w_kb_stride;
     if constexpr (T::NP == 2) {          // two-plane activations: passes of at most 8 rows pack both planes into one operand
-        if (a.M <= 8) { gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, true><<<grid, NW * 64, 0, s>>>(a); return; }
+        if (a.M <= 8) {
+            gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, true><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
+            return;
+        }
     }
-    gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, false><<<grid, NW * 64, 0, s>>>(a);
+    gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, false><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
 }
 
 template <class T, int EPI>
@@ -376,13 +382,16 @@ template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc)
     const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups, a.gh);
     // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
     const bool many = (long)a.grid_groups * units > 512 || e->force_att_w4;
+    // (the leading arguments: what the first requests need, preloaded into SGPRs; see attn_kernel)
+#define ATT_HOT a.q, a.kv, a.page_table, a.q_plane, a.n_h | (a.n_kv << 16), a.M | (a.RS << 8) | (a.gh << 16), a.grid_groups, a.cap_chunks, a.page_tokens, 0
 #define ATT(h)                                                                          \
     if (H == h) {                                                                       \
-        if (many) attn_kernel_w4<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);         \
-        else attn_kernel<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(a);                 \
+        if (many) attn_kernel_w4<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(ATT_HOT, a); \
+        else attn_kernel<T, h><<<grid, ATT_GW * 64, 0, e->stream>>>(ATT_HOT, a);         \
     }
     ATT(32) ATT(64) ATT(128)
 #undef ATT
+#undef ATT_HOT
 }
 void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
     if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
