@@ -161,7 +161,14 @@ GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     if (cls == ASD_K_OPROJ && KB >= 256) { g.kmajor = 1; g.TN = 1; }
     if (cls == ASD_K_DOWN && KB >= 512) g.kmajor = 0;
     g.kint = g.kmajor;
-    g.NW = 8;     // every class: the persistent pass kernel runs 8-wave workgroups and must reduce in the same order
+    // Waves per workgroup: 8, except where a launch has more workgroups than two rounds of 8-wave workgroups can
+    // hold at once and its waves finish far apart (QKV; gate/up with two tile pairs per workgroup): there 4 waves with
+    // twice the loads in flight each (the same bytes per workgroup, half the waves to join) measured 1-4 % faster per
+    // launch on the 7B, 13B and 70B shapes.  The persistent pass kernel (ASD_PERSIST) runs 8-wave workgroups and must
+    // reduce in the same order, so it keeps 8 everywhere.
+    const char* pe = getenv("ASD_PERSIST");
+    const bool want_persist = pe && atoi(pe) > 0;
+    g.NW = (!want_persist && (cls == ASD_K_QKV || (cls == ASD_K_GATEUP && g.TN == 2))) ? 4 : 8;
     static const char* names[ASD_K_COUNT] = {"", "qkv", "", "o", "gu", "down", "lm", ""};       // indexed by kernel class
     if (const char* env = getenv("ASD_TUNE")) {
         std::string e(env), key = std::string(names[cls]) + "=";
@@ -333,16 +340,18 @@ template <class T> void launch_tile(asd_engine* e, const void* src, void* dst, i
 #endif
 template <class T, int EPI, int TN, int NW>
 void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
+    // four-wave workgroups keep twice the weight fragments in flight per wave: the same bytes per workgroup
+    constexpr int UU = NW == 4 ? 2 * ASD_GEMM_U : ASD_GEMM_U;
     // (the leading arguments: what the first requests need, preloaded into SGPRs; see gemm_kernel)
     const int32_t packed = a.k_interleave | (a.M << 8) | (a.RS << 16);
     const int32_t wts = (int32_t)a.w_tile_stride, wks = (int32_t)a.w_kb_stride;
     if constexpr (T::NP == 2) {          // two-plane activations: passes of at most 8 rows pack both planes into one operand
         if (a.M <= 8) {
-            gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, true><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
+            gemm_kernel<T, EPI, TN, NW, UU, true><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
             return;
         }
     }
-    gemm_kernel<T, EPI, TN, NW, ASD_GEMM_U, false><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
+    gemm_kernel<T, EPI, TN, NW, UU, false><<<grid, NW * 64, 0, s>>>(a.W, a.X, wts, wks, a.n_tiles, a.KB, packed, 0, a.x_plane, a.W2, a);
 }
 
 template <class T, int EPI>

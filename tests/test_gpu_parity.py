@@ -304,7 +304,10 @@ def test_graph_replays_match_eager():
 
 def test_persistent_pass_kernel_matches_step_kernels_bitwise(monkeypatch):
     """The one-launch-per-pass kernel (development switch ASD_PERSIST) runs the same block functions with
-    coherent accesses and grid barriers: logits, cosines and generated tokens must equal the per-step path."""
+    coherent accesses and grid barriers: logits, cosines and generated tokens must equal the per-step path.  The
+    persistent kernel's workgroups have 8 waves; the per-step engine is pinned to the same split of K (its QKV launch
+    would otherwise take 4 waves per workgroup, which sums a row's K range in a different order)."""
+    monkeypatch.setenv("ASD_TUNE", "qkv=1,8,1,1")
     shape = MID16
     toks = si.prompt(8, 150, shape.vocab)
     mask = np.zeros(2 * shape.n_layers, np.uint8); mask[1] = mask[4] = 1
