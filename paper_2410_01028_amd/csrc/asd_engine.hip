@@ -389,8 +389,13 @@ template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc)
     if (!e->att_gh1) while (a.gh * 2 * a.RS <= ASD_ROWS && a.gh * 2 <= e->c.n_heads / e->c.n_kv_heads && (e->c.n_heads / e->c.n_kv_heads) % (a.gh * 2) == 0) a.gh *= 2;
     const int units = e->c.n_heads / a.gh;                    // workgroups per group index
     const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups, a.gh);
-    // more workgroups than two per SIMD can hold at once (256 units x 2): the variant that fits four
-    const bool many = (long)a.grid_groups * units > 512 || e->force_att_w4;
+    // The first variant holds 512 workgroups at once (two per compute unit) and keeps all of a chunk's loads in flight;
+    // the four-waves-per-SIMD variant holds 1024.  It wins only where it takes the whole grid in one round while the
+    // first variant would be left with a small second one (measured, 7B: 21.7 against 23.2 us at 544 workgroups);
+    // beyond 1024 workgroups both run in rounds and the first is faster per byte (36 against 40 us at 1056,
+    // 60 against 69 us at 2080, 110 against 115 us at 4128).
+    const long n_wg = (long)a.grid_groups * units;
+    const bool many = (n_wg > 512 && n_wg <= 1024) || e->force_att_w4;
     // (the leading arguments: what the first requests need, preloaded into SGPRs; see attn_kernel)
 #define ATT_HOT a.q, a.kv, a.page_table, a.q_plane, a.n_h | (a.n_kv << 16), a.M | (a.RS << 8) | (a.gh << 16), a.grid_groups, a.cap_chunks, a.page_tokens, 0
 #define ATT(h)                                                                          \
