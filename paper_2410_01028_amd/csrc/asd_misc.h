@@ -61,13 +61,28 @@ template <bool COH>
 __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
                                              DevState* st, int32_t* tokbuf, int32_t* out, int* win) {
     const int tid = threadIdx.x, lane = tid & 63, nw = blockDim.x >> 6;
+    // what the accept step reads is requested now, so that it is there when the rows' winners are known
+    int tb[16], st_emitted = 0, st_target = 0;
+    if (tid == 0 && mode == FIN_ACCEPT) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) tb[q] = q <= j_or_kk ? tokbuf[q] : 0;
+        st_emitted = st->emitted; st_target = st->target;
+    }
     for (int m = tid >> 6; m < M; m += nw) {
         float v = -INFINITY; int idx = 0x7fffffff;
-        for (int p = lane; p < P; p += 64) {
-            AmaxCand c;
-            c.v = ld_f32<COH>(&cand[(size_t)p * 16 + m].v);
-            c.i = __float_as_int(ld_f32<COH>((const float*)&cand[(size_t)p * 16 + m].i));
-            if (amax_better(c.v, c.i, v, idx)) { v = c.v; idx = c.i; }
+        // eight candidates per lane and trip, all requested before the first is looked at (one memory round trip per
+        // trip instead of one per candidate); a lane past the end re-reads the last candidate, which changes nothing
+        for (int p0 = lane; p0 < P; p0 += 64 * 8) {
+            float cv[8]; int ci[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + 64 * u < P ? p0 + 64 * u : P - 1;
+                cv[u] = ld_f32<COH>(&cand[(size_t)p * 16 + m].v);
+                ci[u] = __float_as_int(ld_f32<COH>((const float*)&cand[(size_t)p * 16 + m].i));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (amax_better(cv[u], ci[u], v, idx)) { v = cv[u]; idx = ci[u]; }
         }
         for (int o = 32; o > 0; o >>= 1) {
             const float ov = __shfl_xor(v, o); const int oi = __shfl_xor(idx, o);
@@ -77,8 +92,18 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
         if (mode == FIN_DRAFT && m == 0) {
             // confidence of the drafted token: 1 / sum_i exp(logit_i - max), from the per-workgroup sums
             float se = 0.f;
-            for (int p = lane; p < P; p += 64)
-                se += ld_f32<COH>(&cand[(size_t)p * 16].s) * __expf(ld_f32<COH>(&cand[(size_t)p * 16].v) - v);
+            for (int p0 = lane; p0 < P; p0 += 64 * 8) {          // ascending p per lane, as before; requests batched
+                float cs[8], cv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int p = p0 + 64 * u < P ? p0 + 64 * u : P - 1;
+                    cs[u] = ld_f32<COH>(&cand[(size_t)p * 16].s);
+                    cv[u] = ld_f32<COH>(&cand[(size_t)p * 16].v);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (p0 + 64 * u < P) se += cs[u] * __expf(cv[u] - v);
+            }
             for (int o = 32; o > 0; o >>= 1) se += __shfl_xor(se, o);
             if (lane == 0) st->conf = 1.f / se;
         }
@@ -90,10 +115,10 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
     } else if (mode == FIN_ACCEPT) {
         const int kk = j_or_kk;
         int a = 0;
-        while (a < kk && tokbuf[a + 1] == win[a]) ++a;
-        int e = st->emitted;
-        for (int q = 1; q <= a && e < st->target; ++q) out[e++] = tokbuf[q];
-        if (e < st->target) out[e++] = win[a];
+        while (a < kk && tb[a + 1] == win[a]) ++a;
+        int e = st_emitted;
+        for (int q = 1; q <= a && e < st_target; ++q) out[e++] = tb[q];
+        if (e < st_target) out[e++] = win[a];
         st->emitted = e;
         st->pos += a + 1;
         st->cycles += 1; st->drafted += kk; st->accepted += a;
