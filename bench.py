@@ -200,7 +200,7 @@ def main():
     out["roofline"] = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(achieved / HBM_PEAK_GBS, 4),
                        "traffic": read_traffic(os.path.join(ROOT, "profiles", f"gemm_gateup_{shape.name}_hbm_traffic.txt")),
-                       "kernel": "gemm_kernel<BF16, EPI_GU> (gate/up projection + SiLU*mul)",
+                       "kernel": f"gemm_kernel<{'BF16' if shape.dtype else 'F32'}, EPI_GU> (gate/up projection + SiLU*mul)",
                        "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(gu_us, 2)}
     # every class inside a pass, an event pair around each launch (includes the event overhead of ~2 us)
     out["kernels"] = {n: {"avg_us": round(v["ms"] / v["launches"] * 1e3, 2),
