@@ -46,6 +46,7 @@ enum {
 };
 
 #define ASD_MAX_ROWS 16   /* rows per forward call: draft length k <= 15 */
+#define ASD_MAX_SEQ 65536  /* cache capacity in positions */
 
 typedef struct asd_engine asd_engine;   /* opaque, library-owned host object */
 
@@ -53,7 +54,9 @@ typedef struct asd_engine asd_engine;   /* opaque, library-owned host object */
  * Model and cache shape.  Constraints (else ASD_E_INVAL): d_model, d_ffn, vocab,
  * n_heads*head_dim multiples of 16; head_dim 32, 64 or 128; n_heads a multiple
  * of n_kv_heads; page_tokens a multiple of 64; 1 <= max_rows <= ASD_MAX_ROWS;
- * max_seq >= 1 (rounded up to whole pages).
+ * max_seq >= 1 (rounded up to whole pages), and the rounded capacity at most
+ * ASD_MAX_SEQ positions (the decode-attention merge holds the statistics of at
+ * most 256 groups of 256 keys per head).
  * dtype is the storage type of weights and of the KV cache and the operand type
  * of the matrix cores (with bf16, activations go in as a hi + lo pair of bf16
  * values); the residual stream and every accumulation are fp32.
@@ -63,7 +66,27 @@ typedef struct {
     int32_t max_seq, page_tokens, max_rows;
     int32_t dtype;              /* ASD_DT_F32 or ASD_DT_BF16 */
     float rms_eps, rope_theta;  /* 1e-5, 1e4 for Llama-2 */
+    uint32_t debug_flags;       /* ASD_DBG_* bits; 0 in production */
+    const char* debug_tune;     /* launch-shape overrides (see below); NULL in production */
 } asd_config;
+
+/*
+ * Development and test switches, all explicit in the configuration (the library reads no environment
+ * variable and keeps no global state).  None of them changes what is computed; the tests use them to
+ * show that alternative launch shapes give the same bits.
+ *   ASD_DBG_ATT_W4      always launch the decode-attention variant compiled for four waves per SIMD
+ *   ASD_DBG_ATT_GH1     one query head per decode-attention workgroup also for grouped-query models
+ *   ASD_DBG_RS_POW2     row stride of the activation buffers = next power of two >= rows (default: rows)
+ *   ASD_DBG_SAMPLE_MEM  sampling kernels that re-read their logit rows from memory
+ *   ASD_DBG_STEP_KERNELS  one launch per step for every pass (default: one dataflow launch per pass
+ *                       where that path applies; the two differ only in launch structure)
+ * debug_tune: "name=a,b,c,d;..." with name in {qkv, o, gu, down, lm}: tiles per workgroup, waves per
+ * workgroup, k-major layout (0/1), interleaved k-blocks (0/1); and name in {pf_qkv, pf_o, pf_gu,
+ * pf_down}: 16-row chunks per workgroup, K slices[, prefetch depth] of the prompt-block GEMMs.  A
+ * layout override changes how weights are tiled in the arena, never their values.  The string is
+ * copied by asd_create.
+ */
+enum { ASD_DBG_ATT_W4 = 1, ASD_DBG_ATT_GH1 = 2, ASD_DBG_RS_POW2 = 4, ASD_DBG_SAMPLE_MEM = 8, ASD_DBG_STEP_KERNELS = 16 };
 
 /*
  * Parameters of speculative generation.  alpha, m, n are Algorithm 1's inputs
@@ -74,8 +97,8 @@ typedef struct {
  * mask_mode 1: fixed_mask [2L] is used as given;
  * mask_mode 2: as 0, then the mask is rebuilt after every verification pass from
  *   the running ACS over the prompt rows and all rows committed since (the
- *   verification pass is a full-model pass, so its accepted rows extend Eq. 2's
- *   average); an extension, the paper builds the draft model once per prompt.
+ *   verification pass is a full-model pass, so its accepted rows extend the average
+ *   that Section 3.2 defines as C_l); an extension, the paper builds the draft model once per prompt.
  * use_graphs != 0 replays each draft/verify cycle as a captured HIP graph.
  * use_cs_mlp != 0 also removes MLP sublayers whose ACS reaches alpha_mlp (subject
  *   to rule 2); an extension, Algorithm 1 thresholds attention sublayers only.
@@ -120,12 +143,20 @@ typedef struct {
 } asd_gen_params;
 
 /* Counters of one asd_decode / asd_generate call (emitted includes the first token for asd_generate);
- * gamma, ar: final values of the adaptive draft exit; mask_changes: rebuilds that changed the mask. */
+ * gamma, ar: final values of the adaptive draft exit; mask_changes: rebuilds that changed the mask.
+ * ms_decode is host wall time of the whole decode call.  ms_draft / ms_verify are GPU time of the draft
+ * passes and of the verification passes (accept / rollback included), from HIP events recorded on the
+ * engine's stream between the phases of every cycle; ms_other = ms_decode - ms_draft - ms_verify (host
+ * decisions, the per-cycle read of the decoding state, idle gaps).  bytes_draft / bytes_verify are the
+ * algorithmic bytes those passes had to read (kept sublayers' weights, LM head, K/V of the visible
+ * context), summed over the call. */
 typedef struct {
     int64_t cycles, drafted, accepted, emitted;
     double ms_prefill, ms_decode;
     int64_t mask_changes;
     double gamma, ar;
+    double ms_draft, ms_verify, ms_other;
+    double bytes_draft, bytes_verify;
 } asd_gen_stats;
 
 /* Per-kernel-class GPU time of one profiled forward pass, from HIP events on the engine's stream. */
@@ -196,7 +227,7 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
                 int32_t commit, float* logits, float* cos, float* cos_rows, int32_t* argmax);
 
 /*
- * Prompt pass (Section 3.2, Eq. 1-2): resets the cache, runs all n prompt tokens
+ * Prompt pass (Section 3.2, the definition of C_l): resets the cache, runs all n prompt tokens
  * through the full model, returns the first generated token, the ACS of every
  * sublayer over the n rows (cos_out [2L], optional) and the logits of the last row
  * (last_logits [vocab], optional).  The ACS is kept in the engine for a following

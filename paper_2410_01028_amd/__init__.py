@@ -17,6 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libasd.so")
 OK, E_INVAL, E_STATE, E_NOMEM, E_IO, E_HIP = 0, -1, -2, -3, -4, -5
 DT_F32, DT_BF16 = 0, 1
 MAX_ROWS = 16
+MAX_SEQ = 65536
+# development / test switches of Config.debug_flags (none changes what is computed)
+DBG_ATT_W4, DBG_ATT_GH1, DBG_RS_POW2, DBG_SAMPLE_MEM, DBG_STEP_KERNELS = 1, 2, 4, 8, 16
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "finish")
 
 
@@ -30,7 +33,8 @@ class Config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab",
                  "max_seq", "page_tokens", "max_rows", "dtype")] + \
-               [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float)]
+               [("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
+                ("debug_flags", ctypes.c_uint32), ("debug_tune", ctypes.c_char_p)]
 
 
 class GenParams(ctypes.Structure):
@@ -45,7 +49,8 @@ class GenParams(ctypes.Structure):
 class GenStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("cycles", "drafted", "accepted", "emitted")] + \
                [("ms_prefill", ctypes.c_double), ("ms_decode", ctypes.c_double), ("mask_changes", ctypes.c_int64),
-                ("gamma", ctypes.c_double), ("ar", ctypes.c_double)]
+                ("gamma", ctypes.c_double), ("ar", ctypes.c_double)] + \
+               [(n, ctypes.c_double) for n in ("ms_draft", "ms_verify", "ms_other", "bytes_draft", "bytes_verify")]
 
 
 PREFILL_CLASSES = ("rows", "qkv", "attn", "oproj", "gateup", "down", "lmhead")
@@ -105,10 +110,12 @@ def lib():
     return _lib
 
 
-def make_config(shape, max_seq: int, page_tokens: int = 64, max_rows: int = MAX_ROWS) -> Config:
+def make_config(shape, max_seq: int, page_tokens: int = 64, max_rows: int = MAX_ROWS, debug_flags: int = 0,
+                debug_tune: str | None = None) -> Config:
     """Config from any object with the shape fields (n_layers, d_model, ..., dtype, rms_eps, rope_theta)."""
     return Config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
-                  shape.vocab, max_seq, page_tokens, max_rows, shape.dtype, shape.rms_eps, shape.rope_theta)
+                  shape.vocab, max_seq, page_tokens, max_rows, shape.dtype, shape.rms_eps, shape.rope_theta,
+                  debug_flags, None if debug_tune is None else debug_tune.encode())
 
 
 def arena_bytes(cfg: Config) -> int:
@@ -284,7 +291,8 @@ class Engine:
     @staticmethod
     def _stats(st: GenStats) -> dict:
         return {k: getattr(st, k) for k in ("cycles", "drafted", "accepted", "emitted", "ms_prefill", "ms_decode",
-                                            "mask_changes", "gamma", "ar")}
+                                            "mask_changes", "gamma", "ar", "ms_draft", "ms_verify", "ms_other",
+                                            "bytes_draft", "bytes_verify")}
 
     # ---- measurement
     def time_pass(self, n_rows: int, skip=None, reps: int = 20, use_graph: bool = True):

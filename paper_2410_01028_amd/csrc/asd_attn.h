@@ -254,7 +254,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         for (int hs = 0; hs < HS; ++hs)
 #pragma unroll
             for (int pl = 0; pl < NP; ++pl)
-                qf[hs][pl] = col_ok ? ld_frag<COH>((const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + cm) * KE))
+                qf[hs][pl] = col_ok ? *(const u32x4*)(qp + pl * a.q_plane + ((size_t)(hs * 4 + g) * a.RS + cm) * KE)
                                     : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt)
@@ -332,8 +332,8 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
 // each XCD has its own L2: the query heads that share a KV head (grouped-query attention) read the same K/V, so the
 // workgroups of one (KV head, group) pair get consecutive slots of ONE XCD and its K/V crosses the fabric once instead
 // of once per query head; successive pairs go to successive XCDs.  Returns false for the padding workgroups of the last round.
-__device__ __forceinline__ bool attn_unit(const AttnArgs& a, int* grp, int* head) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, G = a.n_h / a.n_kv, U = G / a.gh;   // U workgroups per pair
+__device__ __forceinline__ bool attn_unit(const AttnArgs& a, const int index, int* grp, int* head) {
+    const int xcd = index & 7, slot = index >> 3, G = a.n_h / a.n_kv, U = G / a.gh;   // U workgroups per pair
     const int pair = (slot / U) * 8 + xcd;
     if (pair >= a.n_kv * a.grid_groups) return false;
     // pairs in group-major order: the launch sweeps the cache page by page (a page's KV heads are neighbours in
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(ATT_HOT_PARAMS, const
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
     int grp, head;
-    if (!attn_unit(a, &grp, &head)) return;
+    if (!attn_unit(a, blockIdx.x, &grp, &head)) return;
     // (a group no row of this call sees does nothing: every wave of it is inactive, and a context of one group
     // returns before the arrival)
     attn_group<T, H, false, true>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
@@ -378,7 +378,7 @@ __global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(ATT_HOT_PARAMS,
     __shared__ float sml[ATT_GW * ASD_ROWS * 2];
     __shared__ unsigned s_old;
     int grp, head;
-    if (!attn_unit(a, &grp, &head)) return;
+    if (!attn_unit(a, blockIdx.x, &grp, &head)) return;
     if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
     attn_group<T, H, false>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
 }

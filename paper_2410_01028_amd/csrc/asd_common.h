@@ -168,4 +168,8 @@ struct DevState {
     int32_t cycles, drafted, accepted;
     float conf;         // top-1 probability of the token the last draft step produced (softmax of its logits)
     int32_t index_base; // sampled decoding: output index of the first token this decode call emits
+    int32_t err;        // DEV_ERR_* bits raised by kernels since the state was last set (checked by the host at its next read)
 };
+// a token id outside the vocabulary reached the embedding (it was replaced by token 0); a row's logits held no
+// finite maximum (NaN / Inf weights: the row's greedy token was replaced by token 0)
+enum { DEV_ERR_TOKEN = 1, DEV_ERR_LOGITS = 2 };

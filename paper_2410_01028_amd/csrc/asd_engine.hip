@@ -5,8 +5,8 @@
 #include "asd_attn.h"
 #include "asd_common.h"
 #include "asd_gemm.h"
+#include "asd_flow.h"
 #include "asd_misc.h"
-#include "asd_persist.h"
 #include "asd_prefill.h"
 #include "asd_sample.h"
 
@@ -38,6 +38,11 @@ struct Profiler {
     std::vector<int> cls;
     std::vector<double> bytes;
 };
+
+// a pass's step table in device memory (dataflow kernel)
+struct FlowTable { const PassOp* ops; const uint16_t* op_of_block; int n_ops, n_blocks; };
+// sizes of the dataflow kernel's per-step buffers and tables (see flow_sizes)
+struct FlowSizes { size_t ws_bytes; int max_ops, max_blocks; size_t act_d, act_q, act_f, q_bytes, xres, part, ssq; };
 
 }  // namespace
 
@@ -86,21 +91,25 @@ struct asd_engine {
     bool acs_valid;
     DevState* h_st;                     // pinned
     std::map<std::vector<int>, hipGraphExec_t> graphs;
-    // persistent pass kernel
-    bool persistent;
-    int pass_grid;
-    char* ops_region;
-    size_t ops_bytes, ops_used;
-    std::map<std::vector<int>, std::pair<const PassOp*, int>> op_cache;
-    unsigned long long* bar;
-    unsigned long long bar_count;
-    int32_t* bar_err;
+    // dataflow pass kernel: per-step output buffers, completion counters, cached step tables
+    bool flow = false;
+    FlowSizes fs{};
+    char* flow_ws = nullptr;
+    size_t flow_ws_bytes = 0;
+    unsigned* flow_done = nullptr;
+    int32_t* flow_err = nullptr;
+    char* ops_region = nullptr;
+    size_t ops_bytes = 0, ops_used = 0;
+    std::map<std::vector<int>, FlowTable> op_cache;
     std::vector<uint8_t> graph_mask;
-    bool sample_mem;                    // ASD_SAMPLE_MEM (test aid): sampling kernels that re-read memory instead of holding their segments
-    bool att_gh1;                       // ASD_ATT_GH1 (test aid): one query head per attention workgroup also for grouped-query models
-    bool force_att_w4;                  // ASD_ATT_W4 (development / test aid): always launch the four-waves-per-SIMD attention variant
-    float graph_T;
-    uint64_t graph_seed;
+    std::string tune;                   // copy of the configuration's debug_tune
+    bool sample_mem = false;            // ASD_DBG_SAMPLE_MEM: sampling kernels that re-read memory instead of holding their segments
+    bool att_gh1 = false;               // ASD_DBG_ATT_GH1: one query head per attention workgroup also for grouped-query models
+    bool force_att_w4 = false;          // ASD_DBG_ATT_W4: always launch the four-waves-per-SIMD attention variant
+    bool rs_pow2 = false;               // ASD_DBG_RS_POW2: activation row stride = next power of two
+    float graph_T = 0.f;
+    uint64_t graph_seed = 0;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};     // phase stamps of a decode cycle: start, drafts done, verification done
     std::string err;
 };
 
@@ -140,18 +149,53 @@ bool config_ok(const asd_config* c, std::string* why) {
     if (c->max_rows < 1 || c->max_rows > ASD_MAX_ROWS) return bad("max_rows must be in 1..16");
     if (!(c->rms_eps > 0.f) || !(c->rope_theta > 1.f)) return bad("rms_eps must be > 0 and rope_theta > 1");
     if ((long)c->n_layers * 2 > 4096) return bad("too many layers");
+    // the decode-attention merge keeps the statistics of at most 64 * ATT_NCL groups of ATT_GROUP keys per head
+    static_assert(ASD_MAX_SEQ == 64 * ATT_NCL * ATT_GROUP, "ASD_MAX_SEQ is the attention merge's limit");
+    const long pages = ((long)c->max_seq + c->page_tokens - 1) / c->page_tokens;
+    if (pages * c->page_tokens > ASD_MAX_SEQ) return bad("max_seq (rounded up to whole pages) exceeds ASD_MAX_SEQ = 65536 positions");
     return true;
+}
+
+// Compute units of the current device (what the tile-per-workgroup rule balances over); 256, an MI355X, when no
+// device is visible (sizing an arena on a machine without a GPU).
+int device_units() {
+    static int units = 0;
+    if (!units) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) units = n;
+        else units = 256;
+    }
+    return units;
+}
+
+// "name=a,b,c,d" entry of the configuration's debug_tune string
+int tune_entry(const char* tune, const char* name, int* v, int max_n) {
+    if (!tune) return 0;
+    const std::string e(tune), key = std::string(name) + "=";
+    const size_t pos = (";" + e).find(";" + key);
+    if (pos == std::string::npos) return 0;
+    int n = 0;
+    const char* q = e.c_str() + pos + key.size();
+    while (n < max_n) {
+        char* end = nullptr;
+        const long x = strtol(q, &end, 10);
+        if (end == q) break;
+        v[n++] = (int)x;
+        if (*end != ',') break;
+        q = end + 1;
+    }
+    return n;
 }
 
 // Launch shape and weight layout per GEMM class.  Tile-major keeps a tile's K range contiguous; k-major
 // keeps the fragments of all tiles for one k-block contiguous (with interleaved k-blocks per wave the
-// whole grid then sweeps one contiguous window).  Chosen by measurement on the 7B, 13B and 70B shapes; ASD_TUNE
-// (development aid) overrides, e.g. ASD_TUNE="qkv=1,8,1,1;o=1,16,0,0" (TN, NW, k-major, interleave).
-GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
+// whole grid then sweeps one contiguous window).  Chosen by measurement on the 7B, 13B and 70B shapes; the
+// configuration's debug_tune (development aid) overrides, e.g. "qkv=1,8,1,1;o=1,16,0,0" (TN, NW, k-major, interleave).
+GemmCfg pick_cfg(const asd_config& c, int epi, int cls, int tiles, int KB) {
     GemmCfg g{};
     // One tile per workgroup unless two tiles per workgroup leave the busiest compute unit with no more tiles than
-    // before (256 units; e.g. 320 tiles: 2 either way, and the two-tile workgroups stream better: 13B O / down).
-    const int units = 256;
+    // before (e.g. 320 tiles on 256 units: 2 either way, and the two-tile workgroups stream better: 13B O / down).
+    const int units = device_units();
     const int max1 = (tiles + units - 1) / units, max2 = ((tiles + 1) / 2 + units - 1) / units * 2;
     g.TN = (epi == EPI_LM || max2 <= max1) ? 2 : 1;      // (the LM head: two tiles per workgroup at every vocabulary size)
     g.kmajor = (cls == ASD_K_QKV || cls == ASD_K_DOWN || cls == ASD_K_LMHEAD) ? 1 : 0;
@@ -161,23 +205,17 @@ GemmCfg pick_cfg(int epi, int cls, int tiles, int KB) {
     if (cls == ASD_K_OPROJ && KB >= 256) { g.kmajor = 1; g.TN = 1; }
     if (cls == ASD_K_DOWN && KB >= 512) g.kmajor = 0;
     g.kint = g.kmajor;
-    // Waves per workgroup: 8, except where a launch has more workgroups than two rounds of 8-wave workgroups can
-    // hold at once and its waves finish far apart (QKV; gate/up with two tile pairs per workgroup): there 4 waves with
-    // twice the loads in flight each (the same bytes per workgroup, half the waves to join) measured 1-4 % faster per
-    // launch on the 7B, 13B and 70B shapes.  The persistent pass kernel (ASD_PERSIST) runs 8-wave workgroups and must
-    // reduce in the same order, so it keeps 8 everywhere.
-    const char* pe = getenv("ASD_PERSIST");
-    const bool want_persist = pe && atoi(pe) > 0;
-    g.NW = (!want_persist && (cls == ASD_K_QKV || (cls == ASD_K_GATEUP && g.TN == 2))) ? 4 : 8;
+    // Waves per workgroup: 8.  With one launch per step for every pass (ASD_DBG_STEP_KERNELS) two launches do better
+    // with 4 waves and twice the loads in flight each (QKV; gate/up with two tile pairs per workgroup: 1-4 % per
+    // launch on the 7B, 13B and 70B shapes).  The dataflow pass kernel runs 8-wave workgroups, and the per-step
+    // kernels that serve beside it (passes it does not take, profiling) must split K the same way, or a row's bits
+    // would depend on which path ran it.
+    const bool steps_only = (c.debug_flags & ASD_DBG_STEP_KERNELS) != 0;
+    g.NW = (steps_only && (cls == ASD_K_QKV || (cls == ASD_K_GATEUP && g.TN == 2))) ? 4 : 8;
+    if (!steps_only && (cls == ASD_K_QKV || cls == ASD_K_GATEUP)) g.TN = 1;      // (the dataflow kernel's shapes for these two)
     static const char* names[ASD_K_COUNT] = {"", "qkv", "", "o", "gu", "down", "lm", ""};       // indexed by kernel class
-    if (const char* env = getenv("ASD_TUNE")) {
-        std::string e(env), key = std::string(names[cls]) + "=";
-        size_t pos = (";" + e).find(";" + key);
-        if (pos != std::string::npos) {
-            int tn, nw, km, ki;
-            if (sscanf(e.c_str() + pos + key.size(), "%d,%d,%d,%d", &tn, &nw, &km, &ki) == 4) { g.TN = tn; g.NW = nw; g.kmajor = km; g.kint = ki; }
-        }
-    }
+    int v[4];
+    if (tune_entry(c.debug_tune, names[cls], v, 4) == 4) { g.TN = v[0]; g.NW = v[1]; g.kmajor = v[2]; g.kint = v[3]; }
     g.grid = (tiles + g.TN - 1) / g.TN;
     return g;
 }
@@ -186,11 +224,35 @@ struct Plan {
     size_t embed, lm, g_final, layer0, layer_stride, wqkv, wo, wg, wu, wd, g_attn, g_mlp;
     size_t kv, kv_layer, page_table;
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
-        argmax, tokbuf, out_tokens, st, ops, ops_bytes, bar, staging, staging_bytes, total, qlogits;
+        argmax, tokbuf, out_tokens, st, ops, ops_bytes, staging, staging_bytes, total, qlogits;
     size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_xb, pf_q, pf_attn_out, pf_hmid;
+    size_t flow_ws, flow_ws_bytes, flow_done, flow_err;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
 };
+
+// Sizes of the dataflow kernel's regions for a configuration.  Per-step output buffers (each written once per launch):
+// tiled activations are sized for 16 rows whatever the pass's row count, as the per-step path's buffers are.
+int round8(int x) { return (x + 7) / 8 * 8; }
+FlowSizes flow_sizes(const asd_config& c, const Plan& p) {
+    FlowSizes f{};
+    const size_t frag = 1024;
+    const int NPL = c.dtype == ASD_DT_BF16 ? 2 : 1;
+    f.act_d = align_up((size_t)p.KBd * frag * NPL); f.act_q = align_up((size_t)p.KBq * frag * NPL); f.act_f = align_up((size_t)p.KBf * frag * NPL);
+    f.q_bytes = align_up((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es * NPL);
+    f.xres = align_up((size_t)ASD_ROWS * c.d_model * 4);
+    int pmax = p.g_o.grid > p.g_down.grid ? p.g_o.grid : p.g_down.grid;
+    if (pmax < EMBED_SPLIT) pmax = EMBED_SPLIT;
+    f.part = align_up((size_t)pmax * ASD_ROWS * 2 * 4);
+    f.ssq = 256;
+    const size_t per_layer = 2 * f.act_d + f.q_bytes + f.act_q + f.act_f + 2 * f.xres + 2 * f.part + 2 * f.ssq;
+    f.ws_bytes = per_layer * c.n_layers + f.act_d + f.xres + f.part + 2 * f.ssq;
+    f.max_ops = 5 * c.n_layers + 3;
+    const int att_units = attn_grid(c.n_heads, c.n_kv_heads, p.nc_stride, 1);
+    const long per_layer_blocks = (long)round8(p.qkv_tiles) + round8((att_units + 1) / 2) + round8(p.g_o.grid) + round8(c.d_ffn / 16) + round8(p.g_down.grid);
+    f.max_blocks = (int)(per_layer_blocks * c.n_layers + round8(EMBED_SPLIT * ASD_ROWS) + round8(p.g_lm.grid) + 8);
+    return f;
+}
 
 Plan make_plan(const asd_config& c) {
     Plan p{};
@@ -204,11 +266,11 @@ Plan make_plan(const asd_config& c) {
     p.n_pages = (c.max_seq + c.page_tokens - 1) / c.page_tokens;
     p.nc_stride = (p.n_pages * c.page_tokens + ATT_GROUP - 1) / ATT_GROUP;
     p.qkv_tiles = (qd + 2 * kvd) / 16;
-    p.g_qkv = pick_cfg(EPI_QKV, ASD_K_QKV, p.qkv_tiles, p.KBd);
-    p.g_o = pick_cfg(EPI_RES, ASD_K_OPROJ, c.d_model / 16, p.KBq);
-    p.g_gu = pick_cfg(EPI_GU, ASD_K_GATEUP, c.d_ffn / 16, p.KBd);
-    p.g_down = pick_cfg(EPI_RES, ASD_K_DOWN, c.d_model / 16, p.KBf);
-    p.g_lm = pick_cfg(EPI_LM, ASD_K_LMHEAD, c.vocab / 16, p.KBd);
+    p.g_qkv = pick_cfg(c, EPI_QKV, ASD_K_QKV, p.qkv_tiles, p.KBd);
+    p.g_o = pick_cfg(c, EPI_RES, ASD_K_OPROJ, c.d_model / 16, p.KBq);
+    p.g_gu = pick_cfg(c, EPI_GU, ASD_K_GATEUP, c.d_ffn / 16, p.KBd);
+    p.g_down = pick_cfg(c, EPI_RES, ASD_K_DOWN, c.d_model / 16, p.KBf);
+    p.g_lm = pick_cfg(c, EPI_LM, ASD_K_LMHEAD, c.vocab / 16, p.KBd);
 
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -253,9 +315,17 @@ Plan make_plan(const asd_config& c) {
     p.tokbuf = take(64 * 4);
     p.out_tokens = take((size_t)(p.n_pages * c.page_tokens + 64) * 4);
     p.st = take(sizeof(DevState));
-    p.bar = take(16 * 8 * (2 + 2 * 8));      // barrier words of the persistent kernel, one per 128-byte line
-    p.ops_bytes = align_up((size_t)(2 * c.n_layers * 3 + 8) * sizeof(PassOp) * 24);     // ~24 cached step lists
-    p.ops = take(p.ops_bytes);
+    // dataflow pass kernel: every step writes buffers of its own (see flow_sizes), a completion counter per step and
+    // shard, and ~24 cached step tables (steps + the step of every workgroup of the grid)
+    {
+        const FlowSizes fs = flow_sizes(c, p);
+        p.flow_ws_bytes = fs.ws_bytes;
+        p.flow_ws = take(p.flow_ws_bytes);
+        p.flow_done = take((size_t)fs.max_ops * FLOW_SHARDS * FLOW_SHARD_WORDS * 4);
+        p.flow_err = take(256);
+        p.ops_bytes = 24 * (align_up((size_t)fs.max_ops * sizeof(PassOp)) + align_up((size_t)fs.max_blocks * 2));
+        p.ops = take(p.ops_bytes);
+    }
     size_t biggest = (size_t)c.vocab * c.d_model;
     if ((size_t)c.d_ffn * c.d_model > biggest) biggest = (size_t)c.d_ffn * c.d_model;
     if ((size_t)qd * c.d_model > biggest) biggest = (size_t)qd * c.d_model;
@@ -374,19 +444,22 @@ int capacity(const asd_engine* e);
 // Row stride of the tiled activation buffers of an M-row pass (rows per k-group).  The activation bytes a GEMM
 // workgroup reads grow with it, so it is the row count itself, not the next power of two (a 5-row verification
 // pass read 8 rows' worth).
-static int row_stride(int M) {
-    if (const char* env = getenv("ASD_RS_POW2")) { (void)env; int rs = 1; while (rs < M) rs *= 2; return rs; }
+static int row_stride(const asd_engine* e, int M) {
+    if (e->rs_pow2) { int rs = 1; while (rs < M) rs *= 2; return rs; }
     return M;
 }
 
-template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc) {
-    const int H = e->c.head_dim;
-    AttnArgs a = a0;
+// Launch shape of the decode attention for a context of nc 64-key chunks (a.M and a.RS are set)
+void attn_shape(const asd_engine* e, AttnArgs& a, int nc) {
     a.grid_groups = (nc + ATT_GW - 1) / ATT_GW;
     a.cap_chunks = capacity(e) / ASD_CHUNK;
     // grouped-query models: as many query heads of a KV head per workgroup as the 16 columns hold beside the rows
     a.gh = 1;
     if (!e->att_gh1) while (a.gh * 2 * a.RS <= ASD_ROWS && a.gh * 2 <= e->c.n_heads / e->c.n_kv_heads && (e->c.n_heads / e->c.n_kv_heads) % (a.gh * 2) == 0) a.gh *= 2;
+}
+
+template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a) {
+    const int H = e->c.head_dim;
     const int units = e->c.n_heads / a.gh;                    // workgroups per group index
     const int grid = attn_grid(e->c.n_heads, e->c.n_kv_heads, a.grid_groups, a.gh);
     // The first variant holds 512 workgroups at once (two per compute unit) and keeps all of a chunk's loads in flight;
@@ -407,8 +480,8 @@ template <class T> void launch_attn_t(asd_engine* e, const AttnArgs& a0, int nc)
 #undef ATT
 #undef ATT_HOT
 }
-void launch_attn(asd_engine* e, const AttnArgs& a, int nc) {
-    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a, nc); else launch_attn_t<F32>(e, a, nc);
+void launch_attn(asd_engine* e, const AttnArgs& a) {
+    if (e->c.dtype == ASD_DT_BF16) launch_attn_t<BF16>(e, a); else launch_attn_t<F32>(e, a);
 }
 
 // ------------------------------------------------------------------ algorithmic bytes
@@ -451,38 +524,80 @@ struct Prof {
     void end() { if (p) hipEventRecord(p->ev.back(), s); }
 };
 
+// Where a pass's results go: the engine's own buffers, or a caller's device buffers.
+struct PassOut {
+    float* logits;       // [rows][vocab]
+    int32_t* argmax;     // [16]
+};
+
+// Buffers of the embedding step (its outputs are the inputs of the first kept sublayer)
+struct EmbedBufs { float* xres; void* xb; float* part; };
+
 // The steps of one forward pass of M rows (first row at cache position st->pos + pos_off) under a skip mask:
-// a removed sublayer contributes no step at all.  The same list drives the per-step kernels and the
-// persistent pass kernel.
-void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_for_bytes, std::vector<PassOp>& ops) {
+// a removed sublayer contributes no step at all.  The same list drives the per-step kernels and the dataflow
+// pass kernel.  flow = false: every step works on the engine's one set of activation buffers (a step's launch ends
+// before the next one starts).  flow = true: every step writes buffers of its own, taken in step order from the
+// dataflow workspace, so that nothing written inside the launch is written twice, and the steps get their place in
+// the launch's grid and the step they wait for.
+void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_for_bytes, int nc, bool flow, const PassOut& out,
+                std::vector<PassOp>& ops, EmbedBufs* emb) {
     const asd_config& c = e->c;
     double cls_bytes[ASD_K_COUNT];
     pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // full-model totals; per-sublayer figures divide by L
     const double L = c.n_layers;
-    const int RS = row_stride(M);
+    const int RS = row_stride(e, M);
     ops.clear();
+    int next_block = 0;
     auto push = [&](int type, int cls, int grid, double bytes) -> PassOp& {
         PassOp op{};
-        op.type = type; op.cls = cls; op.grid = grid; op.bytes = bytes;
+        op.type = type; op.cls = cls; op.grid = grid; op.bytes = bytes; op.tn = 1;
+        op.first_block = next_block;
+        op.n_blocks = type == OP_FINISH ? 1 : round8(grid);
+        op.dep = (int)ops.size() - 1;
+        for (int sh = 0; sh < FLOW_SHARDS; ++sh) op.dep_target[sh] = ops.empty() ? 0 : ops.back().n_blocks / FLOW_SHARDS;
+        next_block += op.n_blocks;
         ops.push_back(op);
         return ops.back();
     };
+    // per-step buffers of the dataflow kernel, taken in step order
+    const FlowSizes fs = flow ? e->fs : FlowSizes{};
+    size_t ws_off = 0;
+    auto take = [&](size_t bytes) { char* ptr = e->flow_ws + ws_off; ws_off += bytes; return ptr; };
+
+    float* cur_xres = e->xres;          // residual stream as of the last step that wrote it
+    void* cur_xb = e->xb;               // its tiled, gained copy
+    float* cur_part = e->part;          // that step's partial sums
+    float* cur_ssq = e->ssq;            // ||residual row||^2 as of the last finished cosine tap
+    if (flow) { cur_xres = (float*)take(fs.xres); cur_xb = take(fs.act_d); cur_part = (float*)take(fs.part); cur_ssq = (float*)take(fs.ssq); }
+    emb->xres = cur_xres; emb->xb = cur_xb; emb->part = cur_part;
     push(OP_EMBED, ASD_K_EMBED, EMBED_SPLIT * M, 0);
 
     GemmArgs base{};
-    base.M = M; base.RS = RS; base.ssq = e->ssq; base.inv_d = 1.f / (float)c.d_model; base.eps = c.rms_eps;
-    base.xres = e->xres; base.xb = e->xb; base.part = e->part; base.d = c.d_model;
-    base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.q = e->q; base.page_table = e->page_table;
+    base.M = M; base.RS = RS; base.inv_d = 1.f / (float)c.d_model; base.eps = c.rms_eps;
+    base.d = c.d_model;
+    base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.page_table = e->page_table;
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
     base.xb_plane = (int64_t)e->KBd * 64 * e->KE; base.hmid_plane = (int64_t)e->KBf * 64 * e->KE;
     base.q_plane = (int64_t)c.n_heads * c.head_dim * ASD_ROWS;
-    base.hmid = e->hmid; base.logits = e->logits; base.V = c.vocab; base.amax_part = e->amax_part;
+    base.logits = out.logits; base.V = c.vocab; base.amax_part = e->amax_part;
     // the cosine tap still open: partials of the last residual-add step and where its cosine goes
     // (the embedding leaves EMBED_SPLIT partials of ||x||^2 and no cosine to finish)
     int open_P = EMBED_SPLIT, open_sub = -1;
+    // a step that reads the normed residual: its input, the producing step's partials, the open cosine tap
     auto consume = [&](GemmArgs& g) {
-        g.part_in = e->part; g.P_in = open_P;
+        g.X = (const u32x4*)cur_xb; g.x_plane = (int64_t)e->KBd * 64;
+        g.part_in = cur_part; g.P_in = open_P;
+        g.ssq_in = cur_ssq;
+        if (flow) cur_ssq = (float*)take(fs.ssq);
+        g.ssq_out = cur_ssq;
         if (open_sub >= 0) { g.fin_cos_rows = e->cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = e->cos_acc + open_sub; }
+    };
+    // a residual-add step: reads the residual stream, writes the new one, its gained copy and its partials
+    auto produce = [&](GemmArgs& g, int sublayer) {
+        g.xres_in = cur_xres;
+        if (flow) { cur_xres = (float*)take(fs.xres); cur_xb = take(fs.act_d); cur_part = (float*)take(fs.part); }
+        g.xres = cur_xres; g.xb = cur_xb; g.part = cur_part;
+        g.g_next = next_gain(e, mask, sublayer);
     };
     auto layout = [&](GemmArgs& g, const GemmCfg& cfg, int total_tiles, int KB) {
         g.KB = KB; g.w_tile_stride = cfg.kmajor ? 1 : KB; g.w_kb_stride = cfg.kmajor ? total_tiles : 1; g.k_interleave = cfg.kint;
@@ -492,44 +607,51 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
         const Layer& ly = e->layers[l];
         if (!(mask && mask[2 * l])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wqkv; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64; a.n_tiles = e->qkv_tiles;
+            a.W = (const u32x4*)ly.wqkv; a.n_tiles = e->qkv_tiles;
             layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
+            a.q = flow ? (void*)take(fs.q_bytes) : e->q;
             consume(a);
-            push(OP_QKV, ASD_K_QKV, e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
+            push(OP_QKV, ASD_K_QKV, flow ? e->qkv_tiles : e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
 
             AttnArgs t{};
-            t.q = e->q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
+            t.q = a.q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
             t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
-            t.nc_stride = e->nc_stride; t.gh = 1; t.scale = 1.f / sqrtf((float)c.head_dim);
-            t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals; t.out = e->attn_out;
-            push(OP_ATTN, ASD_K_ATTN, 0, cls_bytes[ASD_K_ATTN] / L).t = t;
+            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
+            t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals;
+            t.out = flow ? (void*)take(fs.act_q) : e->attn_out;
+            attn_shape(e, t, nc);
+            const int units = attn_grid(c.n_heads, c.n_kv_heads, t.grid_groups, t.gh);
+            push(OP_ATTN, ASD_K_ATTN, flow ? (units + FLOW_WAVES / ATT_GW - 1) / (FLOW_WAVES / ATT_GW) : units, cls_bytes[ASD_K_ATTN] / L).t = t;
 
             GemmArgs o = base;
-            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)e->attn_out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16;
+            o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)t.out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16;
             layout(o, e->g_o, c.d_model / 16, e->KBq);
-            o.g_next = next_gain(e, mask, 2 * l);
+            produce(o, 2 * l);
             open_P = e->g_o.grid; open_sub = 2 * l;
-            push(OP_OPROJ, ASD_K_OPROJ, e->g_o.grid, cls_bytes[ASD_K_OPROJ] / L).g = o;
+            PassOp& po = push(OP_OPROJ, ASD_K_OPROJ, e->g_o.grid, cls_bytes[ASD_K_OPROJ] / L);
+            po.g = o; po.tn = e->g_o.TN;
         }
         if (!(mask && mask[2 * l + 1])) {
             GemmArgs a = base;
-            a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu; a.X = (const u32x4*)e->xb; a.x_plane = (int64_t)e->KBd * 64;
+            a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu;
             a.n_tiles = c.d_ffn / 16; layout(a, e->g_gu, c.d_ffn / 16, e->KBd);
+            a.hmid = flow ? (void*)take(fs.act_f) : e->hmid;
             consume(a);
-            push(OP_GU, ASD_K_GATEUP, e->g_gu.grid, cls_bytes[ASD_K_GATEUP] / L).g = a;
+            push(OP_GU, ASD_K_GATEUP, flow ? c.d_ffn / 16 : e->g_gu.grid, cls_bytes[ASD_K_GATEUP] / L).g = a;
 
             GemmArgs dn = base;
-            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)e->hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16;
+            dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)a.hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16;
             layout(dn, e->g_down, c.d_model / 16, e->KBf);
-            dn.g_next = next_gain(e, mask, 2 * l + 1);
+            produce(dn, 2 * l + 1);
             open_P = e->g_down.grid; open_sub = 2 * l + 1;
-            push(OP_DOWN, ASD_K_DOWN, e->g_down.grid, cls_bytes[ASD_K_DOWN] / L).g = dn;
+            PassOp& pd = push(OP_DOWN, ASD_K_DOWN, e->g_down.grid, cls_bytes[ASD_K_DOWN] / L);
+            pd.g = dn; pd.tn = e->g_down.TN;
         }
     }
     GemmArgs lm = base;
-    lm.W = (const u32x4*)e->lm; lm.X = (const u32x4*)e->xb; lm.x_plane = (int64_t)e->KBd * 64; lm.n_tiles = c.vocab / 16;
+    lm.W = (const u32x4*)e->lm; lm.n_tiles = c.vocab / 16;
     layout(lm, e->g_lm, c.vocab / 16, e->KBd);
     consume(lm);
     push(OP_LM, ASD_K_LMHEAD, e->g_lm.grid, cls_bytes[ASD_K_LMHEAD]).g = lm;
@@ -537,31 +659,31 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
 }
 
 // Run a pass as one launch per step.
-int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d_tokens, int M, const uint8_t* mask, int nc,
-                 Profiler* profiler, int fin_mode, int fin_arg) {
+int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const EmbedBufs& emb, const int32_t* d_tokens, int M, const uint8_t* mask,
+                 Profiler* profiler, int fin_mode, int fin_arg, const PassOut& out) {
     const asd_config& c = e->c;
     Prof pr{profiler, e->stream};
-    const int RS = row_stride(M);
+    const int RS = row_stride(e, M);
     for (const PassOp& op : ops) {
         pr.begin(op.cls, op.bytes);
         bool ok = true;
         switch (op.type) {
             case OP_EMBED:
                 if (c.dtype == ASD_DT_BF16)
-                    embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model,
-                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
+                    embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), EMBED_THREADS, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model, c.vocab, e->st,
+                        next_gain(e, mask, -1), emb.xres, emb.xb, (size_t)e->KBd * 64 * e->KE, RS, emb.part);
                 else
-                    embed_kernel<F32><<<dim3(EMBED_SPLIT, M), 256, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model,
-                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, e->part);
+                    embed_kernel<F32><<<dim3(EMBED_SPLIT, M), EMBED_THREADS, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model, c.vocab, e->st,
+                        next_gain(e, mask, -1), emb.xres, emb.xb, (size_t)e->KBd * 64 * e->KE, RS, emb.part);
                 break;
             case OP_QKV: ok = launch_gemm<EPI_QKV>(e, e->g_qkv, op.g); break;
             case OP_OPROJ: ok = launch_gemm<EPI_RES>(e, e->g_o, op.g); break;
             case OP_DOWN: ok = launch_gemm<EPI_RES>(e, e->g_down, op.g); break;
             case OP_GU: ok = launch_gemm<EPI_GU>(e, e->g_gu, op.g); break;
             case OP_LM: ok = launch_gemm<EPI_LM>(e, e->g_lm, op.g); break;
-            case OP_ATTN: launch_attn(e, op.t, nc); break;
+            case OP_ATTN: launch_attn(e, op.t); break;
             case OP_FINISH:
-                finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, e->argmax, fin_mode, fin_arg,
+                finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, c.vocab, out.argmax, fin_mode, fin_arg,
                                                            e->st, e->tokbuf, e->out_tokens);
                 break;
         }
@@ -573,52 +695,92 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d
     return ASD_OK;
 }
 
-template <class T, int H> const void* pass_kernel_ptr() { return (const void*)pass_kernel<T, H>; }
-const void* pass_kernel_for(const asd_engine* e) {
-    const int H = e->c.head_dim;
-    if (e->c.dtype == ASD_DT_BF16) return H == 32 ? pass_kernel_ptr<BF16, 32>() : H == 64 ? pass_kernel_ptr<BF16, 64>() : pass_kernel_ptr<BF16, 128>();
-    return H == 32 ? pass_kernel_ptr<F32, 32>() : H == 64 ? pass_kernel_ptr<F32, 64>() : pass_kernel_ptr<F32, 128>();
+template <class T, int H, bool PACK> const void* flow_kernel_ptr() { return (const void*)flow_kernel<T, H, PACK>; }
+
+// Does the dataflow kernel take a pass of M rows?  Its GEMM blocks exist for one tile per workgroup (QKV, gate/up),
+// the configured one or two (the residual-add projections) and two (LM head), all with 8 waves.
+bool flow_takes(const asd_engine* e, int M) {
+    (void)M;
+    return e->flow && e->g_qkv.TN == 1 && e->g_gu.TN == 1 && e->g_lm.TN == 2 && e->g_o.TN <= 2 && e->g_down.TN <= 2 && e->g_qkv.NW == FLOW_WAVES &&
+           e->g_o.NW == FLOW_WAVES && e->g_gu.NW == FLOW_WAVES && e->g_down.NW == FLOW_WAVES && e->g_lm.NW == FLOW_WAVES;
 }
 
-// Run a pass as one persistent launch.  The step list lives in a device-side cache keyed by what it depends on.
-int launch_persistent(asd_engine* e, const std::vector<PassOp>& ops, const std::vector<int>& key, const int32_t* d_tokens, int M,
-                      const uint8_t* mask, int fin_mode, int fin_arg) {
+template <class T, bool PACK> void launch_flow_t(asd_engine* e, const FlowArgs& P, int grid) {
+    const int H = e->c.head_dim;
+    if (H == 32) flow_kernel<T, 32, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
+    if (H == 64) flow_kernel<T, 64, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
+    if (H == 128) flow_kernel<T, 128, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
+}
+
+// Run a pass as one dataflow launch.  The step table lives in a device-side cache keyed by what it depends on.
+int launch_flow(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc, int ctx_for_bytes, int fin_mode,
+                int fin_arg, const PassOut& out) {
     const asd_config& c = e->c;
-    auto it = e->op_cache.find(key);
-    if (it == e->op_cache.end()) {
-        const size_t bytes = ops.size() * sizeof(PassOp);
-        if (e->ops_used + bytes > e->ops_bytes) { e->op_cache.clear(); e->ops_used = 0; CK(e, hipStreamSynchronize(e->stream)); }
-        if (bytes > e->ops_bytes) return fail(e, ASD_E_NOMEM, "step list of %zu bytes exceeds the reserved %zu", bytes, e->ops_bytes);
-        char* dst = e->ops_region + e->ops_used;
-        CK(e, hipMemcpyAsync(dst, ops.data(), bytes, hipMemcpyHostToDevice, e->stream));
-        CK(e, hipStreamSynchronize(e->stream));          // the source vector is the caller's
-        it = e->op_cache.emplace(key, std::make_pair((const PassOp*)dst, (int)ops.size())).first;
-        e->ops_used += align_up(bytes);
+    AttnArgs shape{};
+    shape.M = M; shape.RS = row_stride(e, M);
+    attn_shape(e, shape, nc);
+    std::vector<int> key{M, pos_off, (int)(d_tokens - e->tokbuf), shape.grid_groups, out.logits == e->logits ? 0 : 1, out.argmax == e->argmax ? 0 : 1};
+    for (int j = 0; j < 2 * c.n_layers; ++j) key.push_back(mask ? (mask[j] ? 1 : 0) : 0);
+    if (out.logits != e->logits || out.argmax != e->argmax || (d_tokens < e->tokbuf || d_tokens >= e->tokbuf + 64)) {
+        // caller-owned buffers: their addresses are part of the table
+        key.push_back((int)((uintptr_t)out.logits & 0x7fffffff)); key.push_back((int)((uintptr_t)out.logits >> 31));
+        key.push_back((int)((uintptr_t)out.argmax & 0x7fffffff)); key.push_back((int)((uintptr_t)out.argmax >> 31));
+        key.push_back((int)((uintptr_t)d_tokens & 0x7fffffff)); key.push_back((int)((uintptr_t)d_tokens >> 31));
     }
-    const int RS = row_stride(M);
-    PassArgs P{};
-    P.ops = it->second.first; P.n_ops = it->second.second; P.M = M; P.RS = RS; P.d = c.d_model;
-    P.E = e->embed; P.tokens = d_tokens; P.g_first = next_gain(e, mask, -1); P.xres = e->xres; P.xb = e->xb;
-    P.xb_plane = (int64_t)e->KBd * 64 * e->KE; P.part = e->part;
-    P.cand = (const AmaxCand*)e->amax_part; P.P_lm = e->g_lm.grid; P.fin_mode = fin_mode; P.fin_arg = fin_arg; P.argmax = e->argmax;
+    auto it = e->op_cache.find(key);
+    EmbedBufs emb{};
+    if (it == e->op_cache.end()) {
+        std::vector<PassOp> ops;
+        build_pass(e, M, pos_off, mask, ctx_for_bytes, nc, true, out, ops, &emb);
+        const int n_blocks = ops.back().first_block + ops.back().n_blocks;
+        std::vector<uint16_t> blk((size_t)n_blocks);
+        for (size_t i = 0; i < ops.size(); ++i)
+            for (int b = 0; b < ops[i].n_blocks; ++b) blk[(size_t)ops[i].first_block + b] = (uint16_t)i;
+        const size_t ob = align_up(ops.size() * sizeof(PassOp)), bb = align_up(blk.size() * 2);
+        if (ob + bb > e->ops_bytes) return fail(e, ASD_E_NOMEM, "step table of %zu bytes exceeds the reserved %zu", ob + bb, e->ops_bytes);
+        if (e->ops_used + ob + bb > e->ops_bytes) {      // cache full: start over (the stream may still be reading old tables)
+            CK(e, hipStreamSynchronize(e->stream));
+            e->op_cache.clear(); e->ops_used = 0;
+        }
+        char* dst = e->ops_region + e->ops_used;
+        CK(e, hipMemcpyAsync(dst, ops.data(), ops.size() * sizeof(PassOp), hipMemcpyHostToDevice, e->stream));
+        CK(e, hipMemcpyAsync(dst + ob, blk.data(), blk.size() * 2, hipMemcpyHostToDevice, e->stream));
+        CK(e, hipStreamSynchronize(e->stream));          // the source vectors are locals
+        it = e->op_cache.emplace(key, FlowTable{(const PassOp*)dst, (const uint16_t*)(dst + ob), (int)ops.size(), n_blocks}).first;
+        e->ops_used += ob + bb;
+    }
+    // (the embedding's buffers are the first three of the workspace in every table)
+    {
+        const FlowSizes& fs = e->fs;
+        emb.xres = (float*)e->flow_ws; emb.xb = e->flow_ws + fs.xres; emb.part = (float*)(e->flow_ws + fs.xres + fs.act_d);
+    }
+    FlowArgs P{};
+    P.ops = it->second.ops; P.op_of_block = it->second.op_of_block; P.n_ops = it->second.n_ops;
+    P.M = M; P.RS = row_stride(e, M); P.d = c.d_model; P.vocab = c.vocab;
+    P.E = e->embed; P.tokens = d_tokens; P.g_first = next_gain(e, mask, -1);
+    P.xres0 = emb.xres; P.xb0 = emb.xb; P.xb_plane = (int64_t)e->KBd * 64 * e->KE; P.part0 = emb.part;
+    P.cand = (const AmaxCand*)e->amax_part; P.P_lm = e->g_lm.grid; P.fin_mode = fin_mode; P.fin_arg = fin_arg; P.argmax = out.argmax;
     P.st = e->st; P.tokbuf = e->tokbuf; P.out = e->out_tokens;
-    P.bar = e->bar; P.bar_base = e->bar_count; P.err = e->bar_err;
-    e->bar_count += (unsigned long long)(P.n_ops - 1);
-    void* args[] = {&P};
-    CK(e, hipLaunchCooperativeKernel(pass_kernel_for(e), dim3(e->pass_grid), dim3(PASS_THREADS), args, 0, e->stream));
+    P.done = e->flow_done; P.err = e->flow_err;
+    const int grid = it->second.n_blocks;
+    if (c.dtype == ASD_DT_BF16) {
+        if (M <= 8) launch_flow_t<BF16, true>(e, P, grid); else launch_flow_t<BF16, false>(e, P, grid);
+    } else {
+        launch_flow_t<F32, false>(e, P, grid);
+    }
+    hipError_t r = hipGetLastError();
+    if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
     return ASD_OK;
 }
 
 int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
-                    Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0) {
+                    Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0, const PassOut* out_or_null = nullptr) {
+    const PassOut out = out_or_null ? *out_or_null : PassOut{e->logits, e->argmax};
+    if (!profiler && flow_takes(e, M)) return launch_flow(e, d_tokens, M, pos_off, mask, nc, ctx_for_bytes, fin_mode, fin_arg, out);
     std::vector<PassOp> ops;
-    build_pass(e, M, pos_off, mask, ctx_for_bytes, ops);
-    if (e->persistent && !profiler && (M <= 8 || e->c.dtype != ASD_DT_BF16)) {     // (its bf16 GEMM blocks are the packed, at-most-8-row form)
-        std::vector<int> key{M, pos_off, (int)(d_tokens - e->tokbuf)};
-        for (int j = 0; j < 2 * e->c.n_layers; ++j) key.push_back(mask ? (mask[j] ? 1 : 0) : 0);
-        return launch_persistent(e, ops, key, d_tokens, M, mask, fin_mode, fin_arg);
-    }
-    return launch_steps(e, ops, d_tokens, M, mask, nc, profiler, fin_mode, fin_arg);
+    EmbedBufs emb{};
+    build_pass(e, M, pos_off, mask, ctx_for_bytes, nc, false, out, ops, &emb);
+    return launch_steps(e, ops, emb, d_tokens, M, mask, profiler, fin_mode, fin_arg, out);
 }
 
 bool weights_ready(asd_engine* e) {
@@ -628,12 +790,22 @@ bool weights_ready(asd_engine* e) {
 
 int chunks_for(int last_pos) { return last_pos / ASD_CHUNK + 1; }
 
-// after a synchronisation: did a grid barrier of the persistent kernel give up?
-int check_pass_error(asd_engine* e) {
-    if (!e->persistent) return ASD_OK;
+// After a synchronisation: did a wait of the dataflow kernel give up, or did a kernel meet a token id outside the
+// vocabulary / a row of logits without a finite maximum?  (st: a host copy of the decoding state, or NULL to fetch it.)
+int check_pass_error(asd_engine* e, const DevState* st = nullptr) {
+    DevState tmp;
+    if (!st) { CK(e, hipMemcpy(&tmp, e->st, sizeof tmp, hipMemcpyDeviceToHost)); st = &tmp; }
+    if (st->err & DEV_ERR_TOKEN) return fail(e, ASD_E_INVAL, "a token id outside the vocabulary reached the embedding");
+    if (st->err & DEV_ERR_LOGITS) return fail(e, ASD_E_STATE, "a row of logits had no finite maximum (non-finite weights?)");
+    if (!e->flow) return ASD_OK;
     int32_t flag = 0;
-    CK(e, hipMemcpy(&flag, e->bar_err, 4, hipMemcpyDeviceToHost));
-    if (flag) return fail(e, ASD_E_HIP, "a grid barrier of the persistent pass kernel timed out");
+    CK(e, hipMemcpy(&flag, e->flow_err, 4, hipMemcpyDeviceToHost));
+    if (flag) {
+        // the counters are in an unknown state: clear them so that the engine stays usable
+        hipMemset(e->flow_done, 0, (size_t)e->fs.max_ops * FLOW_SHARDS * FLOW_SHARD_WORDS * 4);
+        hipMemset(e->flow_err, 0, 4);
+        return fail(e, ASD_E_HIP, "a step of the dataflow pass kernel gave up waiting for its producer");
+    }
     return ASD_OK;
 }
 
@@ -650,20 +822,22 @@ void drop_graphs(asd_engine* e) {
 
 int capacity(const asd_engine* e) { return e->n_pages * e->c.page_tokens; }
 
+// release what the engine owns on the host side (graphs, events, pinned state) and the engine itself
+void destroy_host(asd_engine* e) {
+    drop_graphs(e);
+    for (hipEvent_t ev : e->ev) if (ev) hipEventDestroy(ev);
+    if (e->h_st) hipHostFree(e->h_st);
+    delete e;
+}
+
 // ------------------------------------------------------------------ prompt blocks
 // Launch shape of a prompt GEMM class: NC 16-row chunks per workgroup and K slices (slices only for the two
-// residual-add GEMMs).  ASD_PF_TUNE (development aid) overrides, e.g. "qkv=8,1;o=8,2;gu=4,1;down=8,4".
-PfCfg pf_pick(const char* name, int nc, int ks) {
+// residual-add GEMMs).  The configuration's debug_tune (development aid) overrides, e.g. "pf_qkv=8,1;pf_o=8,2;pf_gu=4,1;pf_down=8,4".
+PfCfg pf_pick(const char* tune, const char* name, int nc, int ks) {
     PfCfg g{nc, ks, 2};
-    if (const char* env = getenv("ASD_PF_TUNE")) {
-        std::string e(env), key = std::string(name) + "=";
-        size_t pos = (";" + e).find(";" + key);
-        if (pos != std::string::npos) {
-            int a, b, d = 1;
-            if (sscanf(e.c_str() + pos + key.size(), "%d,%d,%d", &a, &b, &d) >= 2 && (a == 2 || a == 4 || a == 8) && b >= 1 && b <= PF_MAX_KSPLIT &&
-                d >= 1 && d <= 4) { g.NC = a; g.KS = b; g.PD = d; }
-        }
-    }
+    int v[3] = {0, 0, 1};
+    const int n = tune_entry(tune, name, v, 3);
+    if (n >= 2 && (v[0] == 2 || v[0] == 4 || v[0] == 8) && v[1] >= 1 && v[1] <= PF_MAX_KSPLIT && v[2] >= 1 && v[2] <= 4) { g.NC = v[0]; g.KS = v[1]; g.PD = v[2]; }
     return g;
 }
 
@@ -798,13 +972,14 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n, Profiler* profil
     pr.begin(ASD_PK_LMHEAD, 2.0 * c.d_model * c.vocab);
     launch_pf_rows(e, 2, rows, 0, 1, nullptr, nullptr, rows - 1);
     std::vector<PassOp> ops;
-    build_pass(e, 1, 0, nullptr, n, ops);
+    EmbedBufs emb{};
+    build_pass(e, 1, 0, nullptr, n, chunks_for(n - 1), false, PassOut{e->logits, e->argmax}, ops, &emb);
     for (PassOp& op : ops) {
         if (op.type != OP_LM) continue;
         op.g.part_in = e->part; op.g.P_in = 1; op.g.fin_cos_rows = nullptr; op.g.fin_cos_acc = nullptr;
         if (!launch_gemm<EPI_LM>(e, e->g_lm, op.g)) return fail(e, ASD_E_STATE, "no kernel instance for the LM head");
     }
-    finish_kernel<<<1, 64, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, 1, e->argmax, FIN_NONE, 0, e->st, e->tokbuf, e->out_tokens);
+    finish_kernel<<<1, 64, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, 1, c.vocab, e->argmax, FIN_NONE, 0, e->st, e->tokbuf, e->out_tokens);
     pr.end();
     hipError_t r = hipGetLastError();
     if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
@@ -861,32 +1036,34 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->pf_tok = (int32_t*)(A + p.pf_tok); e->pf_xres = (float*)(A + p.pf_xres); e->pf_raw = (float*)(A + p.pf_raw);
     e->pf_ssq = (float*)(A + p.pf_ssq); e->pf_rscale = (float*)(A + p.pf_rscale); e->pf_cos_rows = (float*)(A + p.pf_cos_rows);
     e->pf_xb = A + p.pf_xb; e->pf_q = A + p.pf_q; e->pf_attn_out = A + p.pf_attn_out; e->pf_hmid = A + p.pf_hmid;
-    e->pf_qkv = pf_pick("qkv", 4, 1); e->pf_o = pf_pick("o", 4, 4); e->pf_gu = pf_pick("gu", 4, 1); e->pf_down = pf_pick("down", 4, 4);
-    e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
-    e->bar = (unsigned long long*)(A + p.bar); e->bar_err = (int32_t*)(A + p.bar + 64);   // inside the top counter's line, never contended e->bar_count = 0;
+    e->tune = cfg->debug_tune ? cfg->debug_tune : "";
+    e->c.debug_tune = nullptr;              // (the caller's string is not kept; e->tune is the copy)
+    const char* tune = e->tune.empty() ? nullptr : e->tune.c_str();
+    e->pf_qkv = pf_pick(tune, "pf_qkv", 4, 1); e->pf_o = pf_pick(tune, "pf_o", 4, 4);
+    e->pf_gu = pf_pick(tune, "pf_gu", 4, 1); e->pf_down = pf_pick(tune, "pf_down", 4, 4);
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
-    e->att_gh1 = getenv("ASD_ATT_GH1") != nullptr;
-    e->sample_mem = getenv("ASD_SAMPLE_MEM") != nullptr;
-    e->force_att_w4 = getenv("ASD_ATT_W4") != nullptr; e->graph_T = 0.f; e->graph_seed = 0; e->kv_len = 0; e->acs.assign(2 * (size_t)cfg->n_layers, 0.f); e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0); e->acs_rows = 0; e->acs_valid = false; e->h_st = nullptr;
-    // persistent pass kernel: needs the launch shapes it is compiled for and a grid that is resident all at once
-    e->persistent = false; e->pass_grid = 0;
-    {
-        const bool shapes_ok = p.g_qkv.TN == 1 && p.g_o.TN == 1 && p.g_gu.TN == 1 && p.g_down.TN == 1 && p.g_lm.TN == 2 &&
-                               p.g_qkv.NW == 8 && p.g_o.NW == 8 && p.g_gu.NW == 8 && p.g_down.NW == 8 && p.g_lm.NW == 8;
-        const char* env = getenv("ASD_PERSIST");
-        int nb = 0, dev = 0;
-        hipDeviceProp_t prop;
-        if (shapes_ok && env && atoi(env) > 0 && hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, pass_kernel_for(e), PASS_THREADS, 0) == hipSuccess && nb > 0 &&
-            prop.cooperativeLaunch) {
-            const int per_cu = nb < atoi(env) ? nb : atoi(env);
-            e->pass_grid = prop.multiProcessorCount * per_cu;
-            e->persistent = true;
-        }
-    }
+    e->att_gh1 = (cfg->debug_flags & ASD_DBG_ATT_GH1) != 0;
+    e->sample_mem = (cfg->debug_flags & ASD_DBG_SAMPLE_MEM) != 0;
+    e->force_att_w4 = (cfg->debug_flags & ASD_DBG_ATT_W4) != 0;
+    e->rs_pow2 = (cfg->debug_flags & ASD_DBG_RS_POW2) != 0;
+    e->kv_len = 0;
+    e->acs.assign(2 * (size_t)cfg->n_layers, 0.f);
+    e->acs_sum.assign(2 * (size_t)cfg->n_layers, 0.0);
+    e->acs_rows = 0;
+    e->acs_valid = false;
+    e->h_st = nullptr;
+    // dataflow pass kernel
+    e->fs = flow_sizes(*cfg, p);
+    e->flow_ws = A + p.flow_ws; e->flow_ws_bytes = p.flow_ws_bytes;
+    e->flow_done = (unsigned*)(A + p.flow_done); e->flow_err = (int32_t*)(A + p.flow_err);
+    e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
+    e->flow = (cfg->debug_flags & ASD_DBG_STEP_KERNELS) == 0;
+    e->flow = e->flow && flow_takes(e, 1);
 
     hipError_t r = hipHostMalloc((void**)&e->h_st, sizeof(DevState), hipHostMallocDefault);
     if (r != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(r)); }
+    for (int i = 0; i < 3 && r == hipSuccess; ++i) r = hipEventCreate(&e->ev[i]);
+    if (r != hipSuccess) { destroy_host(e); return fail(nullptr, ASD_E_HIP, "hipEventCreate: %s", hipGetErrorString(r)); }
     // clear cache + workspace (everything after the weights), then build the tables
     r = hipMemsetAsync(A + p.kv, 0, p.total - p.kv, e->stream);
     if (r == hipSuccess) {
@@ -897,7 +1074,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
         r = hipStreamSynchronize(e->stream);
     }
     if (r != hipSuccess) {
-        hipHostFree(e->h_st); delete e;
+        destroy_host(e);
         return fail(nullptr, ASD_E_HIP, "engine initialisation: %s", hipGetErrorString(r));
     }
     *out = e;
@@ -907,9 +1084,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
 void asd_destroy(asd_engine* e) {
     if (!e) return;
     hipStreamSynchronize(e->stream);
-    drop_graphs(e);
-    if (e->h_st) hipHostFree(e->h_st);
-    delete e;
+    destroy_host(e);
 }
 
 int asd_set_weight(asd_engine* e, int32_t t, int32_t layer, const void* src, size_t bytes, int32_t src_on_device) {
@@ -1185,11 +1360,14 @@ int asd_prefill_chunked(asd_engine* e, const int32_t* tokens, int32_t n, int32_t
 // one draft/verify/accept cycle, enqueue only: kk draft steps with the masked model, then a (kk+1)-row verify
 #define DECODE_BURST 16      // draft-free decode cycles enqueued between two looks at the device state
 
-static int enqueue_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx) {
+static int enqueue_drafts(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx) {
     for (int j = 0; j < kk; ++j) {
         int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_DRAFT, j);
         if (rc) return rc;
     }
+    return ASD_OK;
+}
+static int enqueue_verify(asd_engine* e, int kk, int nc, int32_t ctx) {
     return enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, kk);
 }
 
@@ -1222,12 +1400,15 @@ static void launch_sample_plain(asd_engine* e, const SampleArgs& sa, int row, in
 }
 
 // one sampled draft / verify / accept cycle, enqueue only
-static int enqueue_sampled_cycle(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx, const SampleArgs& sa) {
+static int enqueue_sampled_drafts(asd_engine* e, int kk, const uint8_t* mask, int nc, int32_t ctx, const SampleArgs& sa) {
     for (int j = 0; j < kk; ++j) {
         int rc = enqueue_forward(e, e->tokbuf + j, 1, j, mask, nc, nullptr, ctx, FIN_NONE, 0);
         if (rc) return rc;
         launch_sample_draft(e, sa, j);
     }
+    return ASD_OK;
+}
+static int enqueue_sampled_verify(asd_engine* e, int kk, int nc, int32_t ctx, const SampleArgs& sa) {
     int rc = enqueue_forward(e, e->tokbuf, kk + 1, 0, nullptr, nc, nullptr, ctx, FIN_NONE, 0);
     if (rc) return rc;
     launch_sample_accept(e, sa, kk);
@@ -1266,7 +1447,7 @@ int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits,
 
 // Run `enqueue` on the engine's stream: eagerly, or (use_graphs) as a HIP graph captured once per key.
 static int run_captured(asd_engine* e, bool use_graphs, const std::vector<int>& key, const std::function<int()>& enqueue) {
-    if (!use_graphs || e->persistent) return enqueue();
+    if (!use_graphs || e->flow) return enqueue();      // (a dataflow pass is one launch: nothing to gain from a graph)
     auto it = e->graphs.find(key);
     if (it == e->graphs.end()) {
         hipGraph_t g = nullptr;
@@ -1346,23 +1527,38 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
     // token and advances the cache by one, so cycles are enqueued DECODE_BURST at a time behind one another and the
     // host looks at the device state once per burst instead of once per token.
     const bool lockstep = k == 0 && !refresh;
+    // phase accounting: GPU time between the stamps of every cycle, algorithmic bytes of its passes
+    double ms_draft = 0.0, ms_verify = 0.0, bytes_draft = 0.0, bytes_verify = 0.0;
+    auto add_bytes = [&](double& acc, const uint8_t* m, int ctx) {
+        double cls[ASD_K_COUNT];
+        pass_bytes(e, m, ctx, cls);
+        for (int i = 0; i < ASD_K_COUNT; ++i) acc += cls[i];
+    };
     while (emitted < n_more) {
         const int burst = lockstep ? (n_more - emitted < DECODE_BURST ? n_more - emitted : DECODE_BURST) : 1;
+        CK(e, hipEventRecord(e->ev[0], e->stream));
         for (int b = 0; b + 1 < burst; ++b) {
             const int nc = chunks_for(e->kv_len + b), ctx = e->kv_len + b + 1;
-            rc = sampled ? run_captured(e, graphs, {3, 0, nc}, [&] { return enqueue_sampled_cycle(e, 0, mask.data(), nc, ctx, sa); })
-                         : run_captured(e, graphs, {0, 0, nc}, [&] { return enqueue_cycle(e, 0, mask.data(), nc, ctx); });
+            rc = sampled ? run_captured(e, graphs, {3, 0, nc}, [&] { return enqueue_sampled_verify(e, 0, nc, ctx, sa); })
+                         : run_captured(e, graphs, {0, 0, nc}, [&] { return enqueue_verify(e, 0, nc, ctx); });
             if (rc) return rc;
+            add_bytes(bytes_verify, nullptr, ctx);
         }
         const int ahead = burst - 1;                 // cycles already enqueued in this trip
         const int kk = k < n_more - emitted - 1 ? k : n_more - emitted - 1;
         const int nc = chunks_for(e->kv_len + ahead + kk), ctx = e->kv_len + ahead + kk + 1;
         int d = kk;
         if (sampled) {
-            rc = run_captured(e, graphs, {3, kk, nc}, [&] { return enqueue_sampled_cycle(e, kk, mask.data(), nc, ctx, sa); });
+            if (kk > 0) rc = run_captured(e, graphs, {4, kk, nc}, [&] { return enqueue_sampled_drafts(e, kk, mask.data(), nc, ctx, sa); });
+            if (rc) return rc;
+            CK(e, hipEventRecord(e->ev[1], e->stream));
+            rc = run_captured(e, graphs, {3, kk, nc}, [&] { return enqueue_sampled_verify(e, kk, nc, ctx, sa); });
             if (rc) return rc;
         } else if (p->exit_mode == 0) {
-            rc = run_captured(e, graphs, {0, kk, nc}, [&] { return enqueue_cycle(e, kk, mask.data(), nc, ctx); });
+            if (kk > 0) rc = run_captured(e, graphs, {5, kk, nc}, [&] { return enqueue_drafts(e, kk, mask.data(), nc, ctx); });
+            if (rc) return rc;
+            CK(e, hipEventRecord(e->ev[1], e->stream));
+            rc = run_captured(e, graphs, {0, kk, nc}, [&] { return enqueue_verify(e, kk, nc, ctx); });
             if (rc) return rc;
         } else {
             // draft until the limit or a low-confidence draft; the host reads the confidence after every step
@@ -1376,15 +1572,28 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
                 CK(e, hipStreamSynchronize(e->stream));
                 if ((double)e->h_st->conf < gamma) break;
             }
+            CK(e, hipEventRecord(e->ev[1], e->stream));
             rc = run_captured(e, graphs, {2, d, nc},
                               [&] { return enqueue_forward(e, e->tokbuf, d + 1, 0, nullptr, nc, nullptr, ctx, FIN_ACCEPT, d); });
             if (rc) return rc;
         }
+        CK(e, hipEventRecord(e->ev[2], e->stream));
+        for (int j = 0; j < d; ++j) add_bytes(bytes_draft, mask.data(), e->kv_len + ahead + j + 1);
+        add_bytes(bytes_verify, nullptr, e->kv_len + ahead + d + 1);
         CK(e, hipMemcpyAsync(e->h_st, e->st, sizeof(DevState), hipMemcpyDeviceToHost, e->stream));
         if (refresh) CK(e, hipMemcpyAsync(cr.data(), e->cos_rows, cr.size() * 4, hipMemcpyDeviceToHost, e->stream));
         CK(e, hipStreamSynchronize(e->stream));
-        if (e->h_st->emitted <= emitted || (lockstep && e->h_st->emitted != emitted + burst))
-            return fail(e, ASD_E_STATE, "decode cycle made no progress");
+        {
+            float t_d = 0.f, t_v = 0.f;
+            CK(e, hipEventElapsedTime(&t_d, e->ev[0], e->ev[1]));
+            CK(e, hipEventElapsedTime(&t_v, e->ev[1], e->ev[2]));
+            if (lockstep) ms_verify += (double)t_d + t_v; else { ms_draft += t_d; ms_verify += t_v; }
+        }
+        if (e->h_st->err) { const int rce = check_pass_error(e, e->h_st); if (rce) return rce; }
+        if (e->h_st->emitted <= emitted || (lockstep && e->h_st->emitted != emitted + burst)) {
+            const int rce = check_pass_error(e, e->h_st);
+            return rce ? rce : fail(e, ASD_E_STATE, "decode cycle made no progress");
+        }
         const int a = e->h_st->accepted - accepted;
         accepted = e->h_st->accepted;
         emitted = e->h_st->emitted;
@@ -1413,6 +1622,9 @@ int asd_decode(asd_engine* e, int32_t last_token, int32_t n_more, const asd_gen_
         stats->emitted = emitted; stats->ms_prefill = 0.0;
         stats->ms_decode = std::chrono::duration<double, std::milli>(t1 - t0).count();
         stats->mask_changes = mask_changes; stats->gamma = gamma; stats->ar = ar;
+        stats->ms_draft = ms_draft; stats->ms_verify = ms_verify;
+        stats->ms_other = stats->ms_decode - ms_draft - ms_verify;
+        stats->bytes_draft = bytes_draft; stats->bytes_verify = bytes_verify;
     }
     if (mask_used) memcpy(mask_used, mask.data(), mask.size());
     return ASD_OK;
@@ -1478,7 +1690,7 @@ int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* mask, int32_t re
     if (rc) return rc;
     const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
     hipGraphExec_t ge = nullptr;
-    if (use_graph && !e->persistent) {
+    if (use_graph && !e->flow) {
         hipGraph_t g = nullptr;
         CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
         rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);
@@ -1593,16 +1805,18 @@ int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps
     if (rc) return rc;
     const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
     std::vector<PassOp> all, sel;
-    build_pass(e, n_rows, 0, nullptr, ctx, all);
-    rc = launch_steps(e, all, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);     // valid inputs for every step
+    EmbedBufs emb{};
+    const PassOut out{e->logits, e->argmax};
+    build_pass(e, n_rows, 0, nullptr, ctx, nc, false, out, all, &emb);
+    rc = launch_steps(e, all, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // valid inputs for every step
     if (rc) return rc;
     double bytes = 0.0;
     for (const PassOp& op : all) if (op.cls == cls) { sel.push_back(op); bytes += op.bytes; }
     if (sel.empty()) return fail(e, ASD_E_INVAL, "the pass has no step of class %d", cls);
-    rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);     // warm-up
+    rc = launch_steps(e, sel, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // warm-up
     hipEvent_t a = nullptr, b = nullptr;
     if (!rc) { hipEventCreate(&a); hipEventCreate(&b); hipEventRecord(a, e->stream); }
-    for (int i = 0; i < reps && !rc; ++i) rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nc, nullptr, FIN_NONE, 0);
+    for (int i = 0; i < reps && !rc; ++i) rc = launch_steps(e, sel, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);
     float ms = 0.f;
     if (!rc) {
         hipEventRecord(b, e->stream);

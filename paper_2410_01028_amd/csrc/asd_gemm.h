@@ -20,8 +20,14 @@
 // the same fixed order to get ||y||^2, and workgroup 0 also finishes the producing
 // sublayer's cosine, cos = <x,y> / sqrt(||x||^2 ||y||^2).  No workgroup ever waits for
 // another inside a kernel, so no device-scope fence (and no L2 write-back) is needed.
+//
+// The same block function also runs inside the dataflow pass kernel (asd_flow.h), where the producer of a step's
+// activations is another workgroup of the same launch: there COH = true makes every store of exchanged data a
+// device-scope write-through store, and `dep` (called once by every wave, after the first weight fragments have
+// been requested and before anything the producer wrote is read) blocks until the producer has finished.
 #pragma once
 #include "asd_common.h"
+#include <type_traits>
 
 enum { EPI_QKV = 0, EPI_RES = 1, EPI_GU = 2, EPI_LM = 3 };
 
@@ -38,7 +44,8 @@ struct GemmArgs {
     int32_t k_interleave;    // how the waves of a workgroup split K
     int32_t M;               // rows in use
     int32_t RS;              // row stride of every activation buffer in this pass (power of two >= M)
-    float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap
+    const float* ssq_in;     // [16] ||residual row||^2 as of the last finished cosine tap
+    float* ssq_out;          // [16] where workgroup 0 leaves this step's ||residual row||^2 (may alias ssq_in)
     float inv_d, eps;
     // input side of QKV / GU / LM: partials of the kernel that produced the residual
     const float* part_in;    // [P_in][16][2]
@@ -46,7 +53,8 @@ struct GemmArgs {
     float* fin_cos_rows;     // [16] cosine per row of the producing sublayer (written by workgroup 0); NULL after the embedding
     double* fin_cos_acc;     // its running sum over rows
     // EPI_RES
-    float* xres;             // [16][d] fp32 residual stream, updated in place
+    const float* xres_in;    // [16][d] fp32 residual stream entering the sublayer
+    float* xres;             // [16][d] residual stream leaving it (may alias xres_in: each element is read and written by one thread)
     void* xb;                // tiled copy of y * g_next in storage type
     int64_t xb_plane, q_plane, hmid_plane;   // plane strides (elements) of the activation buffers written here
     const float* g_next;     // gain of the norm that reads y next
@@ -73,30 +81,46 @@ struct GemmArgs {
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
 // X points at this lane's fragment of k-block 0 (always a valid address); consecutive k-blocks are xstep fragments
 // apart.
-template <class T, int NA, int NPL, int U, bool COH, class F>
+struct NoDep { __device__ __forceinline__ void operator()() const {} };      // the producer is an earlier launch
+
+template <class T, int NA, int NPL, int U, class F, class D>
 __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
-                                           int64_t wks, f32x4 (&acc)[NPL][NA], F between) {
+                                           int64_t wks, f32x4 (&acc)[NPL][NA], F between, D dep) {
     // A ring of U slots.  The steady-state loop has no conditional request in it, and X is a valid address in every
     // lane (a lane whose row is not in use reads another row's fragment: its column of the products is never read,
     // and zeroing it would be a use that waits for the load).  The wait counts the compiler derives are exact only
     // when every path issues the same loads; a single request under a condition made it wait for ALL outstanding
     // loads at the top of every trip, which turns the ring into load-everything-then-drain.
+    // dep() separates what may be requested at once (weights) from what another workgroup produces (activations):
+    // the first ring of weight fragments is in flight while the wave waits for its producer.
     u32x4 a[U][NA], b[U][NPL];
-    auto fill = [&](const int u, const int kb) {
-#pragma unroll
-        for (int pl = 0; pl < NPL; ++pl) b[u][pl] = ld_frag<COH>(X + (size_t)(first + kb * step) * xstep + pl * xpl);
+    auto fill_a = [&](const int u, const int kb) {
 #pragma unroll
         for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + (size_t)(first + kb * step) * ASD_WAVE * wks);
     };
+    auto fill_b = [&](const int u, const int kb) {
+#pragma unroll
+        for (int pl = 0; pl < NPL; ++pl) b[u][pl] = *(X + (size_t)(first + kb * step) * xstep + pl * xpl);
+    };
+    auto fill = [&](const int u, const int kb) { fill_b(u, kb); fill_a(u, kb); };
     auto use = [&](const int u) {
 #pragma unroll
         for (int s = 0; s < NA; ++s)
 #pragma unroll
             for (int pl = 0; pl < NPL; ++pl) mma16<T>(acc[pl][s], a[u][s], b[u][pl]);
     };
+    constexpr bool kNoDep = std::is_same<D, NoDep>::value;
     if (n >= U) {
+        if constexpr (kNoDep) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) fill(u, u);
+            for (int u = 0; u < U; ++u) fill(u, u);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) fill_a(u, u);
+            dep();
+#pragma unroll
+            for (int u = 0; u < U; ++u) fill_b(u, u);
+        }
         between();
         int i = 0;
         for (; i + 2 * U <= n; i += U) {               // every refill of such a trip is a k-block of the range
@@ -113,9 +137,19 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
         for (int u = 0; u + 1 < U; ++u)
             if (u < extra) use(u);
     } else {                                           // a K range shorter than the ring
+        if constexpr (kNoDep) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (u < n) fill(u, u);
+            for (int u = 0; u < U; ++u)
+                if (u < n) fill(u, u);
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (u < n) fill_a(u, u);
+            dep();
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (u < n) fill_b(u, u);
+        }
         between();
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -123,27 +157,41 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
     }
 }
 
+// LDS of one workgroup's block function (a kernel that runs several kinds of block gives them one region in turn)
+template <class T, int EPI, int TN, int NW, bool PACK> struct GemmLds {
+    static constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
+    static constexpr int NPL = PACK ? 1 : T::NP;
+    static constexpr bool kNormed = (EPI != EPI_RES);
+    f32x4 red[NW][NPL][NA][64];
+    float epi_a[(EPI == EPI_RES || EPI == EPI_LM) ? NA * 256 : 1];
+    float epi_b[EPI == EPI_RES ? NA * 256 : 1];
+    float fin_a[kNormed ? NW * 64 : 1];
+    float fin_b[kNormed ? NW * 64 : 1];
+    float rscale[16];
+};
+
 // One workgroup's share of the contraction: "virtual block" bid owns tiles bid*TN .. bid*TN+TN-1.  Called once per
-// workgroup by gemm_kernel (bid = blockIdx.x) and in a loop over virtual blocks by the persistent pass kernel
-// (COH = true: every access to data exchanged with other workgroups of the same kernel is coherent).
+// workgroup, by gemm_kernel (bid = blockIdx.x, COH = false, no dependency) and by the dataflow pass kernel (COH =
+// true: stores of data that other workgroups of the same launch read are device-scope write-through stores; what
+// this block reads of such data it reads after dep() has returned, from addresses nobody read earlier in the launch).
 //
 // Two-plane (bf16) activations: the hi and the lo plane are contracted into separate sums, added once at the end.
 // PACK (passes of at most 8 rows): both planes share one operand, rows in columns 0..7 hi and 8..15 lo, so a
 // k-block costs one fragment load and one MFMA; otherwise each plane has its own operand and accumulators.  Either
 // way an output element is (sum over waves of its hi sums) + (sum over waves of its lo sums): the same bits.
-template <class T, int EPI, int TN, int NW, int U, bool COH, bool PACK>
-__device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
+template <class T, int EPI, int TN, int NW, int U, bool COH, bool PACK, class D = NoDep>
+__device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, GemmLds<T, EPI, TN, NW, PACK>& lds, D dep = D()) {
     constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     constexpr int NT = NW * 64;
     constexpr int NPL = PACK ? 1 : T::NP;               // operands (and accumulator sets) per k-block
     static_assert(!PACK || T::NP == 2, "packing is for two-plane activations");
     constexpr bool kNormed = (EPI != EPI_RES);          // input went through RMSNorm: needs the row scale
-    __shared__ f32x4 red[NW][NPL][NA][64];
-    __shared__ float epi_a[(EPI == EPI_RES || EPI == EPI_LM) ? NA * 256 : 1];
-    __shared__ float epi_b[EPI == EPI_RES ? NA * 256 : 1];
-    __shared__ float fin_a[kNormed ? NT : 1];
-    __shared__ float fin_b[kNormed ? NT : 1];
-    __shared__ float rscale[16];
+    auto& red = lds.red;
+    auto& epi_a = lds.epi_a;
+    auto& epi_b = lds.epi_b;
+    auto& fin_a = lds.fin_a;
+    auto& fin_b = lds.fin_b;
+    auto& rscale = lds.rscale;
 
     // The wave index as a scalar: everything derived from it (this wave's K range, the trip counts of the stream) is
     // then scalar too and the stream's control flow is real branches.  As a vector value the conditions become lane
@@ -189,7 +237,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
                 const int p = j + q * J;
                 const bool on = m < a.M && p < a.P_in;
                 const float* src = &a.part_in[((size_t)(on ? p : 0) * 16 + (on ? m : 0)) * 2];
-                const float y = ld_f32<COH>(src + 1), x = ld_f32<COH>(src);
+                const float y = src[1], x = src[0];
                 py[q] = on ? y : 0.f;
                 px[q] = on ? x : 0.f;
             }
@@ -200,7 +248,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
                 const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
                 xpre[q] = 0.f; gpre[q] = 0.f;
                 if (e < NA * 256 && m < a.M && tval[s]) {
-                    xpre[q] = ld_f32<COH>(&a.xres[(size_t)m * a.d + tile[s] * 16 + nl]);
+                    xpre[q] = a.xres_in[(size_t)m * a.d + tile[s] * 16 + nl];
                     gpre[q] = a.g_next[tile[s] * 16 + nl];
                 }
             }
@@ -216,8 +264,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
                 for (int q = 0; q < PRE_P; ++q)
                     if (j + q * J < a.P_in) { syy += py[q]; if (bid == 0) sxy += px[q]; }
                 for (int p = j + PRE_P * J; p < a.P_in; p += J) {
-                    syy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2 + 1]);
-                    if (bid == 0) sxy += ld_f32<COH>(&a.part_in[((size_t)p * 16 + m) * 2]);
+                    syy += a.part_in[((size_t)p * 16 + m) * 2 + 1];
+                    if (bid == 0) sxy += a.part_in[((size_t)p * 16 + m) * 2];
                 }
             }
         }
@@ -233,7 +281,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
     const u32x4* Xl;
     if constexpr (PACK) Xl = a.X + ((lane & 8) ? a.x_plane : 0) + (lane >> 4) * a.RS + ((lane & 7) < a.M ? (lane & 7) : 0);
     else Xl = a.X + (lane >> 4) * a.RS + ((lane & 15) < a.M ? (lane & 15) : 0);
-    stream_mma<T, NA, NPL, U, COH>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
+    stream_mma<T, NA, NPL, U>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early, dep);
     sum_partials();
 
 #pragma unroll
@@ -252,12 +300,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid) {
             float c = 0.f;
             if (bid == 0 && tid < a.M) {
                 if (a.fin_cos_rows) {            // the partials come from a residual-add kernel: finish its cosine
-                    const float xx = ld_f32<COH>(&a.ssq[tid]);
+                    const float xx = a.ssq_in[tid];
                     c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
                     c = fminf(1.f, fmaxf(-1.f, c));
                     a.fin_cos_rows[tid] = c;
                 }
-                st_f32<COH>(&a.ssq[tid], yy);
+                st_f32<COH>(&a.ssq_out[tid], yy);
             }
             fin_b[tid] = c;
         }
@@ -402,5 +450,6 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const u32x4* W, const u32
     GemmArgs b = a;
     b.W = W; b.W2 = W2; b.X = X; b.w_tile_stride = w_tile_stride; b.w_kb_stride = w_kb_stride; b.x_plane = x_plane;
     b.n_tiles = n_tiles; b.KB = KB; b.k_interleave = packed & 255; b.M = (packed >> 8) & 255; b.RS = packed >> 16;
-    gemm_block<T, EPI, TN, NW, U, false, PACK>(b, blockIdx.x);
+    __shared__ GemmLds<T, EPI, TN, NW, PACK> lds;
+    gemm_block<T, EPI, TN, NW, U, false, PACK>(b, blockIdx.x, lds);
 }

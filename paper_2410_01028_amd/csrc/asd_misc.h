@@ -7,21 +7,33 @@
 // grid (EMBED_SPLIT, rows): x = E[token], the tiled copy x * gain for the first kept norm, and this
 // workgroup's share of ||x||^2 as partial [split][16][2] (slot 1; slot 0 unused) for the next kernel.
 #define EMBED_SPLIT 8
+#define EMBED_THREADS 256
 template <class T, bool COH>
-__device__ __forceinline__ void embed_block(const typename T::elem* E, const int32_t* tokens, int d, const float* g_first, float* xres,
-                                            void* xb, size_t xb_plane, int rs, float* part, const int sp, const int m, float* red) {
+__device__ __forceinline__ void embed_block(const typename T::elem* E, const int32_t* tokens, int d, int vocab, DevState* st, const float* g_first,
+                                            float* xres, void* xb, size_t xb_plane, int rs, float* part, const int sp, const int m, float* red) {
     using El = typename T::elem;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const El* row = E + (size_t)tokens[m] * d;
+    // EMBED_THREADS threads work (the order of the sum of squares depends on that number); a larger workgroup's other
+    // threads only join the barriers
+    const int tid = threadIdx.x, nt = EMBED_THREADS;
+    // a token id that is not a row of the table (possible when the ids come from device memory the host never saw)
+    // must not become an address: it reads row 0 and raises the state's error bit
+    int tok = tokens[m];
+    if ((unsigned)tok >= (unsigned)vocab) {
+        tok = 0;
+        if (tid == 0 && sp == 0) __hip_atomic_fetch_or(&st->err, (int)DEV_ERR_TOKEN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const El* row = E + (size_t)tok * d;
     const int per = (d + EMBED_SPLIT - 1) / EMBED_SPLIT, lo = sp * per, hi = min(d, lo + per);
     float ss = 0.f;
-    for (int i = lo + tid; i < hi; i += nt) {
-        const float x = T::to_f32(row[i]);
-        st_f32<COH>(&xres[(size_t)m * d + i], x);
-        store_act<T, COH>(xb, xb_plane, rs, i, m, x * g_first[i]);
-        ss += x * x;
+    if (tid < nt) {
+        for (int i = lo + tid; i < hi; i += nt) {
+            const float x = T::to_f32(row[i]);
+            st_f32<COH>(&xres[(size_t)m * d + i], x);
+            store_act<T, COH>(xb, xb_plane, rs, i, m, x * g_first[i]);
+            ss += x * x;
+        }
+        red[tid] = ss;
     }
-    red[tid] = ss;
     __syncthreads();
     for (int s = nt / 2; s > 0; s >>= 1) {
         if (tid < s) red[tid] += red[tid + s];
@@ -31,15 +43,15 @@ __device__ __forceinline__ void embed_block(const typename T::elem* E, const int
     __syncthreads();
 }
 template <class T>
-__global__ __launch_bounds__(256) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d,
+__global__ __launch_bounds__(EMBED_THREADS) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d, int vocab, DevState* st,
                                                     const float* g_first, float* xres, void* xb, size_t xb_plane, int rs, float* part) {
-    __shared__ float red[256];
-    embed_block<T, false>(E, tokens, d, g_first, xres, xb, xb_plane, rs, part, blockIdx.x, blockIdx.y, red);
+    __shared__ float red[EMBED_THREADS];
+    embed_block<T, false>(E, tokens, d, vocab, st, g_first, xres, xb, xb_plane, rs, part, blockIdx.x, blockIdx.y, red);
 }
 
 // ---------------------------------------------------------------- decoding state
 __global__ void set_state_kernel(DevState* st, int pos, int emitted, int target, int reset_counts, int index_base = 0) {
-    st->pos = pos; st->emitted = emitted; st->target = target; st->index_base = index_base;
+    st->pos = pos; st->emitted = emitted; st->target = target; st->index_base = index_base; st->err = 0;
     if (reset_counts) { st->cycles = 0; st->drafted = 0; st->accepted = 0; }
 }
 __global__ void set_token_kernel(int32_t* tokbuf, int32_t tok) { tokbuf[0] = tok; }
@@ -58,7 +70,7 @@ struct AmaxCand { float v; int32_t i; float s; float pad; };
 __device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 // one workgroup; wave w handles rows w, w + (waves), ...; candidates are [workgroup][16 rows]
 template <bool COH>
-__device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+__device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M, int V, int32_t* argmax, int mode, int j_or_kk,
                                              DevState* st, int32_t* tokbuf, int32_t* out, int* win) {
     const int tid = threadIdx.x, lane = tid & 63, nw = blockDim.x >> 6;
     // what the accept step reads is requested now, so that it is there when the rows' winners are known
@@ -87,6 +99,12 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
         for (int o = 32; o > 0; o >>= 1) {
             const float ov = __shfl_xor(v, o); const int oi = __shfl_xor(idx, o);
             if (amax_better(ov, oi, v, idx)) { v = ov; idx = oi; }
+        }
+        // a row without a finite maximum (NaN weights) leaves no candidate: its token must still be a valid id,
+        // because the next pass uses it as an address into the embedding table
+        if ((unsigned)idx >= (unsigned)V) {
+            idx = 0;
+            if (lane == 0) __hip_atomic_fetch_or(&st->err, (int)DEV_ERR_LOGITS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         if (lane == 0) { win[m] = idx; argmax[m] = idx; }
         if (mode == FIN_DRAFT && m == 0) {
@@ -125,10 +143,10 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
         tokbuf[0] = win[a];
     }
 }
-__global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int32_t* argmax, int mode, int j_or_kk,
+__global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int V, int32_t* argmax, int mode, int j_or_kk,
                                                       DevState* st, int32_t* tokbuf, int32_t* out) {
     __shared__ int win[16];
-    finish_block<false>(cand, P, M, argmax, mode, j_or_kk, st, tokbuf, out, win);
+    finish_block<false>(cand, P, M, V, argmax, mode, j_or_kk, st, tokbuf, out, win);
 }
 
 // ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double

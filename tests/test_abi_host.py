@@ -48,6 +48,31 @@ def test_arena_sizing_and_config_validation():
     assert asd.lib().asd_create(None, None, 0, None, ctypes.byref(h)) == asd.E_INVAL
 
 
+def test_capacity_beyond_the_attention_merge_limit_is_refused():
+    """The decode-attention merge keeps the statistics of at most 256 groups of 256 keys per head: a cache of more than
+    65536 positions (after rounding up to whole pages) is refused when the engine is sized, not silently truncated."""
+    s = si.SHAPES["tiny"]
+    assert asd.arena_bytes(asd.make_config(s, asd.MAX_SEQ, page_tokens=256)) > 0
+    assert asd.arena_bytes(asd.make_config(s, asd.MAX_SEQ + 1, page_tokens=256)) == 0
+    assert asd.arena_bytes(asd.make_config(s, asd.MAX_SEQ - 36, page_tokens=192)) == 0      # 342 pages of 192 = 65664: rounds up past the limit
+    h = ctypes.c_void_p()
+    cfg = asd.make_config(s, asd.MAX_SEQ + 1, page_tokens=256)
+    assert asd.lib().asd_create(ctypes.byref(cfg), None, 1 << 40, None, ctypes.byref(h)) == asd.E_INVAL
+    assert b"ASD_MAX_SEQ" in asd.lib().asd_last_error(None)
+
+
+def test_debug_switches_are_configuration_fields_not_environment(monkeypatch):
+    """Launch-shape switches live in the configuration: the library reads no environment variable, so the arena it asks
+    for depends on the configuration alone."""
+    s = si.SHAPES["7b"]
+    base = asd.arena_bytes(asd.make_config(s, 1024))
+    for name in ("ASD_TUNE", "ASD_PF_TUNE", "ASD_PERSIST", "ASD_ATT_W4", "ASD_ATT_GH1", "ASD_RS_POW2", "ASD_SAMPLE_MEM"):
+        monkeypatch.setenv(name, "qkv=2,8,0,0" if "TUNE" in name else "1")
+    assert asd.arena_bytes(asd.make_config(s, 1024)) == base
+    tuned = asd.arena_bytes(asd.make_config(s, 1024, debug_flags=asd.DBG_STEP_KERNELS, debug_tune="o=2,8,0,0"))
+    assert tuned > 0
+
+
 def test_admg_matches_oracle_on_all_patterns():
     alpha = 0.985
     for L in range(1, 7):

@@ -31,9 +31,9 @@ def rel_err(got, want):
     return np.abs(got - want).max(-1) / np.abs(want).max(-1)
 
 
-def build_pair(shape, seed=0, max_seq=256, gain_std=0.0, page_tokens=64):
+def build_pair(shape, seed=0, max_seq=256, gain_std=0.0, page_tokens=64, debug_flags=0):
     W = list(si.all_tensors(shape, seed, gain_std))
-    eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens)).load(W)
+    eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens, debug_flags=debug_flags)).load(W)
     orc = oracle.Oracle(shape, max_seq, kv_storage=True).load(W)      # the engine's cache is in the storage type too
     return eng, orc
 
@@ -242,7 +242,9 @@ def test_argument_validation_on_device_engine():
 
 
 def test_long_context_merge_paths():
-    """More than 16 chunks per head (the merge's second loop) and a shuffled page table, bf16 GQA shape."""
+    """A context of 22 chunks = 6 groups of 256 keys per head (the groups' partial results merged by the last group to
+    arrive) and a shuffled page table, bf16 GQA shape.  Contexts of more than 16 groups per head, where the merge takes
+    its second loop, are in test_gpu_long_context.py."""
     shape = BF_GQA
     W = list(si.all_tensors(shape, 11, gain_std=0.1))
     eng = asd.Engine(asd.make_config(shape, 1536, page_tokens=128)).load(W)
@@ -302,24 +304,35 @@ def test_graph_replays_match_eager():
         assert ms > 0
 
 
-def test_persistent_pass_kernel_matches_step_kernels_bitwise(monkeypatch):
-    """The one-launch-per-pass kernel (development switch ASD_PERSIST) runs the same block functions with
-    coherent accesses and grid barriers: logits, cosines and generated tokens must equal the per-step path.  The
-    persistent kernel's workgroups have 8 waves; the per-step engine is pinned to the same split of K (its QKV launch
-    would otherwise take 4 waves per workgroup, which sums a row's K range in a different order)."""
-    monkeypatch.setenv("ASD_TUNE", "qkv=1,8,1,1")
-    shape = MID16
-    toks = si.prompt(8, 150, shape.vocab)
+@pytest.mark.parametrize("shape", [MID16, si.SHAPES["tiny"], BF_GQA], ids=lambda s: s.name)
+def test_dataflow_pass_kernel_matches_step_kernels_bitwise(shape):
+    """The one-launch-per-pass kernel runs the same block functions as the per-step kernels, with write-through stores,
+    per-step output buffers and completion counters between the steps: logits, cosines and generated tokens must equal
+    the per-step path bit for bit, for packed (<= 8 rows) and two-operand passes, one and several attention groups,
+    and under skip masks.  The per-step engine is pinned to the dataflow kernel's launch shapes (8 waves per
+    workgroup, one tile per workgroup for QKV and gate/up), which fix the order of every sum."""
+    toks = si.prompt(8, 700, shape.vocab)
     mask = np.zeros(2 * shape.n_layers, np.uint8); mask[1] = mask[4] = 1
     results = []
-    for persist in ("0", "1"):
-        monkeypatch.setenv("ASD_PERSIST", persist)
-        eng = asd.Engine(asd.make_config(shape, 320)).init_synthetic(5)
+    for flags, tune in ((asd.DBG_STEP_KERNELS, "qkv=1,8,1,1;gu=1,8,0,0"), (0, None)):
+        eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags, debug_tune=tune)).init_synthetic(5)
+        got = []
         first, acs, lg = eng.prefill(toks[:140], want_logits=True)
-        a = eng.forward(toks[140:145], 140, commit=False)
-        b = eng.forward(toks[140:141], 140, mask, commit=False)
+        got += [first, acs, lg]
+        for M, skip in ((5, None), (1, mask), (9, None), (16, mask), (1, None), (8, None)):
+            r = eng.forward(toks[140:140 + M], 140, skip, commit=False)
+            got += [r["logits"], r["cos_rows"], r["cos"], r["argmax"]]
         out, st, _ = eng.generate(toks[:100], 20, 3, fixed_mask=mask, use_graphs=False)
-        results.append((first, acs, lg, a["logits"], a["cos_rows"], b["logits"], out, st["accepted"]))
+        got += [out, st["accepted"]]
+        eng.prefill(toks[:600])                                # three attention groups per head
+        pos = 600
+        for M in (1, 4, 9, 2):
+            r = eng.forward(toks[pos:pos + M], pos)
+            got += [r["logits"], r["cos_rows"]]
+            pos += M
+        out, st, _ = eng.decode(int(toks[pos]), 30, 4, alpha=0.9, m=2, n=1)
+        got += [out, st["accepted"]]
+        results.append(got)
         eng.close()
     for x, y in zip(*results):
         assert np.array_equal(np.asarray(x), np.asarray(y))
@@ -355,18 +368,14 @@ def test_degenerate_sizes():
     assert np.abs(acs - o["cos"]).max() < COS_TOL
 
 
-def test_attention_register_variants_give_the_same_bits(monkeypatch):
+def test_attention_register_variants_give_the_same_bits():
     """Long contexts launch the attention kernel compiled for four waves per SIMD; short ones the one that keeps a
     whole chunk in flight per wave.  Same arithmetic: forcing the former everywhere must not change a bit."""
     shape = MID16
     toks = si.prompt(4, 700, shape.vocab)
     outs = []
-    for force in (False, True):
-        if force:
-            monkeypatch.setenv("ASD_ATT_W4", "1")
-        else:
-            monkeypatch.delenv("ASD_ATT_W4", raising=False)
-        eng = asd.Engine(asd.make_config(shape, 768)).init_synthetic(2)
+    for flags in (asd.DBG_STEP_KERNELS, asd.DBG_STEP_KERNELS | asd.DBG_ATT_W4):
+        eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags)).init_synthetic(2)
         eng.prefill(toks[:690])
         a = eng.forward(toks[690:695], 690)
         b = eng.forward(toks[695:696], 695)
@@ -380,19 +389,15 @@ GQA8 = si.Shape("gqa8", 2, 256, 16, 2, 64, 688, 1024, si.DT_BF16, 40, 12, 4)
 
 
 @pytest.mark.parametrize("shape", [BF_GQA, MID16, GQA8, SMALL_GQA], ids=lambda s: s.name)
-def test_query_heads_per_attention_workgroup_give_the_same_bits(shape, monkeypatch):
+def test_query_heads_per_attention_workgroup_give_the_same_bits(shape):
     """Grouped-query models: a decode-attention workgroup takes as many query heads of a KV head as fit the 16
     matrix-core columns beside the rows of the pass (8 heads for 1-2 rows ... 1 head for 9-16 rows).  Columns are
     independent, so one head per workgroup must give the same bits, for short contexts (one 256-key group) and
     contexts of several groups alike."""
     toks = si.prompt(6, 700, shape.vocab)
     outs = []
-    for single in (False, True):
-        if single:
-            monkeypatch.setenv("ASD_ATT_GH1", "1")
-        else:
-            monkeypatch.delenv("ASD_ATT_GH1", raising=False)
-        eng = asd.Engine(asd.make_config(shape, 768)).init_synthetic(5)
+    for flags in (0, asd.DBG_ATT_GH1, asd.DBG_STEP_KERNELS, asd.DBG_STEP_KERNELS | asd.DBG_ATT_GH1):
+        eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags)).init_synthetic(5)
         got = []
         pos = 0
         for M in (1, 2, 3, 4, 5, 8, 9, 16, 1):                 # one group per head
@@ -409,8 +414,10 @@ def test_query_heads_per_attention_workgroup_give_the_same_bits(shape, monkeypat
         got.append(out)
         outs.append(got)
         eng.close()
-    for x, y in zip(*outs):
-        assert np.array_equal(x, y)
+    # (dataflow and per-step engines split K differently in two launches: compare each with its own single-head variant)
+    for a, b in ((0, 1), (2, 3)):
+        for x, y in zip(outs[a], outs[b]):
+            assert np.array_equal(x, y)
 
 
 # K sizes that put a wave's share of the weight stream (K / 32 k-blocks over 8 waves, ring of 4 slots) into every
@@ -437,18 +444,14 @@ def test_weight_stream_ring_phases_against_oracle(shape):
         pos += n
 
 
-def test_row_stride_of_the_activation_buffers_does_not_change_a_bit(monkeypatch):
+def test_row_stride_of_the_activation_buffers_does_not_change_a_bit():
     """The tiled activation buffers of an M-row pass have a row stride of M (the bytes every GEMM workgroup reads grow
     with it); a stride of the next power of two is only a different layout: same operands, same order, same bits."""
     shape = MID16
     toks = si.prompt(8, 400, shape.vocab)
     outs = []
-    for pow2 in (False, True):
-        if pow2:
-            monkeypatch.setenv("ASD_RS_POW2", "1")
-        else:
-            monkeypatch.delenv("ASD_RS_POW2", raising=False)
-        eng = asd.Engine(asd.make_config(shape, 512)).init_synthetic(4)
+    for flags in (0, asd.DBG_RS_POW2):
+        eng = asd.Engine(asd.make_config(shape, 512, debug_flags=flags)).init_synthetic(4)
         got = []
         eng.prefill(toks[:300])
         pos = 300

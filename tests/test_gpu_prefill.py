@@ -1,6 +1,6 @@
 """GPU parity of the prompt pass taken in blocks (large-M contractions) against the CPU oracle.
 
-What is checked after a prompt of n tokens: the ACS of every sublayer (Eq. 2; 1e-3 absolute), the last row's
+What is checked after a prompt of n tokens: the ACS of every sublayer (Section 3.2, the definition of C_l; 1e-3 absolute), the last row's
 logits (2e-2 bf16 / 1e-4 fp32, inf-norm relative), the first greedy token where the oracle's top-2 gap is clear,
 and the KV cache the pass wrote, through a teacher-forced multi-row pass right behind it.  Prompt lengths
 cover a ragged last 16-row chunk, a ragged last workgroup row block, contexts that span several 256-key
@@ -10,6 +10,7 @@ import numpy as np
 import pytest
 
 import asd_inputs as si
+import paper_2410_01028_amd as asd
 from helpers import SMALL_GQA
 from test_gpu_parity import BF_GQA, MID16, MID32, TOL, COS_TOL, build_pair, check_forward, rel_err
 
@@ -81,17 +82,13 @@ def test_block_boundaries_agree_with_the_chunked_pass(n):
 
 
 @pytest.mark.parametrize("force_w4", [False, True], ids=["default-attention", "four-waves-per-simd-attention"])
-def test_long_context_against_oracle(force_w4, monkeypatch):
+def test_long_context_against_oracle(force_w4):
     """A context of ten 256-key groups per head on a small grouped-query model: the blocked prompt pass (five 512-row
     blocks), then multi-row and single-row passes on top of it, against the oracle; once with the decode attention
     variant that long contexts on large models select."""
-    if force_w4:
-        monkeypatch.setenv("ASD_ATT_W4", "1")
-    else:
-        monkeypatch.delenv("ASD_ATT_W4", raising=False)
     shape = BF_GQA
     n = 2500
-    eng, orc = build_pair(shape, seed=7, max_seq=n + 40)
+    eng, orc = build_pair(shape, seed=7, max_seq=n + 40, debug_flags=asd.DBG_ATT_W4 if force_w4 else 0)
     toks = si.prompt(3, n + 20, shape.vocab)
     first, acs, lg = eng.prefill(toks[:n], want_logits=True)
     o = orc.forward(toks[:n], 0)

@@ -123,7 +123,7 @@ def test_sampled_loop_against_oracle():
     assert compared >= 8
 
 
-def test_register_and_memory_variants_of_the_sampling_kernels_draw_the_same(monkeypatch):
+def test_register_and_memory_variants_of_the_sampling_kernels_draw_the_same():
     """The sampling kernels hold a thread's share of a logit row in registers when the vocabulary allows it, and read
     it from memory at every use otherwise: the same arithmetic in the same order, so the same draws, bit for bit
     (drafts, accepted counts, replacements, and a whole sampled decode)."""
@@ -131,11 +131,7 @@ def test_register_and_memory_variants_of_the_sampling_kernels_draw_the_same(monk
     rng = np.random.default_rng(11)
     outs = []
     for mem in (False, True):
-        if mem:
-            monkeypatch.setenv("ASD_SAMPLE_MEM", "1")
-        else:
-            monkeypatch.delenv("ASD_SAMPLE_MEM", raising=False)
-        eng = asd.Engine(asd.make_config(shape, 128)).init_synthetic(3)
+        eng = asd.Engine(asd.make_config(shape, 128, debug_flags=asd.DBG_SAMPLE_MEM if mem else 0)).init_synthetic(3)
         got = []
         r = np.random.default_rng(5)
         for case in range(12):
