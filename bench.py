@@ -92,7 +92,6 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras")
     ap.add_argument("--n-new", type=int, default=None, help="override the workload's number of new tokens (profiling runs)")
     ap.add_argument("--copy-only-extra", action="store_true", help="with --no-extras: still run the plain copy kernel (counter calibration)")
-    ap.add_argument("--step-kernels", action="store_true", help="development: one launch per step for every pass instead of the dataflow pass kernel")
     ap.add_argument("--only-verify-passes", type=int, default=0, metavar="N",
                     help="counter runs: after the prompt pass launch N eager (draft_len+1)-row verification passes and exit")
     args = ap.parse_args()
@@ -110,7 +109,7 @@ def main():
     k = args.draft_len if args.draft_len is not None else shape.draft_len
     P, N = shape.prompt_len, (args.n_new or shape.n_new)
     max_seq = P + N + 16
-    eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens=256, debug_flags=asd.DBG_STEP_KERNELS if args.step_kernels else 0))
+    eng = asd.Engine(asd.make_config(shape, max_seq, page_tokens=256))
     eng.init_synthetic(seed)
     prompt = si.prompt(seed, P, shape.vocab)
     L2 = 2 * shape.n_layers

@@ -78,15 +78,13 @@ typedef struct {
  *   ASD_DBG_ATT_GH1     one query head per decode-attention workgroup also for grouped-query models
  *   ASD_DBG_RS_POW2     row stride of the activation buffers = next power of two >= rows (default: rows)
  *   ASD_DBG_SAMPLE_MEM  sampling kernels that re-read their logit rows from memory
- *   ASD_DBG_STEP_KERNELS  one launch per step for every pass (default: one dataflow launch per pass
- *                       where that path applies; the two differ only in launch structure)
  * debug_tune: "name=a,b,c,d;..." with name in {qkv, o, gu, down, lm}: tiles per workgroup, waves per
  * workgroup, k-major layout (0/1), interleaved k-blocks (0/1); and name in {pf_qkv, pf_o, pf_gu,
  * pf_down}: 16-row chunks per workgroup, K slices[, prefetch depth] of the prompt-block GEMMs.  A
  * layout override changes how weights are tiled in the arena, never their values.  The string is
  * copied by asd_create.
  */
-enum { ASD_DBG_ATT_W4 = 1, ASD_DBG_ATT_GH1 = 2, ASD_DBG_RS_POW2 = 4, ASD_DBG_SAMPLE_MEM = 8, ASD_DBG_STEP_KERNELS = 16 };
+enum { ASD_DBG_ATT_W4 = 1, ASD_DBG_ATT_GH1 = 2, ASD_DBG_RS_POW2 = 4, ASD_DBG_SAMPLE_MEM = 8 };
 
 /*
  * Parameters of speculative generation.  alpha, m, n are Algorithm 1's inputs

@@ -19,7 +19,7 @@ DT_F32, DT_BF16 = 0, 1
 MAX_ROWS = 16
 MAX_SEQ = 65536
 # development / test switches of Config.debug_flags (none changes what is computed)
-DBG_ATT_W4, DBG_ATT_GH1, DBG_RS_POW2, DBG_SAMPLE_MEM, DBG_STEP_KERNELS = 1, 2, 4, 8, 16
+DBG_ATT_W4, DBG_ATT_GH1, DBG_RS_POW2, DBG_SAMPLE_MEM = 1, 2, 4, 8
 KERNEL_CLASSES = ("embed", "qkv", "attn", "oproj", "gateup", "down", "lmhead", "finish")
 
 

@@ -65,7 +65,7 @@ struct AttnArgs {
 // Pair p of the n_pairs pairs of a workgroup's heads is head head0 + p / M, row p % M; this call takes pairs
 // p0 .. p0 + ATT_RB - 1.  Chunk statistics with one chunk per lane, outputs with two head dims per lane; all
 // loads of a round are requested before any is used.  One wave.
-template <class T, int H, bool COH>
+template <class T, int H>
 __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, int p0, int n_pairs, int pos0, int lane) {
     const bool mine = 2 * lane < H;
     {
@@ -127,8 +127,8 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, in
                 }
             }
             if (mine) {
-                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + 2 * lane, mm, acc.x / L);
-                store_act<T, COH>(a.out, a.out_plane, a.RS, head * H + 2 * lane + 1, mm, acc.y / L);
+                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane, mm, acc.x / L);
+                store_act<T>(a.out, a.out_plane, a.RS, head * H + 2 * lane + 1, mm, acc.y / L);
             }
         }
     }
@@ -185,7 +185,7 @@ __device__ __forceinline__ void att_pfrags(const f32x4 (&s)[4], u32x4 (&pf)[64 /
 }
 // Merge a group's chunks through LDS, ATT_RH columns per pass, ascending chunk order; the result goes to the output
 // (a context of one group) or to the group's partial.  Synchronises the workgroup; the chunk statistics are in sml.
-template <class T, int H, bool COH>
+template <class T, int H>
 __device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int head, bool valid, int n_groups, int n_cols, int hw, int lane,
                                                 const f32x4 (&o)[H / 16], float* so, const float* sml) {
     constexpr int HT = H / 16;
@@ -212,7 +212,7 @@ __device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int 
                 }
             }
             if (n_groups == 1) {
-                store_act<T, COH>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
+                store_act<T>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
             } else {
                 const size_t row = ((size_t)hh * a.nc_stride + grp) * ASD_ROWS + mm;
                 coherent_store(a.o_part + row * H + hd, acc);
@@ -229,7 +229,7 @@ __device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int 
 // every gh.  Every thread of the calling workgroup must call this the same
 // number of times (it synchronises the workgroup); `valid` = false makes the group a no-op, hw is the wave's
 // index inside its group.  so: [ATT_GW][ATT_RH][H] floats, sml: [ATT_GW][16][2] floats, s_old: 1 word, per group.
-template <class T, int H, bool COH, bool EARLY = false>
+template <class T, int H, bool EARLY = false>
 __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, const int head, const bool valid, const int hw,
                                            const int lane, float* so, float* sml, unsigned* s_old) {
     using E = typename T::elem;
@@ -308,7 +308,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
     }
     if (g == 0) { sml[(hw * ASD_ROWS + m) * 2] = mx; sml[(hw * ASD_ROWS + m) * 2 + 1] = l; }
 
-    att_group_merge<T, H, COH>(a, grp, head, live, n_groups, n_cols, hw, lane, o, so, sml);
+    att_group_merge<T, H>(a, grp, head, live, n_groups, n_cols, hw, lane, o, so, sml);
     if (n_groups == 1) return;
 
     // ---- arrival: the group that completes the head's last outstanding group merges the groups
@@ -323,7 +323,7 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         if (hw == 0 && lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int n_pairs = a.gh * a.M;
-        for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H, COH>(a, head, p0, n_pairs, pos0, lane);
+        for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H>(a, head, p0, n_pairs, pos0, lane);
     }
     __syncthreads();
 }
@@ -365,7 +365,7 @@ __global__ __launch_bounds__(ATT_GW * 64) void attn_kernel(ATT_HOT_PARAMS, const
     if (!attn_unit(a, blockIdx.x, &grp, &head)) return;
     // (a group no row of this call sees does nothing: every wave of it is inactive, and a context of one group
     // returns before the arrival)
-    attn_group<T, H, false, true>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
+    attn_group<T, H, true>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
 }
 
 // The same kernel with the register allocation held to four waves per SIMD (128 registers instead of ~220): a wave
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(ATT_GW * 64, 4) void attn_kernel_w4(ATT_HOT_PARAMS,
     int grp, head;
     if (!attn_unit(a, blockIdx.x, &grp, &head)) return;
     if (grp * ATT_GROUP > a.st->pos + a.pos_off + a.M - 1) return;
-    attn_group<T, H, false>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
+    attn_group<T, H>(a, grp, head, true, __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), threadIdx.x & 63, so, sml, &s_old);
 }
 
 // ---------------------------------------------------------------- prompt blocks: causal attention

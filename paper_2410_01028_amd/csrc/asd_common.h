@@ -107,39 +107,13 @@ template <class T> __device__ __forceinline__ size_t act_index(int k, int m, int
     return ((size_t)(k / T::KE) * rs + m) * T::KE + (k % T::KE);
 }
 
-// Memory accesses to data that another workgroup of the SAME kernel produced or will consume (COH = true) are
-// device-scope relaxed atomics: they are served past the per-XCD L2, which is not coherent across XCDs, so
-// no cache-wide fence is needed.  Between kernels (COH = false) plain accesses are enough.
-template <bool COH> __device__ __forceinline__ float ld_f32(const float* p) {
-    if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); else return *p;
-}
-template <bool COH> __device__ __forceinline__ void st_f32(float* p, float v) {
-    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); else *p = v;
-}
-template <bool COH> __device__ __forceinline__ void st_u16(uint16_t* p, uint16_t v) {
-    if constexpr (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); else *p = v;
-}
-template <bool COH> __device__ __forceinline__ u32x4 ld_frag(const u32x4* p) {      // 16 bytes, 16-byte aligned
-    if constexpr (COH) {
-        const uint64_t lo = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint64_t hi = __hip_atomic_load((const uint64_t*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return u32x4{(uint32_t)lo, (uint32_t)(lo >> 32), (uint32_t)hi, (uint32_t)(hi >> 32)};
-    } else {
-        return *p;
-    }
-}
-template <class T, bool COH> __device__ __forceinline__ void st_elem(typename T::elem* p, typename T::elem v) {
-    if constexpr (sizeof(typename T::elem) == 2) st_u16<COH>((uint16_t*)p, (uint16_t)v);
-    else st_f32<COH>((float*)p, (float)v);
-}
-
 // write value v of (feature k, row m) into every plane of a tiled activation buffer (plane stride in elements)
-template <class T, bool COH = false>
+template <class T>
 __device__ __forceinline__ void store_act(void* base, size_t plane, int rs, int k, int m, float v) {
     typename T::elem* p = (typename T::elem*)base + act_index<T>(k, m, rs);
     const typename T::elem hi = T::from_f32(v);
-    st_elem<T, COH>(p, hi);
-    if constexpr (T::NP == 2) st_elem<T, COH>(p + plane, T::from_f32(v - T::to_f32(hi)));
+    *p = hi;
+    if constexpr (T::NP == 2) p[plane] = T::from_f32(v - T::to_f32(hi));
 }
 
 // four consecutive features n0..n0+3 (n0 % 4 == 0) of row m of one chunk, all planes

@@ -5,8 +5,8 @@
 #include "asd_attn.h"
 #include "asd_common.h"
 #include "asd_gemm.h"
-#include "asd_flow.h"
 #include "asd_misc.h"
+#include "asd_pass.h"
 #include "asd_prefill.h"
 #include "asd_sample.h"
 
@@ -38,11 +38,6 @@ struct Profiler {
     std::vector<int> cls;
     std::vector<double> bytes;
 };
-
-// a pass's step table in device memory (dataflow kernel)
-struct FlowTable { const PassOp* ops; const uint16_t* op_of_block; int n_ops, n_blocks; };
-// sizes of the dataflow kernel's per-step buffers and tables (see flow_sizes)
-struct FlowSizes { size_t ws_bytes; int max_ops, max_blocks; size_t act_d, act_q, act_f, q_bytes, xres, part, ssq; };
 
 }  // namespace
 
@@ -91,16 +86,6 @@ struct asd_engine {
     bool acs_valid;
     DevState* h_st;                     // pinned
     std::map<std::vector<int>, hipGraphExec_t> graphs;
-    // dataflow pass kernel: per-step output buffers, completion counters, cached step tables
-    bool flow = false;
-    FlowSizes fs{};
-    char* flow_ws = nullptr;
-    size_t flow_ws_bytes = 0;
-    unsigned* flow_done = nullptr;
-    int32_t* flow_err = nullptr;
-    char* ops_region = nullptr;
-    size_t ops_bytes = 0, ops_used = 0;
-    std::map<std::vector<int>, FlowTable> op_cache;
     std::vector<uint8_t> graph_mask;
     std::string tune;                   // copy of the configuration's debug_tune
     bool sample_mem = false;            // ASD_DBG_SAMPLE_MEM: sampling kernels that re-read memory instead of holding their segments
@@ -205,14 +190,11 @@ GemmCfg pick_cfg(const asd_config& c, int epi, int cls, int tiles, int KB) {
     if (cls == ASD_K_OPROJ && KB >= 256) { g.kmajor = 1; g.TN = 1; }
     if (cls == ASD_K_DOWN && KB >= 512) g.kmajor = 0;
     g.kint = g.kmajor;
-    // Waves per workgroup: 8.  With one launch per step for every pass (ASD_DBG_STEP_KERNELS) two launches do better
-    // with 4 waves and twice the loads in flight each (QKV; gate/up with two tile pairs per workgroup: 1-4 % per
-    // launch on the 7B, 13B and 70B shapes).  The dataflow pass kernel runs 8-wave workgroups, and the per-step
-    // kernels that serve beside it (passes it does not take, profiling) must split K the same way, or a row's bits
-    // would depend on which path ran it.
-    const bool steps_only = (c.debug_flags & ASD_DBG_STEP_KERNELS) != 0;
-    g.NW = (steps_only && (cls == ASD_K_QKV || (cls == ASD_K_GATEUP && g.TN == 2))) ? 4 : 8;
-    if (!steps_only && (cls == ASD_K_QKV || cls == ASD_K_GATEUP)) g.TN = 1;      // (the dataflow kernel's shapes for these two)
+    // Waves per workgroup: 8, except where a launch has more workgroups than two rounds of 8-wave workgroups can
+    // hold at once and its waves finish far apart (QKV; gate/up with two tile pairs per workgroup): there 4 waves with
+    // twice the loads in flight each (the same bytes per workgroup, half the waves to join) measured 1-4 % faster per
+    // launch on the 7B, 13B and 70B shapes.
+    g.NW = (cls == ASD_K_QKV || (cls == ASD_K_GATEUP && g.TN == 2)) ? 4 : 8;
     static const char* names[ASD_K_COUNT] = {"", "qkv", "", "o", "gu", "down", "lm", ""};       // indexed by kernel class
     int v[4];
     if (tune_entry(c.debug_tune, names[cls], v, 4) == 4) { g.TN = v[0]; g.NW = v[1]; g.kmajor = v[2]; g.kint = v[3]; }
@@ -226,33 +208,9 @@ struct Plan {
     size_t xres, ssq, part, cos_rows, logits, o_part, rope, ml_part, arrivals, xb, q, attn_out, hmid, counters, cos_acc, amax_part,
         argmax, tokbuf, out_tokens, st, ops, ops_bytes, staging, staging_bytes, total, qlogits;
     size_t pf_tok, pf_xres, pf_raw, pf_ssq, pf_rscale, pf_cos_rows, pf_xb, pf_q, pf_attn_out, pf_hmid;
-    size_t flow_ws, flow_ws_bytes, flow_done, flow_err;
     int es, KE, KBd, KBq, KBf, n_pages, nc_stride, qkv_tiles;
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
 };
-
-// Sizes of the dataflow kernel's regions for a configuration.  Per-step output buffers (each written once per launch):
-// tiled activations are sized for 16 rows whatever the pass's row count, as the per-step path's buffers are.
-int round8(int x) { return (x + 7) / 8 * 8; }
-FlowSizes flow_sizes(const asd_config& c, const Plan& p) {
-    FlowSizes f{};
-    const size_t frag = 1024;
-    const int NPL = c.dtype == ASD_DT_BF16 ? 2 : 1;
-    f.act_d = align_up((size_t)p.KBd * frag * NPL); f.act_q = align_up((size_t)p.KBq * frag * NPL); f.act_f = align_up((size_t)p.KBf * frag * NPL);
-    f.q_bytes = align_up((size_t)c.n_heads * c.head_dim * ASD_ROWS * p.es * NPL);
-    f.xres = align_up((size_t)ASD_ROWS * c.d_model * 4);
-    int pmax = p.g_o.grid > p.g_down.grid ? p.g_o.grid : p.g_down.grid;
-    if (pmax < EMBED_SPLIT) pmax = EMBED_SPLIT;
-    f.part = align_up((size_t)pmax * ASD_ROWS * 2 * 4);
-    f.ssq = 256;
-    const size_t per_layer = 2 * f.act_d + f.q_bytes + f.act_q + f.act_f + 2 * f.xres + 2 * f.part + 2 * f.ssq;
-    f.ws_bytes = per_layer * c.n_layers + f.act_d + f.xres + f.part + 2 * f.ssq;
-    f.max_ops = 5 * c.n_layers + 3;
-    const int att_units = attn_grid(c.n_heads, c.n_kv_heads, p.nc_stride, 1);
-    const long per_layer_blocks = (long)round8(p.qkv_tiles) + round8((att_units + 1) / 2) + round8(p.g_o.grid) + round8(c.d_ffn / 16) + round8(p.g_down.grid);
-    f.max_blocks = (int)(per_layer_blocks * c.n_layers + round8(EMBED_SPLIT * ASD_ROWS) + round8(p.g_lm.grid) + 8);
-    return f;
-}
 
 Plan make_plan(const asd_config& c) {
     Plan p{};
@@ -315,17 +273,6 @@ Plan make_plan(const asd_config& c) {
     p.tokbuf = take(64 * 4);
     p.out_tokens = take((size_t)(p.n_pages * c.page_tokens + 64) * 4);
     p.st = take(sizeof(DevState));
-    // dataflow pass kernel: every step writes buffers of its own (see flow_sizes), a completion counter per step and
-    // shard, and ~24 cached step tables (steps + the step of every workgroup of the grid)
-    {
-        const FlowSizes fs = flow_sizes(c, p);
-        p.flow_ws_bytes = fs.ws_bytes;
-        p.flow_ws = take(p.flow_ws_bytes);
-        p.flow_done = take((size_t)fs.max_ops * FLOW_SHARDS * FLOW_SHARD_WORDS * 4);
-        p.flow_err = take(256);
-        p.ops_bytes = 24 * (align_up((size_t)fs.max_ops * sizeof(PassOp)) + align_up((size_t)fs.max_blocks * 2));
-        p.ops = take(p.ops_bytes);
-    }
     size_t biggest = (size_t)c.vocab * c.d_model;
     if ((size_t)c.d_ffn * c.d_model > biggest) biggest = (size_t)c.d_ffn * c.d_model;
     if ((size_t)qd * c.d_model > biggest) biggest = (size_t)qd * c.d_model;
@@ -524,80 +471,56 @@ struct Prof {
     void end() { if (p) hipEventRecord(p->ev.back(), s); }
 };
 
-// Where a pass's results go: the engine's own buffers, or a caller's device buffers.
+// Where a pass's results go (the engine's own buffers, or a caller's device buffers) and where its kernels keep what
+// they exchange: partial sums, attention partials and their arrival counters, argmax candidates (the engine's arena,
+// or another region a caller of build_pass names).
 struct PassOut {
     float* logits;       // [rows][vocab]
     int32_t* argmax;     // [16]
+    float *ssq, *part, *cos_rows;
+    double* cos_acc;
+    float *o_part, *ml_part;
+    unsigned* arrivals;
+    AmaxPart* amax_part;
+    int nc_stride;       // groups per head in o_part / ml_part
 };
-
-// Buffers of the embedding step (its outputs are the inputs of the first kept sublayer)
-struct EmbedBufs { float* xres; void* xb; float* part; };
+PassOut engine_out(const asd_engine* e) {
+    return PassOut{e->logits, e->argmax, e->ssq, e->part, e->cos_rows, e->cos_acc, e->o_part, e->ml_part, e->arrivals, e->amax_part, e->nc_stride};
+}
 
 // The steps of one forward pass of M rows (first row at cache position st->pos + pos_off) under a skip mask:
-// a removed sublayer contributes no step at all.  The same list drives the per-step kernels and the dataflow
-// pass kernel.  flow = false: every step works on the engine's one set of activation buffers (a step's launch ends
-// before the next one starts).  flow = true: every step writes buffers of its own, taken in step order from the
-// dataflow workspace, so that nothing written inside the launch is written twice, and the steps get their place in
-// the launch's grid and the step they wait for.
-void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_for_bytes, int nc, bool flow, const PassOut& out,
-                std::vector<PassOp>& ops, EmbedBufs* emb) {
+// a removed sublayer contributes no step at all.
+void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_for_bytes, int nc, const PassOut& out, std::vector<PassOp>& ops) {
     const asd_config& c = e->c;
     double cls_bytes[ASD_K_COUNT];
     pass_bytes(e, nullptr, ctx_for_bytes, cls_bytes);   // full-model totals; per-sublayer figures divide by L
     const double L = c.n_layers;
     const int RS = row_stride(e, M);
     ops.clear();
-    int next_block = 0;
     auto push = [&](int type, int cls, int grid, double bytes) -> PassOp& {
         PassOp op{};
-        op.type = type; op.cls = cls; op.grid = grid; op.bytes = bytes; op.tn = 1;
-        op.first_block = next_block;
-        op.n_blocks = type == OP_FINISH ? 1 : round8(grid);
-        op.dep = (int)ops.size() - 1;
-        for (int sh = 0; sh < FLOW_SHARDS; ++sh) op.dep_target[sh] = ops.empty() ? 0 : ops.back().n_blocks / FLOW_SHARDS;
-        next_block += op.n_blocks;
+        op.type = type; op.cls = cls; op.grid = grid; op.bytes = bytes;
         ops.push_back(op);
         return ops.back();
     };
-    // per-step buffers of the dataflow kernel, taken in step order
-    const FlowSizes fs = flow ? e->fs : FlowSizes{};
-    size_t ws_off = 0;
-    auto take = [&](size_t bytes) { char* ptr = e->flow_ws + ws_off; ws_off += bytes; return ptr; };
-
-    float* cur_xres = e->xres;          // residual stream as of the last step that wrote it
-    void* cur_xb = e->xb;               // its tiled, gained copy
-    float* cur_part = e->part;          // that step's partial sums
-    float* cur_ssq = e->ssq;            // ||residual row||^2 as of the last finished cosine tap
-    if (flow) { cur_xres = (float*)take(fs.xres); cur_xb = take(fs.act_d); cur_part = (float*)take(fs.part); cur_ssq = (float*)take(fs.ssq); }
-    emb->xres = cur_xres; emb->xb = cur_xb; emb->part = cur_part;
     push(OP_EMBED, ASD_K_EMBED, EMBED_SPLIT * M, 0);
 
     GemmArgs base{};
-    base.M = M; base.RS = RS; base.inv_d = 1.f / (float)c.d_model; base.eps = c.rms_eps;
-    base.d = c.d_model;
+    base.M = M; base.RS = RS; base.ssq = out.ssq; base.inv_d = 1.f / (float)c.d_model; base.eps = c.rms_eps;
+    base.xres = e->xres; base.xb = e->xb; base.part = out.part; base.d = c.d_model;
     base.st = e->st; base.pos_off = pos_off; base.rope = e->rope; base.page_table = e->page_table;
     base.n_h = c.n_heads; base.n_kv = c.n_kv_heads; base.h = c.head_dim; base.page_tokens = c.page_tokens;
     base.xb_plane = (int64_t)e->KBd * 64 * e->KE; base.hmid_plane = (int64_t)e->KBf * 64 * e->KE;
     base.q_plane = (int64_t)c.n_heads * c.head_dim * ASD_ROWS;
-    base.logits = out.logits; base.V = c.vocab; base.amax_part = e->amax_part;
+    base.logits = out.logits; base.V = c.vocab; base.amax_part = out.amax_part;
     // the cosine tap still open: partials of the last residual-add step and where its cosine goes
     // (the embedding leaves EMBED_SPLIT partials of ||x||^2 and no cosine to finish)
     int open_P = EMBED_SPLIT, open_sub = -1;
     // a step that reads the normed residual: its input, the producing step's partials, the open cosine tap
     auto consume = [&](GemmArgs& g) {
-        g.X = (const u32x4*)cur_xb; g.x_plane = (int64_t)e->KBd * 64;
-        g.part_in = cur_part; g.P_in = open_P;
-        g.ssq_in = cur_ssq;
-        if (flow) cur_ssq = (float*)take(fs.ssq);
-        g.ssq_out = cur_ssq;
-        if (open_sub >= 0) { g.fin_cos_rows = e->cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = e->cos_acc + open_sub; }
-    };
-    // a residual-add step: reads the residual stream, writes the new one, its gained copy and its partials
-    auto produce = [&](GemmArgs& g, int sublayer) {
-        g.xres_in = cur_xres;
-        if (flow) { cur_xres = (float*)take(fs.xres); cur_xb = take(fs.act_d); cur_part = (float*)take(fs.part); }
-        g.xres = cur_xres; g.xb = cur_xb; g.part = cur_part;
-        g.g_next = next_gain(e, mask, sublayer);
+        g.X = (const u32x4*)e->xb; g.x_plane = (int64_t)e->KBd * 64;
+        g.part_in = out.part; g.P_in = open_P;
+        if (open_sub >= 0) { g.fin_cos_rows = out.cos_rows + (size_t)open_sub * ASD_ROWS; g.fin_cos_acc = out.cos_acc + open_sub; }
     };
     auto layout = [&](GemmArgs& g, const GemmCfg& cfg, int total_tiles, int KB) {
         g.KB = KB; g.w_tile_stride = cfg.kmajor ? 1 : KB; g.w_kb_stride = cfg.kmajor ? total_tiles : 1; g.k_interleave = cfg.kint;
@@ -610,44 +533,41 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
             a.W = (const u32x4*)ly.wqkv; a.n_tiles = e->qkv_tiles;
             layout(a, e->g_qkv, e->qkv_tiles, e->KBd);
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
-            a.q = flow ? (void*)take(fs.q_bytes) : e->q;
+            a.q = e->q;
             consume(a);
-            push(OP_QKV, ASD_K_QKV, flow ? e->qkv_tiles : e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
+            push(OP_QKV, ASD_K_QKV, e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
 
             AttnArgs t{};
             t.q = a.q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
             t.page_table = e->page_table; t.st = e->st; t.pos_off = pos_off; t.M = M; t.RS = RS;
             t.n_h = c.n_heads; t.n_kv = c.n_kv_heads; t.h = c.head_dim; t.page_tokens = c.page_tokens;
-            t.nc_stride = e->nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
-            t.o_part = e->o_part; t.ml_part = e->ml_part; t.arrivals = e->arrivals;
-            t.out = flow ? (void*)take(fs.act_q) : e->attn_out;
+            t.nc_stride = out.nc_stride; t.scale = 1.f / sqrtf((float)c.head_dim);
+            t.o_part = out.o_part; t.ml_part = out.ml_part; t.arrivals = out.arrivals;
+            t.out = e->attn_out;
             attn_shape(e, t, nc);
-            const int units = attn_grid(c.n_heads, c.n_kv_heads, t.grid_groups, t.gh);
-            push(OP_ATTN, ASD_K_ATTN, flow ? (units + FLOW_WAVES / ATT_GW - 1) / (FLOW_WAVES / ATT_GW) : units, cls_bytes[ASD_K_ATTN] / L).t = t;
+            push(OP_ATTN, ASD_K_ATTN, attn_grid(c.n_heads, c.n_kv_heads, t.grid_groups, t.gh), cls_bytes[ASD_K_ATTN] / L).t = t;
 
             GemmArgs o = base;
             o.W = (const u32x4*)ly.wo; o.X = (const u32x4*)t.out; o.x_plane = (int64_t)e->KBq * 64; o.n_tiles = c.d_model / 16;
             layout(o, e->g_o, c.d_model / 16, e->KBq);
-            produce(o, 2 * l);
+            o.g_next = next_gain(e, mask, 2 * l);
             open_P = e->g_o.grid; open_sub = 2 * l;
-            PassOp& po = push(OP_OPROJ, ASD_K_OPROJ, e->g_o.grid, cls_bytes[ASD_K_OPROJ] / L);
-            po.g = o; po.tn = e->g_o.TN;
+            push(OP_OPROJ, ASD_K_OPROJ, e->g_o.grid, cls_bytes[ASD_K_OPROJ] / L).g = o;
         }
         if (!(mask && mask[2 * l + 1])) {
             GemmArgs a = base;
             a.W = (const u32x4*)ly.wg; a.W2 = (const u32x4*)ly.wu;
             a.n_tiles = c.d_ffn / 16; layout(a, e->g_gu, c.d_ffn / 16, e->KBd);
-            a.hmid = flow ? (void*)take(fs.act_f) : e->hmid;
+            a.hmid = e->hmid;
             consume(a);
-            push(OP_GU, ASD_K_GATEUP, flow ? c.d_ffn / 16 : e->g_gu.grid, cls_bytes[ASD_K_GATEUP] / L).g = a;
+            push(OP_GU, ASD_K_GATEUP, e->g_gu.grid, cls_bytes[ASD_K_GATEUP] / L).g = a;
 
             GemmArgs dn = base;
             dn.W = (const u32x4*)ly.wd; dn.X = (const u32x4*)a.hmid; dn.x_plane = (int64_t)e->KBf * 64; dn.n_tiles = c.d_model / 16;
             layout(dn, e->g_down, c.d_model / 16, e->KBf);
-            produce(dn, 2 * l + 1);
+            dn.g_next = next_gain(e, mask, 2 * l + 1);
             open_P = e->g_down.grid; open_sub = 2 * l + 1;
-            PassOp& pd = push(OP_DOWN, ASD_K_DOWN, e->g_down.grid, cls_bytes[ASD_K_DOWN] / L);
-            pd.g = dn; pd.tn = e->g_down.TN;
+            push(OP_DOWN, ASD_K_DOWN, e->g_down.grid, cls_bytes[ASD_K_DOWN] / L).g = dn;
         }
     }
     GemmArgs lm = base;
@@ -659,7 +579,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
 }
 
 // Run a pass as one launch per step.
-int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const EmbedBufs& emb, const int32_t* d_tokens, int M, const uint8_t* mask,
+int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d_tokens, int M, const uint8_t* mask,
                  Profiler* profiler, int fin_mode, int fin_arg, const PassOut& out) {
     const asd_config& c = e->c;
     Prof pr{profiler, e->stream};
@@ -671,10 +591,10 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const EmbedBufs&
             case OP_EMBED:
                 if (c.dtype == ASD_DT_BF16)
                     embed_kernel<BF16><<<dim3(EMBED_SPLIT, M), EMBED_THREADS, 0, e->stream>>>((const uint16_t*)e->embed, d_tokens, c.d_model, c.vocab, e->st,
-                        next_gain(e, mask, -1), emb.xres, emb.xb, (size_t)e->KBd * 64 * e->KE, RS, emb.part);
+                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, out.part);
                 else
                     embed_kernel<F32><<<dim3(EMBED_SPLIT, M), EMBED_THREADS, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model, c.vocab, e->st,
-                        next_gain(e, mask, -1), emb.xres, emb.xb, (size_t)e->KBd * 64 * e->KE, RS, emb.part);
+                        next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, out.part);
                 break;
             case OP_QKV: ok = launch_gemm<EPI_QKV>(e, e->g_qkv, op.g); break;
             case OP_OPROJ: ok = launch_gemm<EPI_RES>(e, e->g_o, op.g); break;
@@ -683,7 +603,7 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const EmbedBufs&
             case OP_LM: ok = launch_gemm<EPI_LM>(e, e->g_lm, op.g); break;
             case OP_ATTN: launch_attn(e, op.t); break;
             case OP_FINISH:
-                finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)e->amax_part, e->g_lm.grid, M, c.vocab, out.argmax, fin_mode, fin_arg,
+                finish_kernel<<<1, 64 * M, 0, e->stream>>>((const AmaxCand*)out.amax_part, e->g_lm.grid, M, c.vocab, out.argmax, fin_mode, fin_arg,
                                                            e->st, e->tokbuf, e->out_tokens);
                 break;
         }
@@ -695,92 +615,12 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const EmbedBufs&
     return ASD_OK;
 }
 
-template <class T, int H, bool PACK> const void* flow_kernel_ptr() { return (const void*)flow_kernel<T, H, PACK>; }
-
-// Does the dataflow kernel take a pass of M rows?  Its GEMM blocks exist for one tile per workgroup (QKV, gate/up),
-// the configured one or two (the residual-add projections) and two (LM head), all with 8 waves.
-bool flow_takes(const asd_engine* e, int M) {
-    (void)M;
-    return e->flow && e->g_qkv.TN == 1 && e->g_gu.TN == 1 && e->g_lm.TN == 2 && e->g_o.TN <= 2 && e->g_down.TN <= 2 && e->g_qkv.NW == FLOW_WAVES &&
-           e->g_o.NW == FLOW_WAVES && e->g_gu.NW == FLOW_WAVES && e->g_down.NW == FLOW_WAVES && e->g_lm.NW == FLOW_WAVES;
-}
-
-template <class T, bool PACK> void launch_flow_t(asd_engine* e, const FlowArgs& P, int grid) {
-    const int H = e->c.head_dim;
-    if (H == 32) flow_kernel<T, 32, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
-    if (H == 64) flow_kernel<T, 64, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
-    if (H == 128) flow_kernel<T, 128, PACK><<<grid, FLOW_THREADS, 0, e->stream>>>(P);
-}
-
-// Run a pass as one dataflow launch.  The step table lives in a device-side cache keyed by what it depends on.
-int launch_flow(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc, int ctx_for_bytes, int fin_mode,
-                int fin_arg, const PassOut& out) {
-    const asd_config& c = e->c;
-    AttnArgs shape{};
-    shape.M = M; shape.RS = row_stride(e, M);
-    attn_shape(e, shape, nc);
-    std::vector<int> key{M, pos_off, (int)(d_tokens - e->tokbuf), shape.grid_groups, out.logits == e->logits ? 0 : 1, out.argmax == e->argmax ? 0 : 1};
-    for (int j = 0; j < 2 * c.n_layers; ++j) key.push_back(mask ? (mask[j] ? 1 : 0) : 0);
-    if (out.logits != e->logits || out.argmax != e->argmax || (d_tokens < e->tokbuf || d_tokens >= e->tokbuf + 64)) {
-        // caller-owned buffers: their addresses are part of the table
-        key.push_back((int)((uintptr_t)out.logits & 0x7fffffff)); key.push_back((int)((uintptr_t)out.logits >> 31));
-        key.push_back((int)((uintptr_t)out.argmax & 0x7fffffff)); key.push_back((int)((uintptr_t)out.argmax >> 31));
-        key.push_back((int)((uintptr_t)d_tokens & 0x7fffffff)); key.push_back((int)((uintptr_t)d_tokens >> 31));
-    }
-    auto it = e->op_cache.find(key);
-    EmbedBufs emb{};
-    if (it == e->op_cache.end()) {
-        std::vector<PassOp> ops;
-        build_pass(e, M, pos_off, mask, ctx_for_bytes, nc, true, out, ops, &emb);
-        const int n_blocks = ops.back().first_block + ops.back().n_blocks;
-        std::vector<uint16_t> blk((size_t)n_blocks);
-        for (size_t i = 0; i < ops.size(); ++i)
-            for (int b = 0; b < ops[i].n_blocks; ++b) blk[(size_t)ops[i].first_block + b] = (uint16_t)i;
-        const size_t ob = align_up(ops.size() * sizeof(PassOp)), bb = align_up(blk.size() * 2);
-        if (ob + bb > e->ops_bytes) return fail(e, ASD_E_NOMEM, "step table of %zu bytes exceeds the reserved %zu", ob + bb, e->ops_bytes);
-        if (e->ops_used + ob + bb > e->ops_bytes) {      // cache full: start over (the stream may still be reading old tables)
-            CK(e, hipStreamSynchronize(e->stream));
-            e->op_cache.clear(); e->ops_used = 0;
-        }
-        char* dst = e->ops_region + e->ops_used;
-        CK(e, hipMemcpyAsync(dst, ops.data(), ops.size() * sizeof(PassOp), hipMemcpyHostToDevice, e->stream));
-        CK(e, hipMemcpyAsync(dst + ob, blk.data(), blk.size() * 2, hipMemcpyHostToDevice, e->stream));
-        CK(e, hipStreamSynchronize(e->stream));          // the source vectors are locals
-        it = e->op_cache.emplace(key, FlowTable{(const PassOp*)dst, (const uint16_t*)(dst + ob), (int)ops.size(), n_blocks}).first;
-        e->ops_used += ob + bb;
-    }
-    // (the embedding's buffers are the first three of the workspace in every table)
-    {
-        const FlowSizes& fs = e->fs;
-        emb.xres = (float*)e->flow_ws; emb.xb = e->flow_ws + fs.xres; emb.part = (float*)(e->flow_ws + fs.xres + fs.act_d);
-    }
-    FlowArgs P{};
-    P.ops = it->second.ops; P.op_of_block = it->second.op_of_block; P.n_ops = it->second.n_ops;
-    P.M = M; P.RS = row_stride(e, M); P.d = c.d_model; P.vocab = c.vocab;
-    P.E = e->embed; P.tokens = d_tokens; P.g_first = next_gain(e, mask, -1);
-    P.xres0 = emb.xres; P.xb0 = emb.xb; P.xb_plane = (int64_t)e->KBd * 64 * e->KE; P.part0 = emb.part;
-    P.cand = (const AmaxCand*)e->amax_part; P.P_lm = e->g_lm.grid; P.fin_mode = fin_mode; P.fin_arg = fin_arg; P.argmax = out.argmax;
-    P.st = e->st; P.tokbuf = e->tokbuf; P.out = e->out_tokens;
-    P.done = e->flow_done; P.err = e->flow_err;
-    const int grid = it->second.n_blocks;
-    if (c.dtype == ASD_DT_BF16) {
-        if (M <= 8) launch_flow_t<BF16, true>(e, P, grid); else launch_flow_t<BF16, false>(e, P, grid);
-    } else {
-        launch_flow_t<F32, false>(e, P, grid);
-    }
-    hipError_t r = hipGetLastError();
-    if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
-    return ASD_OK;
-}
-
 int enqueue_forward(asd_engine* e, const int32_t* d_tokens, int M, int pos_off, const uint8_t* mask, int nc,
                     Profiler* profiler, int ctx_for_bytes, int fin_mode = FIN_NONE, int fin_arg = 0, const PassOut* out_or_null = nullptr) {
-    const PassOut out = out_or_null ? *out_or_null : PassOut{e->logits, e->argmax};
-    if (!profiler && flow_takes(e, M)) return launch_flow(e, d_tokens, M, pos_off, mask, nc, ctx_for_bytes, fin_mode, fin_arg, out);
+    const PassOut out = out_or_null ? *out_or_null : engine_out(e);
     std::vector<PassOp> ops;
-    EmbedBufs emb{};
-    build_pass(e, M, pos_off, mask, ctx_for_bytes, nc, false, out, ops, &emb);
-    return launch_steps(e, ops, emb, d_tokens, M, mask, profiler, fin_mode, fin_arg, out);
+    build_pass(e, M, pos_off, mask, ctx_for_bytes, nc, out, ops);
+    return launch_steps(e, ops, d_tokens, M, mask, profiler, fin_mode, fin_arg, out);
 }
 
 bool weights_ready(asd_engine* e) {
@@ -790,22 +630,13 @@ bool weights_ready(asd_engine* e) {
 
 int chunks_for(int last_pos) { return last_pos / ASD_CHUNK + 1; }
 
-// After a synchronisation: did a wait of the dataflow kernel give up, or did a kernel meet a token id outside the
-// vocabulary / a row of logits without a finite maximum?  (st: a host copy of the decoding state, or NULL to fetch it.)
+// After a synchronisation: did a kernel meet a token id outside the vocabulary, or a row of logits without a finite
+// maximum?  (st: a host copy of the decoding state, or NULL to fetch it.)
 int check_pass_error(asd_engine* e, const DevState* st = nullptr) {
     DevState tmp;
     if (!st) { CK(e, hipMemcpy(&tmp, e->st, sizeof tmp, hipMemcpyDeviceToHost)); st = &tmp; }
     if (st->err & DEV_ERR_TOKEN) return fail(e, ASD_E_INVAL, "a token id outside the vocabulary reached the embedding");
     if (st->err & DEV_ERR_LOGITS) return fail(e, ASD_E_STATE, "a row of logits had no finite maximum (non-finite weights?)");
-    if (!e->flow) return ASD_OK;
-    int32_t flag = 0;
-    CK(e, hipMemcpy(&flag, e->flow_err, 4, hipMemcpyDeviceToHost));
-    if (flag) {
-        // the counters are in an unknown state: clear them so that the engine stays usable
-        hipMemset(e->flow_done, 0, (size_t)e->fs.max_ops * FLOW_SHARDS * FLOW_SHARD_WORDS * 4);
-        hipMemset(e->flow_err, 0, 4);
-        return fail(e, ASD_E_HIP, "a step of the dataflow pass kernel gave up waiting for its producer");
-    }
     return ASD_OK;
 }
 
@@ -972,8 +803,7 @@ int prefill_blocks(asd_engine* e, const int32_t* tokens, int n, Profiler* profil
     pr.begin(ASD_PK_LMHEAD, 2.0 * c.d_model * c.vocab);
     launch_pf_rows(e, 2, rows, 0, 1, nullptr, nullptr, rows - 1);
     std::vector<PassOp> ops;
-    EmbedBufs emb{};
-    build_pass(e, 1, 0, nullptr, n, chunks_for(n - 1), false, PassOut{e->logits, e->argmax}, ops, &emb);
+    build_pass(e, 1, 0, nullptr, n, chunks_for(n - 1), engine_out(e), ops);
     for (PassOp& op : ops) {
         if (op.type != OP_LM) continue;
         op.g.part_in = e->part; op.g.P_in = 1; op.g.fin_cos_rows = nullptr; op.g.fin_cos_acc = nullptr;
@@ -1052,13 +882,6 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->acs_rows = 0;
     e->acs_valid = false;
     e->h_st = nullptr;
-    // dataflow pass kernel
-    e->fs = flow_sizes(*cfg, p);
-    e->flow_ws = A + p.flow_ws; e->flow_ws_bytes = p.flow_ws_bytes;
-    e->flow_done = (unsigned*)(A + p.flow_done); e->flow_err = (int32_t*)(A + p.flow_err);
-    e->ops_region = A + p.ops; e->ops_bytes = p.ops_bytes; e->ops_used = 0;
-    e->flow = (cfg->debug_flags & ASD_DBG_STEP_KERNELS) == 0;
-    e->flow = e->flow && flow_takes(e, 1);
 
     hipError_t r = hipHostMalloc((void**)&e->h_st, sizeof(DevState), hipHostMallocDefault);
     if (r != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(r)); }
@@ -1447,7 +1270,7 @@ int asd_spec_sample(asd_engine* e, const float* q_logits, const float* p_logits,
 
 // Run `enqueue` on the engine's stream: eagerly, or (use_graphs) as a HIP graph captured once per key.
 static int run_captured(asd_engine* e, bool use_graphs, const std::vector<int>& key, const std::function<int()>& enqueue) {
-    if (!use_graphs || e->flow) return enqueue();      // (a dataflow pass is one launch: nothing to gain from a graph)
+    if (!use_graphs) return enqueue();
     auto it = e->graphs.find(key);
     if (it == e->graphs.end()) {
         hipGraph_t g = nullptr;
@@ -1690,7 +1513,7 @@ int asd_time_pass(asd_engine* e, int32_t n_rows, const uint8_t* mask, int32_t re
     if (rc) return rc;
     const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
     hipGraphExec_t ge = nullptr;
-    if (use_graph && !e->flow) {
+    if (use_graph) {
         hipGraph_t g = nullptr;
         CK(e, hipStreamBeginCapture(e->stream, hipStreamCaptureModeThreadLocal));
         rc = enqueue_forward(e, e->tokbuf, n_rows, 0, mask, nc, nullptr, ctx);
@@ -1805,18 +1628,17 @@ int asd_time_step_class(asd_engine* e, int32_t cls, int32_t n_rows, int32_t reps
     if (rc) return rc;
     const int nc = chunks_for(e->kv_len + n_rows - 1), ctx = e->kv_len + n_rows;
     std::vector<PassOp> all, sel;
-    EmbedBufs emb{};
-    const PassOut out{e->logits, e->argmax};
-    build_pass(e, n_rows, 0, nullptr, ctx, nc, false, out, all, &emb);
-    rc = launch_steps(e, all, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // valid inputs for every step
+    const PassOut out = engine_out(e);
+    build_pass(e, n_rows, 0, nullptr, ctx, nc, out, all);
+    rc = launch_steps(e, all, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // valid inputs for every step
     if (rc) return rc;
     double bytes = 0.0;
     for (const PassOp& op : all) if (op.cls == cls) { sel.push_back(op); bytes += op.bytes; }
     if (sel.empty()) return fail(e, ASD_E_INVAL, "the pass has no step of class %d", cls);
-    rc = launch_steps(e, sel, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // warm-up
+    rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);     // warm-up
     hipEvent_t a = nullptr, b = nullptr;
     if (!rc) { hipEventCreate(&a); hipEventCreate(&b); hipEventRecord(a, e->stream); }
-    for (int i = 0; i < reps && !rc; ++i) rc = launch_steps(e, sel, emb, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);
+    for (int i = 0; i < reps && !rc; ++i) rc = launch_steps(e, sel, e->tokbuf, n_rows, nullptr, nullptr, FIN_NONE, 0, out);
     float ms = 0.f;
     if (!rc) {
         hipEventRecord(b, e->stream);

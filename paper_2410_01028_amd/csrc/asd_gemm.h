@@ -20,14 +20,8 @@
 // the same fixed order to get ||y||^2, and workgroup 0 also finishes the producing
 // sublayer's cosine, cos = <x,y> / sqrt(||x||^2 ||y||^2).  No workgroup ever waits for
 // another inside a kernel, so no device-scope fence (and no L2 write-back) is needed.
-//
-// The same block function also runs inside the dataflow pass kernel (asd_flow.h), where the producer of a step's
-// activations is another workgroup of the same launch: there COH = true makes every store of exchanged data a
-// device-scope write-through store, and `dep` (called once by every wave, after the first weight fragments have
-// been requested and before anything the producer wrote is read) blocks until the producer has finished.
 #pragma once
 #include "asd_common.h"
-#include <type_traits>
 
 enum { EPI_QKV = 0, EPI_RES = 1, EPI_GU = 2, EPI_LM = 3 };
 
@@ -44,8 +38,7 @@ struct GemmArgs {
     int32_t k_interleave;    // how the waves of a workgroup split K
     int32_t M;               // rows in use
     int32_t RS;              // row stride of every activation buffer in this pass (power of two >= M)
-    const float* ssq_in;     // [16] ||residual row||^2 as of the last finished cosine tap
-    float* ssq_out;          // [16] where workgroup 0 leaves this step's ||residual row||^2 (may alias ssq_in)
+    float* ssq;              // [16] ||residual row||^2 as of the last finished cosine tap
     float inv_d, eps;
     // input side of QKV / GU / LM: partials of the kernel that produced the residual
     const float* part_in;    // [P_in][16][2]
@@ -53,8 +46,7 @@ struct GemmArgs {
     float* fin_cos_rows;     // [16] cosine per row of the producing sublayer (written by workgroup 0); NULL after the embedding
     double* fin_cos_acc;     // its running sum over rows
     // EPI_RES
-    const float* xres_in;    // [16][d] fp32 residual stream entering the sublayer
-    float* xres;             // [16][d] residual stream leaving it (may alias xres_in: each element is read and written by one thread)
+    float* xres;             // [16][d] fp32 residual stream, updated in place
     void* xb;                // tiled copy of y * g_next in storage type
     int64_t xb_plane, q_plane, hmid_plane;   // plane strides (elements) of the activation buffers written here
     const float* g_next;     // gain of the norm that reads y next
@@ -81,46 +73,30 @@ struct GemmArgs {
 // `between` runs after the first U steps have been requested: work whose own loads should overlap the stream.
 // X points at this lane's fragment of k-block 0 (always a valid address); consecutive k-blocks are xstep fragments
 // apart.
-struct NoDep { __device__ __forceinline__ void operator()() const {} };      // the producer is an earlier launch
-
-template <class T, int NA, int NPL, int U, class F, class D>
+template <class T, int NA, int NPL, int U, class F>
 __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u32x4* X, int xstep, int64_t xpl, int first, int step, int n,
-                                           int64_t wks, f32x4 (&acc)[NPL][NA], F between, D dep) {
+                                           int64_t wks, f32x4 (&acc)[NPL][NA], F between) {
     // A ring of U slots.  The steady-state loop has no conditional request in it, and X is a valid address in every
     // lane (a lane whose row is not in use reads another row's fragment: its column of the products is never read,
     // and zeroing it would be a use that waits for the load).  The wait counts the compiler derives are exact only
     // when every path issues the same loads; a single request under a condition made it wait for ALL outstanding
     // loads at the top of every trip, which turns the ring into load-everything-then-drain.
-    // dep() separates what may be requested at once (weights) from what another workgroup produces (activations):
-    // the first ring of weight fragments is in flight while the wave waits for its producer.
     u32x4 a[U][NA], b[U][NPL];
-    auto fill_a = [&](const int u, const int kb) {
+    auto fill = [&](const int u, const int kb) {
+#pragma unroll
+        for (int pl = 0; pl < NPL; ++pl) b[u][pl] = *(X + (size_t)(first + kb * step) * xstep + pl * xpl);
 #pragma unroll
         for (int s = 0; s < NA; ++s) a[u][s] = __builtin_nontemporal_load(A[s] + (size_t)(first + kb * step) * ASD_WAVE * wks);
     };
-    auto fill_b = [&](const int u, const int kb) {
-#pragma unroll
-        for (int pl = 0; pl < NPL; ++pl) b[u][pl] = *(X + (size_t)(first + kb * step) * xstep + pl * xpl);
-    };
-    auto fill = [&](const int u, const int kb) { fill_b(u, kb); fill_a(u, kb); };
     auto use = [&](const int u) {
 #pragma unroll
         for (int s = 0; s < NA; ++s)
 #pragma unroll
             for (int pl = 0; pl < NPL; ++pl) mma16<T>(acc[pl][s], a[u][s], b[u][pl]);
     };
-    constexpr bool kNoDep = std::is_same<D, NoDep>::value;
     if (n >= U) {
-        if constexpr (kNoDep) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) fill(u, u);
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) fill_a(u, u);
-            dep();
-#pragma unroll
-            for (int u = 0; u < U; ++u) fill_b(u, u);
-        }
+        for (int u = 0; u < U; ++u) fill(u, u);
         between();
         int i = 0;
         for (; i + 2 * U <= n; i += U) {               // every refill of such a trip is a k-block of the range
@@ -137,19 +113,9 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
         for (int u = 0; u + 1 < U; ++u)
             if (u < extra) use(u);
     } else {                                           // a K range shorter than the ring
-        if constexpr (kNoDep) {
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (u < n) fill(u, u);
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (u < n) fill_a(u, u);
-            dep();
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (u < n) fill_b(u, u);
-        }
+        for (int u = 0; u < U; ++u)
+            if (u < n) fill(u, u);
         between();
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -157,7 +123,7 @@ __device__ __forceinline__ void stream_mma(const u32x4* const (&A)[NA], const u3
     }
 }
 
-// LDS of one workgroup's block function (a kernel that runs several kinds of block gives them one region in turn)
+// LDS of one workgroup's block function
 template <class T, int EPI, int TN, int NW, bool PACK> struct GemmLds {
     static constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     static constexpr int NPL = PACK ? 1 : T::NP;
@@ -170,17 +136,14 @@ template <class T, int EPI, int TN, int NW, bool PACK> struct GemmLds {
     float rscale[16];
 };
 
-// One workgroup's share of the contraction: "virtual block" bid owns tiles bid*TN .. bid*TN+TN-1.  Called once per
-// workgroup, by gemm_kernel (bid = blockIdx.x, COH = false, no dependency) and by the dataflow pass kernel (COH =
-// true: stores of data that other workgroups of the same launch read are device-scope write-through stores; what
-// this block reads of such data it reads after dep() has returned, from addresses nobody read earlier in the launch).
+// One workgroup's share of the contraction: block bid owns tiles bid*TN .. bid*TN+TN-1.
 //
 // Two-plane (bf16) activations: the hi and the lo plane are contracted into separate sums, added once at the end.
 // PACK (passes of at most 8 rows): both planes share one operand, rows in columns 0..7 hi and 8..15 lo, so a
 // k-block costs one fragment load and one MFMA; otherwise each plane has its own operand and accumulators.  Either
 // way an output element is (sum over waves of its hi sums) + (sum over waves of its lo sums): the same bits.
-template <class T, int EPI, int TN, int NW, int U, bool COH, bool PACK, class D = NoDep>
-__device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, GemmLds<T, EPI, TN, NW, PACK>& lds, D dep = D()) {
+template <class T, int EPI, int TN, int NW, int U, bool PACK>
+__device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, GemmLds<T, EPI, TN, NW, PACK>& lds) {
     constexpr int NA = (EPI == EPI_GU) ? 2 * TN : TN;
     constexpr int NT = NW * 64;
     constexpr int NPL = PACK ? 1 : T::NP;               // operands (and accumulator sets) per k-block
@@ -248,7 +211,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
                 const int e = tid + q * NT, s = e >> 8, m = (e >> 4) & 15, nl = e & 15;
                 xpre[q] = 0.f; gpre[q] = 0.f;
                 if (e < NA * 256 && m < a.M && tval[s]) {
-                    xpre[q] = a.xres_in[(size_t)m * a.d + tile[s] * 16 + nl];
+                    xpre[q] = a.xres[(size_t)m * a.d + tile[s] * 16 + nl];
                     gpre[q] = a.g_next[tile[s] * 16 + nl];
                 }
             }
@@ -281,7 +244,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
     const u32x4* Xl;
     if constexpr (PACK) Xl = a.X + ((lane & 8) ? a.x_plane : 0) + (lane >> 4) * a.RS + ((lane & 7) < a.M ? (lane & 7) : 0);
     else Xl = a.X + (lane >> 4) * a.RS + ((lane & 15) < a.M ? (lane & 15) : 0);
-    stream_mma<T, NA, NPL, U>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early, dep);
+    stream_mma<T, NA, NPL, U>(A, Xl, 4 * a.RS, a.x_plane, k_first, k_step, k_n, a.w_kb_stride, acc, early);
     sum_partials();
 
 #pragma unroll
@@ -300,12 +263,12 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
             float c = 0.f;
             if (bid == 0 && tid < a.M) {
                 if (a.fin_cos_rows) {            // the partials come from a residual-add kernel: finish its cosine
-                    const float xx = a.ssq_in[tid];
+                    const float xx = a.ssq[tid];
                     c = xy * rsqrtf(fmaxf(xx, 1e-16f) * fmaxf(yy, 1e-16f));
                     c = fminf(1.f, fmaxf(-1.f, c));
                     a.fin_cos_rows[tid] = c;
                 }
-                st_f32<COH>(&a.ssq_out[tid], yy);
+                a.ssq[tid] = yy;
             }
             fin_b[tid] = c;
         }
@@ -354,19 +317,19 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
             }
             if (head < a.n_h) {
                 E* q = (E*)a.q + (size_t)head * a.h * a.RS;
-                store_act<T, COH>(q, a.q_plane, a.RS, i, m, v0);
-                store_act<T, COH>(q, a.q_plane, a.RS, i + hh, m, v1);
+                store_act<T>(q, a.q_plane, a.RS, i, m, v0);
+                store_act<T>(q, a.q_plane, a.RS, i + hh, m, v1);
             } else {
                 const bool isk = head < a.n_h + a.n_kv;
                 const int kvh = isk ? head - a.n_h : head - a.n_h - a.n_kv;
                 const int PT = a.page_tokens, page = a.page_table[pos / PT], slot = pos % PT;
                 E* base = (E*)a.kv + ((size_t)page * a.n_kv + kvh) * 2 * PT * a.h;
                 if (isk) {                       // into the chunk's K fragments
-                    st_elem<T, COH>(base + kv_k_off<T>(slot, i, a.h), T::from_f32(v0));
-                    st_elem<T, COH>(base + kv_k_off<T>(slot, i + hh, a.h), T::from_f32(v1));
+                    *(base + kv_k_off<T>(slot, i, a.h)) = T::from_f32(v0);
+                    *(base + kv_k_off<T>(slot, i + hh, a.h)) = T::from_f32(v1);
                 } else {                         // into the chunk's V^T fragments
-                    st_elem<T, COH>(base + kv_v_off<T>(slot, i, a.h), T::from_f32(v0));
-                    st_elem<T, COH>(base + kv_v_off<T>(slot, i + hh, a.h), T::from_f32(v1));
+                    *(base + kv_v_off<T>(slot, i, a.h)) = T::from_f32(v0);
+                    *(base + kv_v_off<T>(slot, i + hh, a.h)) = T::from_f32(v1);
                 }
             }
         }
@@ -380,7 +343,7 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
             const float rs = rscale[m];
             const float g = gather(s, m, nl) * rs, u = gather(TN + s, m, nl) * rs;
             const float act = g / (1.f + __expf(-g)) * u;
-            store_act<T, COH>(a.hmid, a.hmid_plane, a.RS, tile[s] * 16 + nl, m, act);
+            store_act<T>(a.hmid, a.hmid_plane, a.RS, tile[s] * 16 + nl, m, act);
         }
         return;
     }
@@ -395,8 +358,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
                 const int n = tile[s] * 16 + nl;
                 const float x = xpre[q];
                 const float y = x + gather(s, m, nl);
-                st_f32<COH>(&a.xres[(size_t)m * a.d + n], y);
-                store_act<T, COH>(a.xb, a.xb_plane, a.RS, n, m, y * gpre[q]);
+                a.xres[(size_t)m * a.d + n] = y;
+                store_act<T>(a.xb, a.xb_plane, a.RS, n, m, y * gpre[q]);
                 pxy = x * y; pyy = y * y;
             }
             epi_a[e] = pxy; epi_b[e] = pyy;
@@ -406,8 +369,8 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
             float sxy = 0.f, syy = 0.f;
             for (int s = 0; s < NA; ++s)
                 for (int nl = 0; nl < 16; ++nl) { sxy += epi_a[s * 256 + tid * 16 + nl]; syy += epi_b[s * 256 + tid * 16 + nl]; }
-            st_f32<COH>(&a.part[((size_t)bid * 16 + tid) * 2], sxy);
-            st_f32<COH>(&a.part[((size_t)bid * 16 + tid) * 2 + 1], syy);
+            a.part[((size_t)bid * 16 + tid) * 2] = sxy;
+            a.part[((size_t)bid * 16 + tid) * 2 + 1] = syy;
         }
     }
 
@@ -433,9 +396,9 @@ __device__ __forceinline__ void gemm_block(const GemmArgs& a, const int bid, Gem
             if (best.v != -INFINITY)
                 for (int s = 0; s < NA; ++s)
                     for (int nl = 0; nl < 16; ++nl) se += __expf(epi_a[s * 256 + tid * 16 + nl] - best.v);
-            st_f32<COH>(&a.amax_part[(size_t)bid * 16 + tid].v, best.v);
-            st_f32<COH>((float*)&a.amax_part[(size_t)bid * 16 + tid].i, __int_as_float(best.i));
-            st_f32<COH>(&a.amax_part[(size_t)bid * 16 + tid].s, se);
+            a.amax_part[(size_t)bid * 16 + tid].v = best.v;
+            a.amax_part[(size_t)bid * 16 + tid].i = best.i;
+            a.amax_part[(size_t)bid * 16 + tid].s = se;
         }
     }
 }
@@ -451,5 +414,5 @@ __global__ __launch_bounds__(NW * 64) void gemm_kernel(const u32x4* W, const u32
     b.W = W; b.W2 = W2; b.X = X; b.w_tile_stride = w_tile_stride; b.w_kb_stride = w_kb_stride; b.x_plane = x_plane;
     b.n_tiles = n_tiles; b.KB = KB; b.k_interleave = packed & 255; b.M = (packed >> 8) & 255; b.RS = packed >> 16;
     __shared__ GemmLds<T, EPI, TN, NW, PACK> lds;
-    gemm_block<T, EPI, TN, NW, U, false, PACK>(b, blockIdx.x, lds);
+    gemm_block<T, EPI, TN, NW, U, PACK>(b, blockIdx.x, lds);
 }

@@ -8,12 +8,10 @@
 // workgroup's share of ||x||^2 as partial [split][16][2] (slot 1; slot 0 unused) for the next kernel.
 #define EMBED_SPLIT 8
 #define EMBED_THREADS 256
-template <class T, bool COH>
+template <class T>
 __device__ __forceinline__ void embed_block(const typename T::elem* E, const int32_t* tokens, int d, int vocab, DevState* st, const float* g_first,
                                             float* xres, void* xb, size_t xb_plane, int rs, float* part, const int sp, const int m, float* red) {
     using El = typename T::elem;
-    // EMBED_THREADS threads work (the order of the sum of squares depends on that number); a larger workgroup's other
-    // threads only join the barriers
     const int tid = threadIdx.x, nt = EMBED_THREADS;
     // a token id that is not a row of the table (possible when the ids come from device memory the host never saw)
     // must not become an address: it reads row 0 and raises the state's error bit
@@ -25,28 +23,26 @@ __device__ __forceinline__ void embed_block(const typename T::elem* E, const int
     const El* row = E + (size_t)tok * d;
     const int per = (d + EMBED_SPLIT - 1) / EMBED_SPLIT, lo = sp * per, hi = min(d, lo + per);
     float ss = 0.f;
-    if (tid < nt) {
-        for (int i = lo + tid; i < hi; i += nt) {
-            const float x = T::to_f32(row[i]);
-            st_f32<COH>(&xres[(size_t)m * d + i], x);
-            store_act<T, COH>(xb, xb_plane, rs, i, m, x * g_first[i]);
-            ss += x * x;
-        }
-        red[tid] = ss;
+    for (int i = lo + tid; i < hi; i += nt) {
+        const float x = T::to_f32(row[i]);
+        xres[(size_t)m * d + i] = x;
+        store_act<T>(xb, xb_plane, rs, i, m, x * g_first[i]);
+        ss += x * x;
     }
+    red[tid] = ss;
     __syncthreads();
     for (int s = nt / 2; s > 0; s >>= 1) {
         if (tid < s) red[tid] += red[tid + s];
         __syncthreads();
     }
-    if (tid == 0) { st_f32<COH>(&part[((size_t)sp * 16 + m) * 2], 0.f); st_f32<COH>(&part[((size_t)sp * 16 + m) * 2 + 1], red[0]); }
+    if (tid == 0) { part[((size_t)sp * 16 + m) * 2] = 0.f; part[((size_t)sp * 16 + m) * 2 + 1] = red[0]; }
     __syncthreads();
 }
 template <class T>
 __global__ __launch_bounds__(EMBED_THREADS) void embed_kernel(const typename T::elem* E, const int32_t* tokens, int d, int vocab, DevState* st,
                                                     const float* g_first, float* xres, void* xb, size_t xb_plane, int rs, float* part) {
     __shared__ float red[EMBED_THREADS];
-    embed_block<T, false>(E, tokens, d, vocab, st, g_first, xres, xb, xb_plane, rs, part, blockIdx.x, blockIdx.y, red);
+    embed_block<T>(E, tokens, d, vocab, st, g_first, xres, xb, xb_plane, rs, part, blockIdx.x, blockIdx.y, red);
 }
 
 // ---------------------------------------------------------------- decoding state
@@ -69,7 +65,6 @@ enum { FIN_NONE = 0, FIN_DRAFT = 1, FIN_ACCEPT = 2 };
 struct AmaxCand { float v; int32_t i; float s; float pad; };
 __device__ __forceinline__ bool amax_better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 // one workgroup; wave w handles rows w, w + (waves), ...; candidates are [workgroup][16 rows]
-template <bool COH>
 __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M, int V, int32_t* argmax, int mode, int j_or_kk,
                                              DevState* st, int32_t* tokbuf, int32_t* out, int* win) {
     const int tid = threadIdx.x, lane = tid & 63, nw = blockDim.x >> 6;
@@ -89,8 +84,8 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int p = p0 + 64 * u < P ? p0 + 64 * u : P - 1;
-                cv[u] = ld_f32<COH>(&cand[(size_t)p * 16 + m].v);
-                ci[u] = __float_as_int(ld_f32<COH>((const float*)&cand[(size_t)p * 16 + m].i));
+                cv[u] = cand[(size_t)p * 16 + m].v;
+                ci[u] = cand[(size_t)p * 16 + m].i;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u)
@@ -115,8 +110,8 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int p = p0 + 64 * u < P ? p0 + 64 * u : P - 1;
-                    cs[u] = ld_f32<COH>(&cand[(size_t)p * 16].s);
-                    cv[u] = ld_f32<COH>(&cand[(size_t)p * 16].v);
+                    cs[u] = cand[(size_t)p * 16].s;
+                    cv[u] = cand[(size_t)p * 16].v;
                 }
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
@@ -146,7 +141,7 @@ __device__ __forceinline__ void finish_block(const AmaxCand* cand, int P, int M,
 __global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int P, int M, int V, int32_t* argmax, int mode, int j_or_kk,
                                                       DevState* st, int32_t* tokbuf, int32_t* out) {
     __shared__ int win[16];
-    finish_block<false>(cand, P, M, V, argmax, mode, j_or_kk, st, tokbuf, out, win);
+    finish_block(cand, P, M, V, argmax, mode, j_or_kk, st, tokbuf, out, win);
 }
 
 // ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double

@@ -347,7 +347,7 @@ __global__ __launch_bounds__(256) void pf_tail_kernel(const float* xres_pf, cons
     for (int i = threadIdx.x; i < d; i += 256) {
         const float y = xres_pf[(size_t)r * d + i];
         xres[i] = y;
-        store_act<T, false>(xb, (size_t)xb_plane, 1, i, 0, y * g_final[i]);
+        store_act<T>(xb, (size_t)xb_plane, 1, i, 0, y * g_final[i]);
     }
     if (threadIdx.x == 0) { part[0] = 0.f; part[1] = ssq_pf[r]; }
 }

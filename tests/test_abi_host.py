@@ -69,7 +69,7 @@ def test_debug_switches_are_configuration_fields_not_environment(monkeypatch):
     for name in ("ASD_TUNE", "ASD_PF_TUNE", "ASD_PERSIST", "ASD_ATT_W4", "ASD_ATT_GH1", "ASD_RS_POW2", "ASD_SAMPLE_MEM"):
         monkeypatch.setenv(name, "qkv=2,8,0,0" if "TUNE" in name else "1")
     assert asd.arena_bytes(asd.make_config(s, 1024)) == base
-    tuned = asd.arena_bytes(asd.make_config(s, 1024, debug_flags=asd.DBG_STEP_KERNELS, debug_tune="o=2,8,0,0"))
+    tuned = asd.arena_bytes(asd.make_config(s, 1024, debug_flags=asd.DBG_ATT_W4, debug_tune="o=2,8,0,0"))
     assert tuned > 0
 
 

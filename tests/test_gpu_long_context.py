@@ -4,8 +4,7 @@ the operating range of the long-context workload (Section 1: every decoded token
 There the final merge of a head's group partials takes its second loop (16 partials are preloaded, the rest come 8
 per trip), which shorter contexts never enter.  The engine is compared with the CPU oracle element by element: the
 prompt's ACS and last-row logits (prompt pass in blocks), then multi-row and single-row passes whose rows straddle a
-group boundary, for head_dim 32 (grouped-query) and head_dim 128, through the dataflow pass kernel and through the
-per-step kernels with both register variants of the attention kernel.
+group boundary, for head_dim 32 (grouped-query) and head_dim 128, with both register variants of the attention kernel.
 
 Stated tolerances: logits 2e-2 (bf16) of the row's largest |logit|, cosines 1e-3; asserted: the working bounds of
 test_gpu_parity.py (2e-4, 2e-5).
@@ -45,7 +44,7 @@ def oracle_run(name):
     return W, toks, res
 
 
-VARIANTS = {"dataflow": 0, "step-kernels": asd.DBG_STEP_KERNELS, "step-kernels-w4-attention": asd.DBG_STEP_KERNELS | asd.DBG_ATT_W4}
+VARIANTS = {"default-attention": 0, "four-waves-per-simd-attention": asd.DBG_ATT_W4}
 
 
 @pytest.mark.parametrize("variant", list(VARIANTS))

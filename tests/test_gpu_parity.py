@@ -304,40 +304,6 @@ def test_graph_replays_match_eager():
         assert ms > 0
 
 
-@pytest.mark.parametrize("shape", [MID16, si.SHAPES["tiny"], BF_GQA], ids=lambda s: s.name)
-def test_dataflow_pass_kernel_matches_step_kernels_bitwise(shape):
-    """The one-launch-per-pass kernel runs the same block functions as the per-step kernels, with write-through stores,
-    per-step output buffers and completion counters between the steps: logits, cosines and generated tokens must equal
-    the per-step path bit for bit, for packed (<= 8 rows) and two-operand passes, one and several attention groups,
-    and under skip masks.  The per-step engine is pinned to the dataflow kernel's launch shapes (8 waves per
-    workgroup, one tile per workgroup for QKV and gate/up), which fix the order of every sum."""
-    toks = si.prompt(8, 700, shape.vocab)
-    mask = np.zeros(2 * shape.n_layers, np.uint8); mask[1] = mask[4] = 1
-    results = []
-    for flags, tune in ((asd.DBG_STEP_KERNELS, "qkv=1,8,1,1;gu=1,8,0,0"), (0, None)):
-        eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags, debug_tune=tune)).init_synthetic(5)
-        got = []
-        first, acs, lg = eng.prefill(toks[:140], want_logits=True)
-        got += [first, acs, lg]
-        for M, skip in ((5, None), (1, mask), (9, None), (16, mask), (1, None), (8, None)):
-            r = eng.forward(toks[140:140 + M], 140, skip, commit=False)
-            got += [r["logits"], r["cos_rows"], r["cos"], r["argmax"]]
-        out, st, _ = eng.generate(toks[:100], 20, 3, fixed_mask=mask, use_graphs=False)
-        got += [out, st["accepted"]]
-        eng.prefill(toks[:600])                                # three attention groups per head
-        pos = 600
-        for M in (1, 4, 9, 2):
-            r = eng.forward(toks[pos:pos + M], pos)
-            got += [r["logits"], r["cos_rows"]]
-            pos += M
-        out, st, _ = eng.decode(int(toks[pos]), 30, 4, alpha=0.9, m=2, n=1)
-        got += [out, st["accepted"]]
-        results.append(got)
-        eng.close()
-    for x, y in zip(*results):
-        assert np.array_equal(np.asarray(x), np.asarray(y))
-
-
 def test_degenerate_sizes():
     """One-token prompt, one new token, the longest draft the row limit allows, and a cache filled to its last slot."""
     s = si.SHAPES["tiny"]
@@ -374,7 +340,7 @@ def test_attention_register_variants_give_the_same_bits():
     shape = MID16
     toks = si.prompt(4, 700, shape.vocab)
     outs = []
-    for flags in (asd.DBG_STEP_KERNELS, asd.DBG_STEP_KERNELS | asd.DBG_ATT_W4):
+    for flags in (0, asd.DBG_ATT_W4):
         eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags)).init_synthetic(2)
         eng.prefill(toks[:690])
         a = eng.forward(toks[690:695], 690)
@@ -396,7 +362,7 @@ def test_query_heads_per_attention_workgroup_give_the_same_bits(shape):
     contexts of several groups alike."""
     toks = si.prompt(6, 700, shape.vocab)
     outs = []
-    for flags in (0, asd.DBG_ATT_GH1, asd.DBG_STEP_KERNELS, asd.DBG_STEP_KERNELS | asd.DBG_ATT_GH1):
+    for flags in (0, asd.DBG_ATT_GH1):
         eng = asd.Engine(asd.make_config(shape, 768, debug_flags=flags)).init_synthetic(5)
         got = []
         pos = 0
@@ -414,10 +380,8 @@ def test_query_heads_per_attention_workgroup_give_the_same_bits(shape):
         got.append(out)
         outs.append(got)
         eng.close()
-    # (dataflow and per-step engines split K differently in two launches: compare each with its own single-head variant)
-    for a, b in ((0, 1), (2, 3)):
-        for x, y in zip(outs[a], outs[b]):
-            assert np.array_equal(x, y)
+    for x, y in zip(*outs):
+        assert np.array_equal(x, y)
 
 
 # K sizes that put a wave's share of the weight stream (K / 32 k-blocks over 8 waves, ring of 4 slots) into every
