@@ -225,6 +225,33 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
                 int32_t commit, float* logits, float* cos, float* cos_rows, int32_t* argmax);
 
 /*
+ * asd_forward for callers that cannot allocate device memory or wait for the device while they enqueue work: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same pass, same kernels, same
+ * bits as asd_forward, but
+ *   - d_tokens [n_rows] is a DEVICE pointer, and so are the outputs d_logits [n_rows][vocab], d_cos [2L] (mean over
+ *     the rows; a removed sublayer reports exactly 1) and d_argmax [n_rows], each optional (NULL); skip_mask is a
+ *     HOST array, read before the call returns;
+ *   - everything is enqueued on the engine's stream and the call returns without synchronising: the outputs are
+ *     valid once the stream has reached this point;
+ *   - the kernels' scratch (partial sums of the cosine taps and norms, attention partials and their arrival counters,
+ *     argmax candidates) lives in a static device array of the library, ASD_NOALLOC_SCRATCH_BYTES per GPU, held until
+ *     the process ends, instead of in the engine's arena.  The call allocates nothing on the device and calls no
+ *     allocating runtime routine.  A pass whose scratch does not fit (it grows with heads x head_dim x context:
+ *     the 7B shape fits up to 7680 positions) is refused with ASD_E_NOMEM;
+ *   - every such call on a GPU uses that GPU's one array: calls that overlap on one GPU (two engines, two streams)
+ *     race.  The array keeps the last call's contents; the call clears what must start at zero itself;
+ *   - a token id outside the vocabulary cannot be refused up front (the ids are on the device): it is replaced by
+ *     token 0 and raises a device flag that asd_check reports.
+ * pos0 must equal asd_kv_len(); commit != 0 leaves kv_len at pos0 + n_rows.
+ * asd_check synchronises the engine's stream and returns ASD_OK, or the error a kernel flagged since the last pass
+ * started (ASD_E_INVAL: token id outside the vocabulary; ASD_E_STATE: a row of logits without a finite maximum).
+ */
+#define ASD_NOALLOC_SCRATCH_BYTES (8u << 20)
+int asd_forward_noalloc(asd_engine* e, const int32_t* d_tokens, int32_t n_rows, int32_t pos0, const uint8_t* skip_mask,
+                        int32_t commit, float* d_logits, float* d_cos, int32_t* d_argmax);
+int asd_check(asd_engine* e);
+
+/*
  * Prompt pass (Section 3.2, the definition of C_l): resets the cache, runs all n prompt tokens
  * through the full model, returns the first generated token, the ACS of every
  * sublayer over the n rows (cos_out [2L], optional) and the logits of the last row

@@ -94,6 +94,8 @@ def lib():
         L.asd_truncate.argtypes = [vp, i32]
         L.asd_kv_len.argtypes = [vp]
         L.asd_forward.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
+        L.asd_forward_noalloc.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp]
+        L.asd_check.argtypes = [vp]
         L.asd_prefill.argtypes = [vp, vp, i32, vp, vp, vp]
         L.asd_prefill_chunked.argtypes = [vp, vp, i32, vp, vp, vp]
         L.asd_admg2.argtypes = [vp, i32, ctypes.c_float, i32, i32, i32, ctypes.c_float, i32, vp]
@@ -235,6 +237,18 @@ class Engine:
         self._ck(lib().asd_forward(self._h, tok.ctypes.data, n, pos0, _ptr(sk), int(commit), _ptr(logits),
                                    cos.ctypes.data, cos_rows.ctypes.data, am.ctypes.data))
         return {"logits": logits, "cos": cos, "cos_rows": cos_rows, "argmax": am}
+
+    def forward_noalloc(self, d_tokens, pos0: int, skip=None, commit: bool = True, d_logits=None, d_cos=None, d_argmax=None):
+        """asd_forward_noalloc: tokens and outputs are device tensors (int32 [n], float32 [n, V], float32 [2L], int32 [n]);
+        enqueues on the engine's stream and returns without synchronising."""
+        sk = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
+        ptr = lambda t: None if t is None else t.data_ptr()
+        self._ck(lib().asd_forward_noalloc(self._h, d_tokens.data_ptr(), d_tokens.numel(), pos0, _ptr(sk), int(commit),
+                                           ptr(d_logits), ptr(d_cos), ptr(d_argmax)))
+
+    def check(self):
+        """Synchronise the engine's stream and raise if a kernel flagged an error since the last pass started."""
+        self._ck(lib().asd_check(self._h))
 
     def prefill(self, tokens, want_logits: bool = False, chunked: bool = False):
         tok = np.ascontiguousarray(tokens, dtype=np.int32)

@@ -21,9 +21,34 @@
 #include <string>
 #include <vector>
 
+// Scratch of asd_forward_noalloc: the partial sums, attention partials, counters and argmax candidates of one pass.
+// One copy per GPU the library runs on, held until the process ends.  In host code the array's name is only a stand-in
+// for the symbol: the address kernels can use comes from hipGetSymbolAddress (scratch_ptr below), once per device.
+#define ASD_SCRATCH_BYTES ASD_NOALLOC_SCRATCH_BYTES
+static __device__ __align__(256) unsigned char scratch[ASD_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_create_error;
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_scratch_ptr[kMaxDevices];      // per device: address of that device's copy of `scratch`
+
+// The current device's scratch address (looked up on the first call per device, with that device current).
+hipError_t scratch_ptr(unsigned char** out) {
+    int dev = 0;
+    hipError_t r = hipGetDevice(&dev);
+    if (r != hipSuccess) return r;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        r = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (r != hipSuccess) return r;
+        g_scratch_ptr[dev] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 struct GemmCfg { int TN, NW, grid, kmajor, kint; };
 struct PfCfg { int NC, KS, PD; };      // prompt GEMM: 16-row chunks per workgroup, K slices
@@ -87,6 +112,7 @@ struct asd_engine {
     DevState* h_st;                     // pinned
     std::map<std::vector<int>, hipGraphExec_t> graphs;
     std::vector<uint8_t> graph_mask;
+    unsigned char* scratch = nullptr;   // this device's copy of the static scratch array (asd_forward_noalloc)
     std::string tune;                   // copy of the configuration's debug_tune
     bool sample_mem = false;            // ASD_DBG_SAMPLE_MEM: sampling kernels that re-read memory instead of holding their segments
     bool att_gh1 = false;               // ASD_DBG_ATT_GH1: one query head per attention workgroup also for grouped-query models
@@ -473,7 +499,7 @@ struct Prof {
 
 // Where a pass's results go (the engine's own buffers, or a caller's device buffers) and where its kernels keep what
 // they exchange: partial sums, attention partials and their arrival counters, argmax candidates (the engine's arena,
-// or another region a caller of build_pass names).
+// or the library's static scratch array).
 struct PassOut {
     float* logits;       // [rows][vocab]
     int32_t* argmax;     // [16]
@@ -883,6 +909,10 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->acs_valid = false;
     e->h_st = nullptr;
 
+    {   // the static scratch of asd_forward_noalloc: resolve this device's address now, not in the middle of a caller's loop
+        const hipError_t rs = scratch_ptr(&e->scratch);
+        if (rs != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(rs)); }
+    }
     hipError_t r = hipHostMalloc((void**)&e->h_st, sizeof(DevState), hipHostMallocDefault);
     if (r != hipSuccess) { delete e; return fail(nullptr, ASD_E_HIP, "hipHostMalloc: %s", hipGetErrorString(r)); }
     for (int i = 0; i < 3 && r == hipSuccess; ++i) r = hipEventCreate(&e->ev[i]);
@@ -1124,6 +1154,67 @@ int asd_forward(asd_engine* e, const int32_t* tokens, int32_t n_rows, int32_t po
     if (argmax) memcpy(argmax, am.data(), (size_t)n_rows * 4);
     if (commit) e->kv_len = pos0 + n_rows;
     return ASD_OK;
+}
+
+// The static scratch laid out for a pass of an engine's shape over a context of `groups` attention groups per head.
+// Returns the bytes needed (the layout is valid when they fit ASD_SCRATCH_BYTES).
+static size_t scratch_layout(const asd_engine* e, int groups, unsigned char* base, PassOut* o) {
+    const asd_config& c = e->c;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char* p = base + off; off = align_up(off + bytes); return p; };
+    int pmax = e->g_o.grid > e->g_down.grid ? e->g_o.grid : e->g_down.grid;
+    if (pmax < EMBED_SPLIT) pmax = EMBED_SPLIT;
+    o->ssq = (float*)take(ASD_ROWS * 4);
+    o->part = (float*)take((size_t)pmax * ASD_ROWS * 2 * 4);
+    o->cos_rows = (float*)take((size_t)2 * c.n_layers * ASD_ROWS * 4);
+    o->cos_acc = (double*)take((size_t)2 * c.n_layers * 8);
+    o->arrivals = (unsigned*)take((size_t)c.n_heads * 4);
+    o->amax_part = (AmaxPart*)take((size_t)e->g_lm.grid * ASD_ROWS * sizeof(AmaxPart));
+    o->argmax = (int32_t*)take(ASD_ROWS * 4);
+    o->ml_part = (float*)take((size_t)c.n_heads * groups * ASD_ROWS * 8);
+    o->o_part = (float*)take((size_t)c.n_heads * groups * ASD_ROWS * c.head_dim * 4);
+    o->nc_stride = groups;
+    return off;
+}
+
+int asd_forward_noalloc(asd_engine* e, const int32_t* d_tokens, int32_t n_rows, int32_t pos0, const uint8_t* mask, int32_t commit,
+                        float* d_logits, float* d_cos, int32_t* d_argmax) {
+    if (!e) return ASD_E_INVAL;
+    if (!d_tokens) return fail(e, ASD_E_INVAL, "d_tokens is NULL");
+    if (n_rows < 1 || n_rows > e->c.max_rows) return fail(e, ASD_E_INVAL, "n_rows %d outside [1, %d]", n_rows, e->c.max_rows);
+    if (!weights_ready(e)) return fail(e, ASD_E_STATE, "weights are not fully loaded");
+    if (pos0 != e->kv_len) return fail(e, ASD_E_STATE, "pos0 %d differs from the cache length %d", pos0, e->kv_len);
+    if (pos0 + n_rows > capacity(e)) return fail(e, ASD_E_INVAL, "position %d exceeds the cache capacity %d", pos0 + n_rows, capacity(e));
+    const int L2 = 2 * e->c.n_layers;
+    const int groups = (pos0 + n_rows + ATT_GROUP - 1) / ATT_GROUP;
+    PassOut out{};
+    const size_t need = scratch_layout(e, groups, e->scratch, &out);
+    if (need > ASD_SCRATCH_BYTES)
+        return fail(e, ASD_E_NOMEM, "a pass of this shape over %d positions needs %zu bytes of scratch, the static array holds %u",
+                    pos0 + n_rows, need, (unsigned)ASD_SCRATCH_BYTES);
+    out.logits = d_logits ? d_logits : e->logits;
+    if (d_argmax) out.argmax = d_argmax;
+    // what must start at zero: the running cosine sums and the heads' arrival counters (neighbours in the layout)
+    const int nz = (int)(((unsigned char*)out.amax_part - (unsigned char*)out.cos_acc) / 4);
+    zero_words_kernel<<<(nz + 255) / 256, 256, 0, e->stream>>>((uint32_t*)out.cos_acc, nz);
+    set_state_kernel<<<1, 1, 0, e->stream>>>(e->st, e->kv_len, 0, 0, 0);
+    const int rc = enqueue_forward(e, d_tokens, n_rows, 0, mask, chunks_for(e->kv_len + n_rows - 1), nullptr, e->kv_len + n_rows, FIN_NONE, 0, &out);
+    if (rc) return rc;
+    if (d_cos) {
+        MaskBits mb{};
+        for (int j = 0; j < L2; ++j) if (mask && mask[j]) mb.w[j >> 5] |= 1u << (j & 31);
+        cos_mean_kernel<<<(L2 + 255) / 256, 256, 0, e->stream>>>(out.cos_acc, L2, n_rows, mb, d_cos);
+    }
+    const hipError_t r = hipGetLastError();
+    if (r != hipSuccess) return fail(e, ASD_E_HIP, "kernel launch: %s", hipGetErrorString(r));
+    if (commit) e->kv_len = pos0 + n_rows;
+    return ASD_OK;
+}
+
+int asd_check(asd_engine* e) {
+    if (!e) return ASD_E_INVAL;
+    CK(e, hipStreamSynchronize(e->stream));
+    return check_pass_error(e);
 }
 
 static int prefill_impl(asd_engine* e, const int32_t* tokens, int32_t n, int32_t* first_token, float* cos_out, float* last_logits, bool blocks) {

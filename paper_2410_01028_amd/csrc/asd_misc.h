@@ -144,6 +144,21 @@ __global__ __launch_bounds__(1024) void finish_kernel(const AmaxCand* cand, int 
     finish_block(cand, P, M, V, argmax, mode, j_or_kk, st, tokbuf, out, win);
 }
 
+// ---------------------------------------------------------------- helpers of the entry point that allocates nothing
+// clears n 32-bit words (counters and running sums that must start at zero; a kernel, not a memset, so that a caller
+// may record the call into a HIP graph)
+__global__ void zero_words_kernel(uint32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+// one bit per sublayer of a skip mask, passed to a kernel by value
+struct MaskBits { uint32_t w[128]; };
+// mean over the rows of every sublayer's cosine (a removed sublayer reports exactly 1), to a caller's device buffer
+__global__ void cos_mean_kernel(const double* cos_acc, int n_sub, int rows, MaskBits skip, float* out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < n_sub) out[j] = ((skip.w[j >> 5] >> (j & 31)) & 1u) ? 1.f : (float)(cos_acc[j] / (double)rows);
+}
+
 // ---------------------------------------------------------------- rotary table: cos/sin(pos * theta^(-2i/h)) in double
 __global__ void rope_table_kernel(float* tab, int max_seq, int half, double theta) {
     const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
