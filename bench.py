@@ -9,14 +9,29 @@ verification kernels), the figure the HBM-roofline target is stated for; the spe
 runs (ADMG mask from the prompt's ACS, and the all-keep bracket) are reported beside it with
 their acceptance, which on random-init weights is an artefact of the init.
 
+The default run (7B workload) also carries, in the same JSON line:
+  passes      whole-pass time and fraction of the 8 TB/s HBM peak: full single-row pass, (k+1)-row verification pass,
+              single-row draft pass under the ADMG mask (the target is stated for these: >= 70 %)
+  draft_len_sweep   draft lengths 4, 6, 8 with the all-keep mask and the cosine-only draft model
+  workloads   the 13B, long-context 7B and 70B-GQA workloads: the same three pass timings (the long-context one also
+              under the fixed masks keeping 50 % / 25 % of the sublayers), the prompt pass and a shortened plain decode
+  roofline    the dominant kernel (gate/up GEMM): bytes per launch / launch time, and `traffic` = HBM bytes per launch
+              from two rocprofv3 counter runs of this script (child processes, started before this process touches the GPU)
+  cpu_baseline  the CPU oracle timed on this host: the 7B shape with all host threads and with one, the tiny workload
+
 Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import csv
+import ctypes
 import json
 import os
+import shutil
+import subprocess
 import sys
+import tempfile
 import time
 
 import numpy as np
@@ -25,37 +40,137 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E peak
+COPY_BYTES = 192 << 20    # plain copy kernel of the counter calibration: this many bytes read and written per launch
 
 
-def cpu_baseline(shape, seed, n_prompt=2, n_decode=6):
-    """The oracle as it stands, timed on this host: a short prompt plus a few greedy tokens."""
+def progress(msg):
+    """One line on stderr per finished phase: long workloads stay visibly alive; stdout carries only the JSON line."""
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+# ---------------------------------------------------------------------------------------------- CPU oracle leg
+def omp_threads(n=None):
+    """Set (n given) or read the OpenMP thread count of the oracle's runtime."""
+    omp = ctypes.CDLL("libgomp.so.1")
+    if n is not None:
+        omp.omp_set_num_threads(int(n))
+    return int(omp.omp_get_max_threads())
+
+
+def cpu_baseline(shape, seed, budget_tokens):
+    """The oracle as it stands, timed on this host: the workload's shape at full depth and width, a 2-token prompt,
+    then plain greedy tokens with all host threads and with one thread; and the tiny workload in full (plain and
+    speculative).  `value` is the all-threads rate on the workload's shape."""
     import asd_inputs as si
     import oracle
+    n_all = omp_threads()
     t0 = time.time()
-    orc = oracle.Oracle(shape, n_prompt + n_decode + 1, kv_storage=True)
+    orc = oracle.Oracle(shape, 64, kv_storage=True)
     for t, l, a in si.all_tensors(shape, seed):
         orc.set_weight(t, l, a)
     t_load = time.time() - t0
-    prompt = si.prompt(seed, n_prompt, shape.vocab)
-    t0 = time.time()
-    orc.forward(prompt, 0, want_logits=False)
-    t_prompt = time.time() - t0
-    tok = np.array([1], np.int32)
-    t0 = time.time()
-    for i in range(n_decode):
-        r = orc.forward(tok, n_prompt + i, want_logits=False)
-        tok = r["argmax"][:1].copy()
-    t_dec = time.time() - t0
+    prompt = si.prompt(seed, 2, shape.vocab)
+
+    def run(n_decode):
+        orc.reset()
+        t0 = time.time()
+        orc.forward(prompt, 0, want_logits=False)
+        t_prompt = time.time() - t0
+        tok = np.array([1], np.int32)
+        t0 = time.time()
+        for i in range(n_decode):
+            r = orc.forward(tok, 2 + i, want_logits=False)
+            tok = r["argmax"][:1].copy()
+        return n_decode / (time.time() - t0), t_prompt
+
+    rate_all, t_prompt = run(budget_tokens)
+    progress(f"oracle, {n_all} threads: {rate_all:.2f} tokens/s")
+    n_one = max(2, budget_tokens // 12)
+    omp_threads(1)
+    rate_one, _ = run(n_one)
+    omp_threads(n_all)
+    progress(f"oracle, 1 thread: {rate_one:.3f} tokens/s")
     orc.close()
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": n_decode / t_dec, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{shape.name} shape, full depth and width: {n_prompt}-token prompt then {n_decode} plain greedy "
-                      f"tokens (decode phase timed: {t_dec:.1f} s; prompt {t_prompt:.1f} s; weight generation "
-                      f"{t_load:.1f} s not counted)"}
+    out = {"value": rate_all, "unit": "tokens/s", "cores": n_all, "kind": "oracle",
+           "sample": f"{shape.name} shape, full depth and width: 2-token prompt then {budget_tokens} plain greedy tokens "
+                     f"(decode phase timed; prompt {t_prompt:.1f} s and weight generation {t_load:.1f} s not counted)",
+           "one_thread": {"value": rate_one, "unit": "tokens/s", "cores": 1, "sample": f"same model, {n_one} plain greedy tokens"}}
+    # the tiny workload in full: prompt 32, 32 tokens, draft length 4 (ADMG with m = 2, n = 1)
+    tiny = si.SHAPES["tiny"]
+    orc = oracle.Oracle(tiny, 128, kv_storage=True).load(si.all_tensors(tiny, seed))
+    tp = si.prompt(seed, tiny.prompt_len, tiny.vocab)
+    res = {}
+    for label, nthr in ((f"{n_all}_threads", n_all), ("1_thread", 1)):
+        omp_threads(nthr)
+        t0 = time.time(); orc.generate_plain(tp, tiny.n_new); t_plain = time.time() - t0
+        t0 = time.time(); orc.generate_spec(tp, tiny.n_new, tiny.draft_len, alpha=0.985, m=2, n=1); t_spec = time.time() - t0
+        res[label] = {"plain_tokens_per_s": round(tiny.n_new / t_plain, 2), "speculative_tokens_per_s": round(tiny.n_new / t_spec, 2)}
+    omp_threads(n_all)
+    orc.close()
+    out["tiny"] = dict(res, sample="tiny workload in full (prompt pass included): 32-token prompt, 32 tokens, draft length 4")
+    return out
 
 
-def read_traffic(path):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary, or None."""
+# ---------------------------------------------------------------------------------------------- HBM traffic (counters)
+def pmc_child(workload):
+    """Counter run (child process under rocprofv3 --pmc): the gate/up GEMM launched eagerly over the layers' weights and
+    the plain copy kernel of known size, nothing captured into graphs."""
+    import asd_inputs as si
+    import paper_2410_01028_amd as asd
+    shape = si.SHAPES[workload]
+    eng = asd.Engine(asd.make_config(shape, 64 + 16, page_tokens=64))
+    eng.init_synthetic(0)
+    eng.time_step_class("gateup", 1, 2)
+    eng.copy_bench(COPY_BYTES, 3)
+    eng.close()
+
+
+def measure_traffic(workload):
+    """HBM bytes per launch of the gate/up GEMM from two rocprofv3 counter runs (FETCH_SIZE, then WRITE_SIZE; KiB per
+    dispatch), each scaled by what the same counter reads for the plain copy kernel.  None if the profiler is missing or a
+    run fails."""
+    if shutil.which("rocprofv3") is None:
+        return None
+    got = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        d = tempfile.mkdtemp(prefix=f"asd_pmc_{counter}_", dir="/tmp")
+        cmd = ["rocprofv3", "--pmc", counter, "--output-format", "csv", "-d", d, "-o", "pmc", "--",
+               sys.executable, os.path.join(ROOT, "bench.py"), "--pmc-child", "--workload", workload]
+        try:
+            r = subprocess.run(cmd, cwd="/tmp", env=dict(os.environ, TMPDIR="/tmp"), stdout=subprocess.PIPE, stderr=subprocess.PIPE, timeout=240)
+        except (subprocess.TimeoutExpired, OSError) as ex:
+            progress(f"counter run {counter}: {ex}")
+            return None
+        path = None
+        for base, _, files in os.walk(d):
+            for f in files:
+                if f.endswith("counter_collection.csv"):
+                    path = os.path.join(base, f)
+        if r.returncode != 0 or path is None:
+            progress(f"counter run {counter}: rc {r.returncode}" + (", no counter file" if path is None else ""))
+            return None
+        gu, cp = [], []
+        with open(path) as f:
+            for row in csv.DictReader(f):
+                if row["Counter_Name"] != counter:
+                    continue
+                kname = row["Kernel_Name"]
+                if "gemm_kernel<" in kname and "pf_gemm_kernel" not in kname and kname.split("gemm_kernel<")[1].split(",")[1].strip() == "2":
+                    gu.append(float(row["Counter_Value"]))
+                elif "copy_kernel" in kname:
+                    cp.append(float(row["Counter_Value"]))
+        shutil.rmtree(d, ignore_errors=True)
+        if not gu or not cp:
+            progress(f"counter run {counter}: kernels not found in the counter file")
+            return None
+        factor = (COPY_BYTES / 1024.0) / (sum(cp) / len(cp))
+        got[counter] = {"kib_per_dispatch": round(sum(gu) / len(gu), 1), "copy_kernel_factor": round(factor, 5), "dispatches": len(gu)}
+        progress(f"counter run {counter}: {got[counter]['kib_per_dispatch']:.1f} KiB per gate/up launch, copy-kernel factor {factor:.4f}")
+    total = sum(v["kib_per_dispatch"] * v["copy_kernel_factor"] * 1024.0 for v in got.values())
+    return {"bytes": total, "detail": got}
+
+
+def committed_traffic(path):
     try:
         for ln in open(path):
             if ln.startswith("TRAFFIC_BYTES_PER_LAUNCH"):
@@ -65,20 +180,76 @@ def read_traffic(path):
     return None
 
 
-def progress(msg):
-    """One line on stderr per finished phase: long workloads stay visibly alive; stdout carries only the JSON line."""
-    print(f"[bench] {msg}", file=sys.stderr, flush=True)
-
-
+# ---------------------------------------------------------------------------------------------- GPU helpers
 def copy_rate(eng):
     """GB/s of a plain copy kernel (192 MiB read + 192 MiB written); None when the engine's scratch region is too small
     for that (the tiny workload), where the figure would not be an HBM number anyway."""
     import paper_2410_01028_amd as asd
     try:
-        ms = eng.copy_bench(192 << 20, 10)
+        ms = eng.copy_bench(COPY_BYTES, 10)
     except asd.AsdError:
         return None
-    return round(2 * (192 << 20) / ms / 1e6, 1)
+    return round(2 * COPY_BYTES / ms / 1e6, 1)
+
+
+def pass_entry(eng, rows, mask, reps, n_layers=None):
+    ms, by = eng.time_pass(rows, mask, reps, True)
+    d = {"ms": round(ms, 4), "GBps": round(by / ms / 1e6, 1), "frac_peak": round(by / ms / 1e6 / HBM_PEAK_GBS, 4)}
+    if mask is not None and n_layers is not None:
+        d["kept_attn"] = int(n_layers - mask[0::2].sum())
+        d["kept_mlp"] = int(n_layers - mask[1::2].sum())
+    return d
+
+
+def pass_table(eng, shape, k, acs, reps, fixed_masks=False):
+    """Whole-pass timings at the engine's current cache length: full single-row pass, (k+1)-row verification pass,
+    single-row draft pass under Algorithm 1's mask with Table 2's hyper-parameters."""
+    import asd_inputs as si
+    import paper_2410_01028_amd as asd
+    out = {"full_1row": pass_entry(eng, 1, None, reps),
+           f"verify_{k + 1}rows": pass_entry(eng, k + 1, None, reps),
+           "draft_admg_1row": pass_entry(eng, 1, asd.admg(acs[0::2], 0.985, 3, 2), reps, shape.n_layers)}
+    if fixed_masks:
+        for period, label in ((2, "draft_fixed_keep50pct_1row"), (4, "draft_fixed_keep25pct_1row")):
+            out[label] = pass_entry(eng, 1, si.fixed_keep_mask(shape.n_layers, period), reps, shape.n_layers)
+    return out
+
+
+def run_workload(name, seed, n_decode):
+    """One of the other workloads at its full shape: prompt pass, pass timings at the prompt's end, a shortened plain
+    greedy decode."""
+    import torch
+    import asd_inputs as si
+    import paper_2410_01028_amd as asd
+    shape = si.SHAPES[name]
+    k, P = shape.draft_len, shape.prompt_len
+    eng = asd.Engine(asd.make_config(shape, P + shape.n_new + 16, page_tokens=256))
+    eng.init_synthetic(seed)
+    prompt = si.prompt(seed, P, shape.vocab)
+    first, acs, _ = eng.prefill(prompt)
+    t0 = time.time()
+    first, acs, _ = eng.prefill(prompt)
+    t_prefill = time.time() - t0
+    res = {"config": f"{shape.n_layers} layers, d_model {shape.d_model}, {shape.n_heads} heads ({shape.n_kv_heads} KV) x {shape.head_dim}, "
+                     f"FFN {shape.d_ffn}; prompt {P}, draft length {k}",
+           "prefill_ms": round(t_prefill * 1e3, 1)}
+    eng.decode(first, n_decode, 0)                   # graph capture, first touches, clocks settled on the decode kernels
+    eng.truncate(P)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    plain, st, _ = eng.decode(first, n_decode, 0)
+    dt = time.time() - t0
+    res["plain_greedy"] = {"tokens": n_decode, "tokens_per_s": round(n_decode / dt, 2), "ms_verify_gpu": round(st["ms_verify"], 2),
+                           "GBps": round(st["bytes_verify"] / max(st["ms_verify"], 1e-9) / 1e6, 1)}
+    eng.truncate(P)
+    spec, st, _ = eng.decode(first, n_decode, k, fixed_mask=np.zeros(2 * shape.n_layers, np.uint8))
+    res["all_keep_tokens_equal_plain"] = bool(np.array_equal(spec, plain))
+    eng.truncate(P)
+    res["passes"] = pass_table(eng, shape, k, acs, 10 if name == "70b" else 30, fixed_masks=(name == "7b-long"))
+    eng.close()
+    del eng
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -89,14 +260,25 @@ def main():
     ap.add_argument("--workload", default="7b", help="tiny | 7b | 13b | 7b-long | 70b")
     ap.add_argument("--draft-len", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras")
+    ap.add_argument("--no-extras", action="store_true", help="skip the speculative / per-pass extras, the other workloads and the counter runs")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the 13b / 7b-long / 70b section of the default run")
+    ap.add_argument("--no-traffic", action="store_true", help="skip the two rocprofv3 counter runs (roofline.traffic then comes from profiles/)")
     ap.add_argument("--n-new", type=int, default=None, help="override the workload's number of new tokens (profiling runs)")
     ap.add_argument("--copy-only-extra", action="store_true", help="with --no-extras: still run the plain copy kernel (counter calibration)")
     ap.add_argument("--only-verify-passes", type=int, default=0, metavar="N",
                     help="counter runs: after the prompt pass launch N eager (draft_len+1)-row verification passes and exit")
+    ap.add_argument("--pmc-child", action="store_true", help=argparse.SUPPRESS)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+    if args.pmc_child:
+        pmc_child(args.workload)
+        return
+
+    # the counter runs are child processes of their own; they go first, while this process has not touched the GPU
+    traffic = None
+    if not (args.no_extras or args.no_traffic or args.only_verify_passes) and args.workload in ("7b", "13b", "7b-long"):
+        traffic = measure_traffic(args.workload)
 
     import torch
     import asd_inputs as si
@@ -159,6 +341,10 @@ def main():
                    "mode": "plain greedy (draft length 0), decode phase after the prompt pass", "draft_len_spec": k},
         "prefill_ms": round(t_prefill * 1e3, 2),
         "e2e_tokens_per_s": round(N / (t_prefill + ms_per_step / 1e3), 2),
+        # per-phase accounting of the last timed decode (HIP events between the phases, algorithmic bytes of its passes)
+        "decode_phases": {"ms_draft": round(st_plain["ms_draft"], 3), "ms_verify": round(st_plain["ms_verify"], 3),
+                          "ms_other": round(st_plain["ms_other"], 3),
+                          "verify_GBps": round(st_plain["bytes_verify"] / max(st_plain["ms_verify"], 1e-9) / 1e6, 1)},
     }
     # the prompt pass is the one matrix-core-bound step: flops of the weight contractions (each counted once, although
     # bf16 activations go through the matrix cores as two planes) plus causal attention, against the dense bf16 peak
@@ -197,9 +383,15 @@ def main():
     eng.truncate(P)
     gu_us, bytes_per_launch = eng.time_step_class("gateup", 1, 10)
     achieved = bytes_per_launch / gu_us / 1e3
+    if traffic is not None:
+        traffic_bytes = traffic["bytes"]
+        traffic_source = "two rocprofv3 --pmc runs of this script in this invocation (FETCH_SIZE, WRITE_SIZE), each scaled by the plain copy kernel"
+    else:
+        traffic_bytes = committed_traffic(os.path.join(ROOT, "profiles", f"gemm_gateup_{shape.name}_hbm_traffic.txt"))
+        traffic_source = "profiles/ (committed counter summary; no counter run in this invocation)" if traffic_bytes else None
     out["roofline"] = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                       "frac": round(achieved / HBM_PEAK_GBS, 4),
-                       "traffic": read_traffic(os.path.join(ROOT, "profiles", f"gemm_gateup_{shape.name}_hbm_traffic.txt")),
+                       "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic_bytes, "traffic_source": traffic_source,
+                       "traffic_detail": traffic["detail"] if traffic else None,
                        "kernel": f"gemm_kernel<{'BF16' if shape.dtype else 'F32'}, EPI_GU> (gate/up projection + SiLU*mul)",
                        "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(gu_us, 2)}
     # every class inside a pass, an event pair around each launch (includes the event overhead of ~2 us)
@@ -211,16 +403,13 @@ def main():
         out["copy_kernel_GBps"] = copy_rate(eng)
     if not args.no_extras:
         eng.truncate(P)
-        ms1, by1 = eng.time_pass(1, None, 30, True)
-        msv, byv = eng.time_pass(k + 1, None, 30, True)
-        mask = asd.admg(acs[0::2], 0.985, 3, 2)
-        msd, byd = eng.time_pass(1, mask, 30, True)
-        out["passes"] = {
-            "full_1row": {"ms": round(ms1, 4), "GBps": round(by1 / ms1 / 1e6, 1), "frac_peak": round(by1 / ms1 / 1e6 / HBM_PEAK_GBS, 4)},
-            f"verify_{k + 1}rows": {"ms": round(msv, 4), "GBps": round(byv / msv / 1e6, 1), "frac_peak": round(byv / msv / 1e6 / HBM_PEAK_GBS, 4)},
-            "draft_admg_1row": {"ms": round(msd, 4), "GBps": round(byd / msd / 1e6, 1), "frac_peak": round(byd / msd / 1e6 / HBM_PEAK_GBS, 4),
-                                "kept_attn": int(shape.n_layers - mask[0::2].sum()), "kept_mlp": int(shape.n_layers - mask[1::2].sum())},
-        }
+        out["passes"] = pass_table(eng, shape, k, acs, 30, fixed_masks=(shape.name == "7b-long"))
+        # the stated target is for whole passes, not for the dominant kernel: say so next to the kernel's figure
+        pv = out["passes"][f"verify_{k + 1}rows"]["frac_peak"]
+        p1 = out["passes"]["full_1row"]["frac_peak"]
+        pd = out["passes"]["draft_admg_1row"]["frac_peak"]
+        out["roofline"]["pass_level"] = {"full_1row_frac": p1, f"verify_{k + 1}rows_frac": pv, "draft_admg_1row_frac": pd, "target_frac": 0.70,
+                                         "target_met": {"full_1row": bool(p1 >= 0.70), "verify": bool(pv >= 0.70), "draft": bool(pd >= 0.70)}}
         out["copy_kernel_GBps"] = copy_rate(eng)
         progress("per-pass timings done")
         spec = {}
@@ -245,9 +434,26 @@ def main():
             spec[name] = {"tokens_per_s": round((N - 1) / dt, 2), "speedup_vs_plain": round((N - 1) / dt / value, 3),
                           "cycles": st["cycles"], "drafted": st["drafted"], "accepted": st["accepted"],
                           "removed_attn": int(used[0::2].sum()), "removed_mlp": int(used[1::2].sum()), "mask_changes": st["mask_changes"],
+                          "ms_draft": round(st["ms_draft"], 2), "ms_verify": round(st["ms_verify"], 2), "ms_other": round(st["ms_other"], 2),
+                          "draft_GBps": round(st["bytes_draft"] / st["ms_draft"] / 1e6, 1) if st["ms_draft"] > 0.01 else None,
+                          "verify_GBps": round(st["bytes_verify"] / max(st["ms_verify"], 1e-9) / 1e6, 1),
                           "tokens_equal_plain": bool(np.array_equal(toks, plain))}
             progress(f"speculative {name}: {spec[name]['tokens_per_s']} tokens/s")
         out["speculative"] = spec
+        # draft lengths 4, 6, 8: the all-keep bracket (pure cost of verification) and the cosine-only draft model
+        sweep = {}
+        for kk in (4, 6, 8):
+            for name, kw in (("all_keep", dict(fixed_mask=np.zeros(L2, np.uint8))), ("admg_a0.9999_m0_n0", dict(alpha=0.9999, m=0, n=0))):
+                decode_step(kk, **kw)
+                torch.cuda.synchronize()
+                t0 = time.time()
+                toks, st, used = decode_step(kk, **kw)
+                dt = time.time() - t0
+                sweep[f"k{kk}_{name}"] = {"tokens_per_s": round((N - 1) / dt, 2), "speedup_vs_plain": round((N - 1) / dt / value, 3),
+                                          "cycles": st["cycles"], "drafted": st["drafted"], "accepted": st["accepted"],
+                                          "tokens_equal_plain": bool(np.array_equal(toks, plain))}
+            progress(f"draft length {kk} done")
+        out["draft_len_sweep"] = sweep
         # sampled decoding at the paper's higher temperature: plain sampling of the full model against speculative sampling
         samp = {}
         for name, kk, kw in (("plain_T0.6", 0, dict(fixed_mask=np.zeros(L2, np.uint8))),
@@ -268,15 +474,22 @@ def main():
     del eng
     torch.cuda.empty_cache()
 
+    # ---- the other workloads (full shapes), each with its own engine
+    if shape.name == "7b" and not (args.no_extras or args.no_workloads):
+        out["workloads"] = {}
+        for name, n_dec in (("13b", 48), ("7b-long", 48), ("70b", 24)):
+            out["workloads"][name] = run_workload(name, seed, n_dec)
+            progress(f"workload {name}: plain greedy {out['workloads'][name]['plain_greedy']['tokens_per_s']} tokens/s")
+
     if not args.no_cpu_baseline:
         progress("GPU part done; timing the CPU oracle")
         if shape.name == "tiny":
-            out["cpu_baseline"] = cpu_baseline(shape, seed, 8, 24)
+            out["cpu_baseline"] = cpu_baseline(shape, seed, 24)
         else:
-            # about ten seconds of decoding on the box's 16 host threads: 40 tokens at the 7B size, fewer for larger models
+            # a few seconds of decoding on the machine's host threads: ~24 tokens at the 7B size, fewer for larger models
             per_tok = shape.n_layers * (shape.d_model * (shape.q_dim + 2 * shape.kv_dim) + shape.q_dim * shape.d_model
                                         + 3 * shape.d_model * shape.d_ffn) + shape.vocab * shape.d_model
-            out["cpu_baseline"] = cpu_baseline(shape, seed, 2, max(4, int(40 * 6.6e9 / per_tok)))
+            out["cpu_baseline"] = cpu_baseline(shape, seed, max(4, int(24 * 6.6e9 / per_tok)))
     print(json.dumps(out), flush=True)
 
 
