@@ -1,5 +1,5 @@
 // Prompt processing as large-M contractions: the pass that fills the KV cache and measures the prompt's
-// average cosine similarity per sublayer (Section 3.2, Eq. 1-2) before the draft / verify loop starts.
+// average cosine similarity per sublayer (Section 3.2, the definition of C_l) before the draft / verify loop starts.
 //
 // The prompt is processed in blocks of up to PF_ROWS rows, layer by layer, so every weight is read once per
 // block instead of once per 16 rows.  Activations of a block are kept as 16-row chunks, each chunk in the same
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void pf_embed_kernel(const typename T::elem* E
 }
 
 // grid = valid rows: y = x + sum of the K slices (slice order), residual stream, normed copy for the next sublayer,
-// the row's cosine(x, y) (Eq. 1) and the statistics of y
+// the row's cosine(x, y) (the summand of C_l, Section 3.2) and the statistics of y
 template <class T>
 __global__ __launch_bounds__(256) void pf_resid_kernel(const float* raw, int ksplit, int d, float* xres, void* xb, int64_t xb_plane,
                                                        int64_t xb_chunk, const float* g_next, float* ssq, float* rscale, float* cos_row,
@@ -324,7 +324,7 @@ __global__ __launch_bounds__(256) void pf_resid_kernel(const float* raw, int ksp
     }
 }
 
-// grid = sublayers: adds the block's rows' cosines (fixed order, double) to the running sums of Eq. 2
+// grid = sublayers: adds the block's rows' cosines (fixed order, double) to the running sums of C_l (Section 3.2)
 __global__ __launch_bounds__(256) void pf_cos_sum_kernel(const float* cos_rows /* [sublayers][PF_ROWS] */, int rows, double* cos_acc) {
     __shared__ double red[256];
     const int j = blockIdx.x, tid = threadIdx.x;
