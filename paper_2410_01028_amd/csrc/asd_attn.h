@@ -26,8 +26,9 @@
 #define ATT_GW 4                           // waves (chunks) per group
 #define ATT_GROUP (ATT_GW * ASD_CHUNK)     // keys per group
 #define ATT_RH 4                           // rows per LDS merge pass
-#define ATT_RB 2                           // rows per merge round
-#define ATT_CB 16                          // group partials requested per merge round
+#define ATT_RB 2                           // (head, row) pairs a wave merges per round when it has more than one
+#define ATT_CB 16                          // group partials requested up front per pair, ATT_RB pairs per round
+#define ATT_CB1 36                         // the same with one pair per round (long contexts: one round trip up to 9216 keys)
 #define ATT_NCL 4                          // group statistics per lane: up to 256 groups (64K positions) per head
 
 // device-scope coherent scalar accesses (relaxed atomics: served past the per-XCD L2)
@@ -61,18 +62,19 @@ struct AttnArgs {
     void* out;                // tiled activation [n_h*h]
 };
 
-// Merge the group partials of ATT_RB (head, row) pairs, in ascending chunk order, and write the normalised output.
+// Merge the group partials of RB (head, row) pairs, in ascending chunk order, and write the normalised output.
 // Pair p of the n_pairs pairs of a workgroup's heads is head head0 + p / M, row p % M; this call takes pairs
-// p0 .. p0 + ATT_RB - 1.  Chunk statistics with one chunk per lane, outputs with two head dims per lane; all
-// loads of a round are requested before any is used.  One wave.
-template <class T, int H>
+// p0 .. p0 + RB - 1.  Chunk statistics with one chunk per lane, outputs with two head dims per lane; all
+// loads of a round are requested before any is used.  One wave.  RB pairs per call with CB partials each requested
+// up front; the sums run in ascending group order whatever RB and CB are, so the result is the same bits.
+template <class T, int H, int RB = ATT_RB, int CB = ATT_CB>
 __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, int p0, int n_pairs, int pos0, int lane) {
     const bool mine = 2 * lane < H;
     {
-        float2 st[ATT_RB][ATT_NCL], v[ATT_RB][ATT_CB];
-        int nc[ATT_RB], hd[ATT_RB], row[ATT_RB];
+        float2 st[RB][ATT_NCL], v[RB][CB];
+        int nc[RB], hd[RB], row[RB];
 #pragma unroll
-        for (int rb = 0; rb < ATT_RB; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             const int pp = p0 + rb < n_pairs ? p0 + rb : p0;        // an inactive slot aliases the first pair and loads nothing
             hd[rb] = head0 + pp / a.M; row[rb] = pp % a.M;
             const int head = hd[rb], mm = row[rb];
@@ -85,11 +87,11 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, in
                 st[rb][q] = cc < nc[rb] ? coherent_load2(ml + (size_t)cc * ASD_ROWS * 2) : float2{-INFINITY, 0.f};
             }
 #pragma unroll
-            for (int u = 0; u < ATT_CB; ++u)
+            for (int u = 0; u < CB; ++u)
                 v[rb][u] = (mine && u < nc[rb]) ? coherent_load2(opm + (size_t)u * ASD_ROWS * H) : float2{0.f, 0.f};
         }
 #pragma unroll
-        for (int rb = 0; rb < ATT_RB; ++rb) {
+        for (int rb = 0; rb < RB; ++rb) {
             if (p0 + rb >= n_pairs) break;
             const int head = hd[rb], mm = row[rb];
             float gmax = -INFINITY;
@@ -110,12 +112,12 @@ __device__ __forceinline__ void attn_merge_rows(const AttnArgs& a, int head0, in
             };
             float2 acc = float2{0.f, 0.f};
 #pragma unroll
-            for (int u = 0; u < ATT_CB; ++u) {                 // ascending chunk order
+            for (int u = 0; u < CB; ++u) {                 // ascending chunk order
                 const float wgt = weight(u);
                 if (u < nc[rb]) { acc.x += v[rb][u].x * wgt; acc.y += v[rb][u].y * wgt; }
             }
             const float* opm = a.o_part + ((size_t)head * a.nc_stride * ASD_ROWS + mm) * H + 2 * lane;
-            for (int c0 = ATT_CB; c0 < nc[rb]; c0 += 8) {      // contexts beyond ATT_CB chunks: 8 more per trip
+            for (int c0 = CB; c0 < nc[rb]; c0 += 8) {          // contexts beyond CB groups: 8 more per trip
                 float2 x[8];
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
@@ -323,7 +325,11 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         if (hw == 0 && lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int n_pairs = a.gh * a.M;
-        for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H>(a, head, p0, n_pairs, pos0, lane);
+        if (n_pairs <= ATT_GW) {                      // at most one pair per wave: all of a long context's partials in one round trip
+            if (hw < n_pairs) attn_merge_rows<T, H, 1, ATT_CB1>(a, head, hw, n_pairs, pos0, lane);
+        } else {
+            for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H>(a, head, p0, n_pairs, pos0, lane);
+        }
     }
     __syncthreads();
 }
