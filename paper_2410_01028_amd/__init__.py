@@ -151,7 +151,9 @@ def _ptr(a):
 class Engine:
     """One engine on the current CUDA/HIP device; owns a torch uint8 arena it lends to the library."""
 
-    def __init__(self, cfg: Config, device: str = "cuda:0"):
+    def __init__(self, cfg: Config, device: str = "cuda:0", arena_fill: int | None = None):
+        """arena_fill: byte value the arena is filled with before the library sees it (tests: every region the
+        library reads must have been written by the library first); None leaves the allocator's bytes."""
         import torch
         self._torch = torch
         self.cfg = cfg
@@ -161,6 +163,9 @@ class Engine:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.arena = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        if arena_fill is not None:
+            self.arena.fill_(arena_fill)
+            torch.cuda.synchronize(self.device)
         base = (self.arena.data_ptr() + 255) // 256 * 256
         # a stream of its own (default priority): graph capture is not allowed on the legacy default stream
         self.stream = torch.cuda.Stream(self.device)
