@@ -25,15 +25,15 @@
 
 #define ATT_GW 4                           // waves (chunks) per group
 #define ATT_GROUP (ATT_GW * ASD_CHUNK)     // keys per group
-#define ATT_RH 4                           // rows per LDS merge pass
+#define ATT_RH 8                           // columns per LDS merge pass (one pass for the passes of at most 8 rows)
 #define ATT_RB 2                           // (head, row) pairs a wave merges per round when it has more than one
 #define ATT_CB 16                          // group partials requested up front per pair, ATT_RB pairs per round
 #define ATT_CB1 36                         // the same with one pair per round (long contexts: one round trip up to 9216 keys)
 #define ATT_NCL 4                          // group statistics per lane: up to 256 groups (64K positions) per head
 
 // device-scope coherent scalar accesses (relaxed atomics: served past the per-XCD L2)
-__device__ __forceinline__ void coherent_store(float* p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void coherent_store2(float* p, float x, float y) {     // p 8-byte aligned
+    __hip_atomic_store((uint64_t*)p, (uint64_t)__float_as_uint(x) | ((uint64_t)__float_as_uint(y) << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float coherent_load(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -198,27 +198,31 @@ __device__ __forceinline__ void att_group_merge(const AttnArgs& a, int grp, int 
             for (int ht = 0; ht < HT; ++ht) *(f32x4*)&so[((size_t)hw * ATT_RH + (m - m0)) * H + ht * 16 + 4 * g] = o[ht];
         }
         __syncthreads();
-        for (int idx = hw * 64 + lane; idx < ATT_RH * H; idx += ATT_GW * 64) {
-            const int rr = idx / H, hd = idx % H, col = m0 + rr, mm = col % a.RS, hh = head + col / a.RS;
+        const int n_here = n_cols - m0 < ATT_RH ? n_cols - m0 : ATT_RH;                 // columns of this pass
+        for (int idx = hw * 64 + lane; idx < n_here * (H / 2); idx += ATT_GW * 64) {       // two head dims per thread and trip
+            const int rr = idx / (H / 2), hd = 2 * (idx % (H / 2)), col = m0 + rr, mm = col % a.RS, hh = head + col / a.RS;
             if (!valid || col >= n_cols || mm >= a.M) continue;
             float gmax = -INFINITY;
 #pragma unroll
             for (int ww = 0; ww < ATT_GW; ++ww) gmax = fmaxf(gmax, sml[(ww * ASD_ROWS + col) * 2]);
-            float L = 0.f, acc = 0.f;
+            float L = 0.f, acc0 = 0.f, acc1 = 0.f;
             if (gmax != -INFINITY) {
 #pragma unroll
                 for (int ww = 0; ww < ATT_GW; ++ww) {          // a chunk the row does not see has max -inf: weight 0
                     const float wgt = __expf(sml[(ww * ASD_ROWS + col) * 2] - gmax);
+                    const float2 v = *(const float2*)&so[((size_t)ww * ATT_RH + rr) * H + hd];
                     L += sml[(ww * ASD_ROWS + col) * 2 + 1] * wgt;
-                    acc += so[((size_t)ww * ATT_RH + rr) * H + hd] * wgt;
+                    acc0 += v.x * wgt;
+                    acc1 += v.y * wgt;
                 }
             }
             if (n_groups == 1) {
-                store_act<T>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc / L);
+                store_act<T>(a.out, a.out_plane, a.RS, hh * H + hd, mm, acc0 / L);
+                store_act<T>(a.out, a.out_plane, a.RS, hh * H + hd + 1, mm, acc1 / L);
             } else {
                 const size_t row = ((size_t)hh * a.nc_stride + grp) * ASD_ROWS + mm;
-                coherent_store(a.o_part + row * H + hd, acc);
-                if (hd == 0) { coherent_store(a.ml_part + row * 2, gmax); coherent_store(a.ml_part + row * 2 + 1, L); }
+                coherent_store2(a.o_part + row * H + hd, acc0, acc1);
+                if (hd == 0) coherent_store2(a.ml_part + row * 2, gmax, L);
             }
         }
         __syncthreads();
