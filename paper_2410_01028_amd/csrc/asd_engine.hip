@@ -103,6 +103,7 @@ struct asd_engine {
     PfCfg pf_qkv, pf_o, pf_gu, pf_down;
     // launch shapes
     GemmCfg g_qkv, g_o, g_gu, g_down, g_lm;
+    GemmCfg g_qkv_rows;                 // QKV launch shape of passes of at least QKV_ROWS_MIN rows (same layout, same bits)
     // host state
     int kv_len;
     std::vector<float> acs;
@@ -225,6 +226,27 @@ GemmCfg pick_cfg(const asd_config& c, int epi, int cls, int tiles, int KB) {
     int v[4];
     if (tune_entry(c.debug_tune, names[cls], v, 4) == 4) { g.TN = v[0]; g.NW = v[1]; g.kmajor = v[2]; g.kint = v[3]; }
     g.grid = (tiles + g.TN - 1) / g.TN;
+    return g;
+}
+
+// QKV in passes of several rows.  Every workgroup reads the whole activation vector of every row (as many bytes as its
+// weights at 8 rows), and the tiles of one workgroup share those loads: with three tiles per workgroup the 7B QKV
+// launch takes 18.5 us at 1, 5, 7 and 9 rows alike, with one tile 17.9 / 18.9 / 19.9 / 21.9 us.  The tiles of a
+// workgroup are independent outputs and the waves split K the same way, so the bits do not depend on the choice
+// (`test_tiles_per_qkv_workgroup_give_the_same_bits`).  Rule: from QKV_ROWS_MIN rows on, the largest of 3, 2, 1 tiles
+// per workgroup that leaves the busiest compute unit with no more tiles than one tile per workgroup does.
+#define QKV_ROWS_MIN 5
+GemmCfg pick_qkv_rows(const asd_config& c, const GemmCfg& base, int tiles, const char* tune) {
+    GemmCfg g = base;
+    int v[4];
+    if (tune_entry(tune, "qkv", v, 4) == 4) return g;               // an explicit launch shape holds for every row count
+    const int units = device_units();
+    auto busiest = [&](int tn) { return ((tiles + tn - 1) / tn + units - 1) / units * tn; };
+    for (int tn = 3; tn > base.TN; --tn)
+        if (busiest(tn) <= busiest(base.TN)) { g.TN = tn; break; }
+    if (tune_entry(tune, "qkv_rows", v, 1) == 1 && v[0] >= 1 && v[0] <= 3) g.TN = v[0];
+    g.grid = (tiles + g.TN - 1) / g.TN;
+    (void)c;
     return g;
 }
 
@@ -400,7 +422,7 @@ void launch_gemm_inst(hipStream_t s, int grid, const GemmArgs& a) {
 template <class T, int EPI>
 bool launch_gemm_t(hipStream_t s, const GemmCfg& g, const GemmArgs& a) {
 #define CASE(tn, nw) if (g.TN == tn && g.NW == nw) { launch_gemm_inst<T, EPI, tn, nw>(s, g.grid, a); return true; }
-    if constexpr (EPI == EPI_QKV) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) }
+    if constexpr (EPI == EPI_QKV) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) CASE(3, 4) CASE(3, 8) }
     if constexpr (EPI == EPI_RES) { CASE(1, 4) CASE(1, 8) CASE(1, 16) CASE(2, 4) CASE(2, 8) CASE(2, 16) }
     if constexpr (EPI == EPI_GU) { CASE(1, 4) CASE(1, 8) CASE(2, 4) CASE(2, 8) }
     if constexpr (EPI == EPI_LM) { CASE(1, 4) CASE(1, 8) CASE(2, 4) CASE(2, 8) }
@@ -413,6 +435,8 @@ template <int EPI> bool launch_gemm(asd_engine* e, const GemmCfg& g, const GemmA
 }
 
 int capacity(const asd_engine* e);
+
+static const GemmCfg& qkv_cfg(const asd_engine* e, int M) { return M >= QKV_ROWS_MIN ? e->g_qkv_rows : e->g_qkv; }
 
 // Row stride of the tiled activation buffers of an M-row pass (rows per k-group).  The activation bytes a GEMM
 // workgroup reads grow with it, so it is the row count itself, not the next power of two (a 5-row verification
@@ -561,7 +585,7 @@ void build_pass(asd_engine* e, int M, int pos_off, const uint8_t* mask, int ctx_
             a.kv = e->kv + (size_t)l * e->kv_layer_bytes;
             a.q = e->q;
             consume(a);
-            push(OP_QKV, ASD_K_QKV, e->g_qkv.grid, cls_bytes[ASD_K_QKV] / L).g = a;
+            push(OP_QKV, ASD_K_QKV, qkv_cfg(e, M).grid, cls_bytes[ASD_K_QKV] / L).g = a;
 
             AttnArgs t{};
             t.q = a.q; t.q_plane = base.q_plane; t.out_plane = (int64_t)e->KBq * 64 * e->KE; t.kv = a.kv;
@@ -622,7 +646,7 @@ int launch_steps(asd_engine* e, const std::vector<PassOp>& ops, const int32_t* d
                     embed_kernel<F32><<<dim3(EMBED_SPLIT, M), EMBED_THREADS, 0, e->stream>>>((const float*)e->embed, d_tokens, c.d_model, c.vocab, e->st,
                         next_gain(e, mask, -1), e->xres, e->xb, (size_t)e->KBd * 64 * e->KE, RS, out.part);
                 break;
-            case OP_QKV: ok = launch_gemm<EPI_QKV>(e, e->g_qkv, op.g); break;
+            case OP_QKV: ok = launch_gemm<EPI_QKV>(e, qkv_cfg(e, M), op.g); break;
             case OP_OPROJ: ok = launch_gemm<EPI_RES>(e, e->g_o, op.g); break;
             case OP_DOWN: ok = launch_gemm<EPI_RES>(e, e->g_down, op.g); break;
             case OP_GU: ok = launch_gemm<EPI_GU>(e, e->g_gu, op.g); break;
@@ -898,6 +922,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->pf_qkv = pf_pick(tune, "pf_qkv", 4, 1); e->pf_o = pf_pick(tune, "pf_o", 4, 4);
     e->pf_gu = pf_pick(tune, "pf_gu", 4, 1); e->pf_down = pf_pick(tune, "pf_down", 4, 4);
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
+    e->g_qkv_rows = pick_qkv_rows(e->c, e->g_qkv, e->qkv_tiles, tune);
     e->att_gh1 = (cfg->debug_flags & ASD_DBG_ATT_GH1) != 0;
     e->sample_mem = (cfg->debug_flags & ASD_DBG_SAMPLE_MEM) != 0;
     e->force_att_w4 = (cfg->debug_flags & ASD_DBG_ATT_W4) != 0;

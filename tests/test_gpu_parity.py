@@ -354,6 +354,35 @@ def test_attention_register_variants_give_the_same_bits():
 GQA8 = si.Shape("gqa8", 2, 256, 16, 2, 64, 688, 1024, si.DT_BF16, 40, 12, 4)
 
 
+@pytest.mark.parametrize("shape", [BF_GQA, MID16, MID32], ids=lambda s: s.name)
+def test_tiles_per_qkv_workgroup_give_the_same_bits(shape):
+    """Passes of five rows and more launch the QKV GEMM with up to three tiles per workgroup (the tiles share the
+    activation loads) where that keeps the compute units balanced; the small test shapes never qualify on their own.
+    A workgroup's tiles are independent outputs and its waves split K the same way, so forcing one, two and three tiles
+    for those passes must not change a bit (tile counts that are not multiples of three included), and the rows of a
+    pass must still equal single-row passes."""
+    toks = si.prompt(9, 400, shape.vocab)
+    outs = []
+    for tn in (1, 2, 3):
+        eng = asd.Engine(asd.make_config(shape, 512, debug_tune=f"qkv_rows={tn}")).init_synthetic(4)
+        eng.prefill(toks[:300])
+        got = []
+        pos = 300
+        for M in (5, 7, 9, 16):
+            r = eng.forward(toks[pos:pos + M], pos)
+            got += [r["logits"], r["cos_rows"]]
+            pos += M
+        multi = eng.forward(toks[pos:pos + 6], pos, commit=False)
+        for i in range(6):
+            one = eng.forward(toks[pos + i:pos + i + 1], pos + i)
+            assert np.array_equal(one["logits"][0], multi["logits"][i]), (tn, i)
+        outs.append(got)
+        eng.close()
+    for other in outs[1:]:
+        for x, y in zip(outs[0], other):
+            assert np.array_equal(x, y)
+
+
 @pytest.mark.parametrize("shape", [BF_GQA, MID16, GQA8, SMALL_GQA], ids=lambda s: s.name)
 def test_query_heads_per_attention_workgroup_give_the_same_bits(shape):
     """Grouped-query models: a decode-attention workgroup takes as many query heads of a KV head as fit the 16
