@@ -329,8 +329,13 @@ __device__ __forceinline__ void attn_group(const AttnArgs& a, const int grp, con
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         if (hw == 0 && lane == 0) __hip_atomic_store(a.arrivals + head, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int n_pairs = a.gh * a.M;
-        if (n_pairs <= ATT_GW) {                      // at most one pair per wave: all of a long context's partials in one round trip
-            if (hw < n_pairs) attn_merge_rows<T, H, 1, ATT_CB1>(a, head, hw, n_pairs, pos0, lane);
+        // One pair per call with ATT_CB1 partials requested up front, or ATT_RB pairs per call with ATT_CB each: whichever
+        // takes the busiest wave through fewer memory round trips (the same sums in the same order either way)
+        const int per_wave = (n_pairs + ATT_GW - 1) / ATT_GW;
+        const int trips1 = per_wave * (1 + (n_groups > ATT_CB1 ? (n_groups - ATT_CB1 + 7) / 8 : 0));
+        const int trips2 = (per_wave + ATT_RB - 1) / ATT_RB * (1 + (n_groups > ATT_CB ? (n_groups - ATT_CB + 7) / 8 : 0));
+        if (trips1 <= trips2) {
+            for (int p0 = hw; p0 < n_pairs; p0 += ATT_GW) attn_merge_rows<T, H, 1, ATT_CB1>(a, head, p0, n_pairs, pos0, lane);
         } else {
             for (int p0 = hw * ATT_RB; p0 < n_pairs; p0 += ATT_GW * ATT_RB) attn_merge_rows<T, H>(a, head, p0, n_pairs, pos0, lane);
         }
