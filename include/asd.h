@@ -207,6 +207,15 @@ int asd_load_weights_file(asd_engine* e, const char* path);
  */
 int asd_set_page_table(asd_engine* e, const int32_t* table, int32_t n_pages);
 
+/*
+ * The cache rows of positions pos0 .. pos0 + n - 1 of one layer, as the decode attention reads them (Section 1: the
+ * cache a decoded token reloads): k_out and v_out are HOST arrays [n][n_kv_heads][head_dim] of fp32 (the stored
+ * values widened; K after the rotary embedding), looked up through the page table.  Any position below the cache
+ * capacity may be read, also beyond the current length (a never-written slot reads as 0, a slot left by a rejected
+ * draft holds that draft's values).  Synchronises the stream.  Either output may be NULL.
+ */
+int asd_get_kv(asd_engine* e, int32_t layer, int32_t pos0, int32_t n, float* k_out, float* v_out);
+
 /* Cache length control: reset = truncate to 0; truncate rolls back to new_len <= kv_len. */
 int asd_reset(asd_engine* e);
 int asd_truncate(asd_engine* e, int32_t new_len);

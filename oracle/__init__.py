@@ -68,6 +68,7 @@ def _L():
         L.orc_reset.argtypes = [vp]
         L.orc_truncate.argtypes = [vp, i32]
         L.orc_kv_len.argtypes = [vp]
+        L.orc_get_kv.argtypes = [vp, i32, i32, i32, vp, vp]
         L.orc_forward.argtypes = [vp, vp, i32, i32, vp, i32, vp, vp, vp, vp]
         L.orc_acs.argtypes = [vp, i32, i32, vp]
         L.orc_cosine.restype = ctypes.c_double
@@ -219,6 +220,14 @@ class Oracle:
     @property
     def kv_len(self) -> int:
         return _L().orc_kv_len(self._h)
+
+    def get_kv(self, layer: int, pos0: int, n: int):
+        """(K, V) of positions pos0 .. pos0+n-1 of one layer as the cache holds them: float64 [n, n_kv_heads, head_dim]."""
+        k = np.empty((n, self.shape.n_kv_heads, self.shape.head_dim))
+        v = np.empty_like(k)
+        if _L().orc_get_kv(self._h, layer, pos0, n, k.ctypes.data, v.ctypes.data):
+            raise ValueError("orc_get_kv: bad layer or positions")
+        return k, v
 
     def forward(self, tokens, pos0: int, skip=None, commit: bool = True, want_logits=True, want_hidden=False):
         """Returns dict(logits [n,V], cos_rows [n,2L], cos [2L] mean over rows, argmax [n], hidden [n,d])."""

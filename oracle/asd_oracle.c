@@ -186,6 +186,17 @@ static int weights_complete(const orc_model* M) {
     return 1;
 }
 
+/* The cache rows of positions pos0 .. pos0 + n - 1 of one layer as the model holds them (K after the rotary
+   embedding; in the storage type when kv_storage is set): k_out, v_out [n][n_kv_heads * head_dim], either may be NULL.
+   A read accessor for tests of the KV append step (Section 1: the cache every decoded token reloads). */
+int orc_get_kv(const orc_model* M, int32_t layer, int32_t pos0, int32_t n, double* k_out, double* v_out) {
+    if (!M || layer < 0 || layer >= M->c.n_layers || pos0 < 0 || n < 0 || pos0 + n > M->c.max_seq) return -1;
+    size_t kd = (size_t)M->c.n_kv_heads * M->c.head_dim;
+    if (k_out) memcpy(k_out, M->layer[layer].kc + (size_t)pos0 * kd, (size_t)n * kd * sizeof(double));
+    if (v_out) memcpy(v_out, M->layer[layer].vc + (size_t)pos0 * kd, (size_t)n * kd * sizeof(double));
+    return 0;
+}
+
 void orc_reset(orc_model* M) { M->kv_len = 0; }
 int32_t orc_kv_len(const orc_model* M) { return M->kv_len; }
 int orc_truncate(orc_model* M, int32_t len) {

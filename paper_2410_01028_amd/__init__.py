@@ -87,6 +87,7 @@ def lib():
         L.asd_last_error.argtypes = [vp]
         L.asd_set_weight.argtypes = [vp, i32, i32, vp, sz, i32]
         L.asd_get_weight.argtypes = [vp, i32, i32, vp, sz]
+        L.asd_get_kv.argtypes = [vp, i32, i32, i32, vp, vp]
         L.asd_init_synthetic.argtypes = [vp, ctypes.c_uint64]
         L.asd_load_weights_file.argtypes = [vp, ctypes.c_char_p]
         L.asd_set_page_table.argtypes = [vp, vp, i32]
@@ -219,6 +220,13 @@ class Engine:
     def set_page_table(self, table):
         t = np.ascontiguousarray(table, dtype=np.int32)
         self._ck(lib().asd_set_page_table(self._h, t.ctypes.data, t.size))
+
+    def get_kv(self, layer: int, pos0: int, n: int):
+        """(K, V) of positions pos0 .. pos0+n-1 of one layer: float32 [n, n_kv_heads, head_dim], the stored values widened."""
+        k = np.empty((n, self.cfg.n_kv_heads, self.cfg.head_dim), dtype=np.float32)
+        v = np.empty_like(k)
+        self._ck(lib().asd_get_kv(self._h, layer, pos0, n, k.ctypes.data, v.ctypes.data))
+        return k, v
 
     def reset(self):
         self._ck(lib().asd_reset(self._h))

@@ -66,26 +66,26 @@ template <> __device__ __forceinline__ int score_key<BF16>(int kt, int r) {
 }
 template <> __device__ __forceinline__ int score_key<F32>(int kt, int r) { return 16 * kt + r; }
 // the inverse: score tile and tile row of a chunk's key
-template <class T> __device__ __forceinline__ void score_tile_of(int key, int* kt, int* r);
-template <> __device__ __forceinline__ void score_tile_of<BF16>(int key, int* kt, int* r) {
+template <class T> __host__ __device__ __forceinline__ void score_tile_of(int key, int* kt, int* r);
+template <> __host__ __device__ __forceinline__ void score_tile_of<BF16>(int key, int* kt, int* r) {
     *kt = 2 * (key >> 5) + ((key >> 2) & 1); *r = 4 * ((key >> 3) & 3) + (key & 3);
 }
-template <> __device__ __forceinline__ void score_tile_of<F32>(int key, int* kt, int* r) { *kt = key >> 4; *r = key & 15; }
+template <> __host__ __device__ __forceinline__ void score_tile_of<F32>(int key, int* kt, int* r) { *kt = key >> 4; *r = key & 15; }
 // element offsets inside a block (h = head dim, slot = token slot in the page)
-template <class T> __device__ __forceinline__ size_t kv_chunk_off(int chunk_in_page, int h) { return (size_t)chunk_in_page * 2 * ASD_CHUNK * h; }
-template <class T> __device__ __forceinline__ size_t kv_k_frag_off(int kt, int hs, int h) {      // + lane * KE
+template <class T> __host__ __device__ __forceinline__ size_t kv_chunk_off(int chunk_in_page, int h) { return (size_t)chunk_in_page * 2 * ASD_CHUNK * h; }
+template <class T> __host__ __device__ __forceinline__ size_t kv_k_frag_off(int kt, int hs, int h) {      // + lane * KE
     return (size_t)(kt * (h / (4 * T::KE)) + hs) * 64 * T::KE;
 }
-template <class T> __device__ __forceinline__ size_t kv_v_frag_off(int ht, int ks, int h) {      // + lane * KE
+template <class T> __host__ __device__ __forceinline__ size_t kv_v_frag_off(int ht, int ks, int h) {      // + lane * KE
     return (size_t)ASD_CHUNK * h + (size_t)(ht * (ASD_CHUNK / (4 * T::KE)) + ks) * 64 * T::KE;
 }
-template <class T> __device__ __forceinline__ size_t kv_k_off(int slot, int dim, int h) {
+template <class T> __host__ __device__ __forceinline__ size_t kv_k_off(int slot, int dim, int h) {
     constexpr int KE = T::KE;
     int kt, r;
     score_tile_of<T>(slot % ASD_CHUNK, &kt, &r);
     return kv_chunk_off<T>(slot / ASD_CHUNK, h) + kv_k_frag_off<T>(kt, dim / (4 * KE), h) + (size_t)(((dim / KE) & 3) * 16 + r) * KE + dim % KE;
 }
-template <class T> __device__ __forceinline__ size_t kv_v_off(int slot, int dim, int h) {
+template <class T> __host__ __device__ __forceinline__ size_t kv_v_off(int slot, int dim, int h) {
     constexpr int KE = T::KE;
     const int key = slot % ASD_CHUNK;
     return kv_chunk_off<T>(slot / ASD_CHUNK, h) + kv_v_frag_off<T>(dim >> 4, key / (4 * KE), h) + (size_t)(((key / KE) & 3) * 16 + (dim & 15)) * KE + key % KE;

@@ -1011,6 +1011,49 @@ int asd_get_weight(asd_engine* e, int32_t t, int32_t layer, void* dst, size_t by
     return ASD_OK;
 }
 
+extern "C++" {
+static float widen(uint16_t v) { const uint32_t u = (uint32_t)v << 16; float f; memcpy(&f, &u, 4); return f; }    // bf16 code -> fp32
+static float widen(float v) { return v; }
+template <class T>
+static void untile_kv(const asd_engine* e, const std::vector<char>& block, int slot, float* k_row, float* v_row) {
+    using E = typename T::elem;
+    const int H = e->c.head_dim, PT = e->c.page_tokens, nkv = e->c.n_kv_heads;
+    for (int kvh = 0; kvh < nkv; ++kvh) {
+        const E* B = (const E*)block.data() + (size_t)kvh * 2 * PT * H;
+        for (int d = 0; d < H; ++d) {
+            if (k_row) k_row[kvh * H + d] = widen(B[kv_k_off<T>(slot, d, H)]);
+            if (v_row) v_row[kvh * H + d] = widen(B[kv_v_off<T>(slot, d, H)]);
+        }
+    }
+}
+}   // extern "C++"
+
+int asd_get_kv(asd_engine* e, int32_t layer, int32_t pos0, int32_t n, float* k_out, float* v_out) {
+    if (!e) return ASD_E_INVAL;
+    if (layer < 0 || layer >= e->c.n_layers) return fail(e, ASD_E_INVAL, "layer %d out of range", layer);
+    if (pos0 < 0 || n < 0 || pos0 + n > capacity(e)) return fail(e, ASD_E_INVAL, "positions %d .. %d outside the cache capacity %d", pos0, pos0 + n, capacity(e));
+    const int H = e->c.head_dim, PT = e->c.page_tokens, nkv = e->c.n_kv_heads;
+    const size_t row = (size_t)nkv * H, page_bytes = (size_t)nkv * 2 * PT * H * e->es;
+    CK(e, hipStreamSynchronize(e->stream));
+    std::vector<int32_t> table(e->n_pages);
+    CK(e, hipMemcpy(table.data(), e->page_table, table.size() * 4, hipMemcpyDeviceToHost));
+    std::vector<char> block(page_bytes);
+    int have = -1;
+    for (int i = 0; i < n; ++i) {
+        const int pos = pos0 + i, lp = pos / PT;
+        if (lp != have) {
+            const int page = table[lp];
+            if (page < 0 || page >= e->n_pages) return fail(e, ASD_E_STATE, "page table entry %d is %d", lp, page);
+            CK(e, hipMemcpy(block.data(), e->kv + (size_t)layer * e->kv_layer_bytes + (size_t)page * page_bytes, page_bytes, hipMemcpyDeviceToHost));
+            have = lp;
+        }
+        float* kr = k_out ? k_out + (size_t)i * row : nullptr;
+        float* vr = v_out ? v_out + (size_t)i * row : nullptr;
+        if (e->c.dtype == ASD_DT_BF16) untile_kv<BF16>(e, block, pos % PT, kr, vr); else untile_kv<F32>(e, block, pos % PT, kr, vr);
+    }
+    return ASD_OK;
+}
+
 // host copy of the input generator's stream key and constants (pure integer / one sqrt / one pow)
 static uint64_t h_mix64(uint64_t z) {
     z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;

@@ -281,8 +281,15 @@ def test_cache_in_storage_type_against_matrix_formulation(dtype):
     Z = Y + (G / (1 + np.exp(-G)) * U) @ w[(si.T_WD, 0)].T
     logits = rms(Z, w[(si.T_FINAL_NORM, 0)]) @ w[(si.T_LM_HEAD, 0)].T
 
-    r = make_oracle(s, seed=9, max_seq=16, gain_std=0.2, kv_storage=True).forward(tok, 0, want_hidden=True)
+    orc = make_oracle(s, seed=9, max_seq=16, gain_std=0.2, kv_storage=True)
+    r = orc.forward(tok, 0, want_hidden=True)
     assert np.abs(r["logits"] - logits).max() < 1e-12 and np.abs(r["hidden"] - Z).max() < 1e-13
+    # the cache accessor returns exactly those rounded rows (and zeros where nothing was written)
+    ck, cv = orc.get_kv(0, 0, 16)
+    assert np.abs(ck[:S] - Kr).max() < 1e-15 and np.abs(cv[:S] - Vh).max() < 1e-15
+    assert np.all(ck[S:] == 0) and np.all(cv[S:] == 0)
+    with pytest.raises(ValueError):
+        orc.get_kv(0, 10, 7)
     # and it is a different function from the unrounded cache, by about the storage type's rounding
     r0 = make_oracle(s, seed=9, max_seq=16, gain_std=0.2).forward(tok, 0)
     gap = np.abs(r["logits"] - r0["logits"]).max() / np.abs(r0["logits"]).max()
