@@ -236,7 +236,7 @@ GemmCfg pick_cfg(const asd_config& c, int epi, int cls, int tiles, int KB) {
 // (`test_tiles_per_qkv_workgroup_give_the_same_bits`).  Rule: from QKV_ROWS_MIN rows on, the largest of 3, 2, 1 tiles
 // per workgroup that leaves the busiest compute unit with no more tiles than one tile per workgroup does.
 #define QKV_ROWS_MIN 5
-GemmCfg pick_qkv_rows(const asd_config& c, const GemmCfg& base, int tiles, const char* tune) {
+GemmCfg pick_qkv_rows(const GemmCfg& base, int tiles, const char* tune) {
     GemmCfg g = base;
     int v[4];
     if (tune_entry(tune, "qkv", v, 4) == 4) return g;               // an explicit launch shape holds for every row count
@@ -246,7 +246,6 @@ GemmCfg pick_qkv_rows(const asd_config& c, const GemmCfg& base, int tiles, const
         if (busiest(tn) <= busiest(base.TN)) { g.TN = tn; break; }
     if (tune_entry(tune, "qkv_rows", v, 1) == 1 && v[0] >= 1 && v[0] <= 3) g.TN = v[0];
     g.grid = (tiles + g.TN - 1) / g.TN;
-    (void)c;
     return g;
 }
 
@@ -922,7 +921,7 @@ int asd_create(const asd_config* cfg, void* device_arena, size_t arena_bytes, vo
     e->pf_qkv = pf_pick(tune, "pf_qkv", 4, 1); e->pf_o = pf_pick(tune, "pf_o", 4, 4);
     e->pf_gu = pf_pick(tune, "pf_gu", 4, 1); e->pf_down = pf_pick(tune, "pf_down", 4, 4);
     e->g_qkv = p.g_qkv; e->g_o = p.g_o; e->g_gu = p.g_gu; e->g_down = p.g_down; e->g_lm = p.g_lm;
-    e->g_qkv_rows = pick_qkv_rows(e->c, e->g_qkv, e->qkv_tiles, tune);
+    e->g_qkv_rows = pick_qkv_rows(e->g_qkv, e->qkv_tiles, tune);
     e->att_gh1 = (cfg->debug_flags & ASD_DBG_ATT_GH1) != 0;
     e->sample_mem = (cfg->debug_flags & ASD_DBG_SAMPLE_MEM) != 0;
     e->force_att_w4 = (cfg->debug_flags & ASD_DBG_ATT_W4) != 0;
