@@ -1363,7 +1363,7 @@ static SampleArgs sample_args(asd_engine* e, float temperature, uint64_t seed) {
 }
 
 // The sampling kernels hold a thread's share of a logit row in registers when the vocabulary allows it
-// (ASD_SAMPLE_MEM, a test aid, forces the variant that re-reads memory: same arithmetic, same draws).
+// (ASD_DBG_SAMPLE_MEM, a test aid, forces the variant that re-reads memory: same arithmetic, same draws).
 static bool sample_in_registers(const asd_engine* e) {
     return !e->sample_mem && e->c.vocab <= SAMPLE_SEG * SAMPLE_THREADS;
 }
