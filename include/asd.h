@@ -80,7 +80,7 @@ typedef struct {
  *   ASD_DBG_SAMPLE_MEM  sampling kernels that re-read their logit rows from memory
  * debug_tune: "name=a,b,c,d;..." with name in {qkv, o, gu, down, lm}: tiles per workgroup, waves per
  * workgroup, k-major layout (0/1), interleaved k-blocks (0/1); and name in {pf_qkv, pf_o, pf_gu,
- * pf_down}: 16-row chunks per workgroup, K slices[, prefetch depth] of the prompt-block GEMMs;
+ * pf_down}: 16-row chunks per workgroup, K slices[, prefetch depth[, tiles per wave (pf_qkv: 3..5)]] of the prompt-block GEMMs;
  * "qkv_rows=N": tiles per QKV workgroup in passes of five rows and more (default: by balance).  A
  * layout override changes how weights are tiled in the arena, never their values.  The string is
  * copied by asd_create.

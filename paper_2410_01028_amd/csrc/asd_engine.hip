@@ -51,7 +51,7 @@ hipError_t scratch_ptr(unsigned char** out) {
 }
 
 struct GemmCfg { int TN, NW, grid, kmajor, kint; };
-struct PfCfg { int NC, KS, PD; };      // prompt GEMM: 16-row chunks per workgroup, K slices
+struct PfCfg { int NC, KS, PD, NA; };  // prompt GEMM: 16-row chunks per workgroup, K slices, prefetch depth, tiles per wave (0: by balance)
 
 struct Layer {
     char *wqkv, *wo, *wg, *wu, *wd;
@@ -714,27 +714,53 @@ void destroy_host(asd_engine* e) {
 // Launch shape of a prompt GEMM class: NC 16-row chunks per workgroup and K slices (slices only for the two
 // residual-add GEMMs).  The configuration's debug_tune (development aid) overrides, e.g. "pf_qkv=8,1;pf_o=8,2;pf_gu=4,1;pf_down=8,4".
 PfCfg pf_pick(const char* tune, const char* name, int nc, int ks) {
-    PfCfg g{nc, ks, 2};
-    int v[3] = {0, 0, 1};
-    const int n = tune_entry(tune, name, v, 3);
+    PfCfg g{nc, ks, 2, 0};
+    int v[4] = {0, 0, 1, 0};
+    const int n = tune_entry(tune, name, v, 4);
     if (n >= 2 && (v[0] == 2 || v[0] == 4 || v[0] == 8) && v[1] >= 1 && v[1] <= PF_MAX_KSPLIT && v[2] >= 1 && v[2] <= 4) { g.NC = v[0]; g.KS = v[1]; g.PD = v[2]; }
+    if (n == 4 && v[3] >= 3 && v[3] <= 5) g.NA = v[3];
     return g;
 }
 
 constexpr int PF_NW = 4;                 // waves per workgroup of a prompt GEMM
 template <int EPI> constexpr int pf_na() { return EPI == PF_GU ? 2 : 4; }     // weight tiles per wave (gate and up each, for PF_GU)
 
-template <class T, int EPI> bool launch_pf_gemm_t(hipStream_t s, const PfCfg& g, PfArgs a, int n_chunks) {
-    constexpr int NA = pf_na<EPI>();
+template <class T, int EPI, int NA> bool launch_pf_gemm_na(hipStream_t s, const PfCfg& g, PfArgs a, int n_chunks) {
     a.n_fb = (a.n_tiles + PF_NW * NA - 1) / (PF_NW * NA);
     a.n_rb = (n_chunks + g.NC - 1) / g.NC;
     a.ksplit = EPI == PF_RAW ? g.KS : 1;
     if (a.ksplit > a.KB) a.ksplit = a.KB;
     const unsigned grid = (unsigned)((a.n_fb + 7) / 8 * 8 * a.n_rb * a.ksplit);
 #define PFK(nc, pd) if (g.NC == nc && g.PD == pd) { pf_gemm_kernel<T, EPI, NA, nc, PF_NW, pd><<<grid, PF_NW * 64, 0, s>>>(a); return true; }
-    PFK(2, 1) PFK(4, 1) PFK(8, 1) PFK(2, 2) PFK(4, 2) PFK(8, 2) PFK(2, 3) PFK(4, 3) PFK(2, 4) PFK(4, 4)
+    if constexpr (NA == pf_na<EPI>()) { PFK(2, 1) PFK(4, 1) PFK(8, 1) PFK(2, 2) PFK(4, 2) PFK(8, 2) PFK(2, 3) PFK(4, 3) PFK(2, 4) PFK(4, 4) }
+    else { PFK(4, 2) }
 #undef PFK
     return false;
+}
+// Tiles per wave of the prompt QKV GEMM.  Its workgroups cannot split K (the epilogue rotates and stores whole sums),
+// so their number is feature blocks x row blocks, and with the default 4 tiles per wave that is 384 on the 7B shape:
+// half the compute units hold two workgroups, half one, and the launch lasts as long as two.  Among 4, 3 and 5
+// tiles per wave the one is taken that gives the busiest compute unit the least work (workgroups on it x tiles per
+// wave): 7B 3 tiles (512 workgroups, two everywhere), 13B 4, 70B 5.  Which wave owns a tile does not enter any sum.
+static int pf_qkv_na(const PfCfg& g, int n_tiles, int n_chunks) {
+    if (g.NA) return g.NA;
+    if (g.NC != 4 || g.PD != 2) return 4;
+    const int units = device_units(), n_rb = (n_chunks + g.NC - 1) / g.NC;
+    int best = 4, best_cost = 1 << 30;
+    for (int na : {4, 3, 5}) {
+        const int n_fb = (n_tiles + PF_NW * na - 1) / (PF_NW * na);
+        const int cost = (n_fb * n_rb + units - 1) / units * na;
+        if (cost < best_cost) { best = na; best_cost = cost; }
+    }
+    return best;
+}
+template <class T, int EPI> bool launch_pf_gemm_t(hipStream_t s, const PfCfg& g, PfArgs a, int n_chunks) {
+    if constexpr (EPI == PF_QKV) {
+        const int na = pf_qkv_na(g, a.n_tiles, n_chunks);
+        if (na == 3) return launch_pf_gemm_na<T, EPI, 3>(s, g, a, n_chunks);
+        if (na == 5) return launch_pf_gemm_na<T, EPI, 5>(s, g, a, n_chunks);
+    }
+    return launch_pf_gemm_na<T, EPI, pf_na<EPI>()>(s, g, a, n_chunks);
 }
 template <int EPI> bool launch_pf_gemm(asd_engine* e, const PfCfg& g, const PfArgs& a, int n_chunks) {
     return e->c.dtype == ASD_DT_BF16 ? launch_pf_gemm_t<BF16, EPI>(e->stream, g, a, n_chunks) : launch_pf_gemm_t<F32, EPI>(e->stream, g, a, n_chunks);
